@@ -1,0 +1,165 @@
+"""Float64 CPU oracle of the FAEDKV / IWDFT hot path (arxiv 2507.20030).
+
+TEST INFRASTRUCTURE ONLY.  This module is the slow, plain definition the GPU
+library is checked against.  Only tests, the smoke check and the benchmark's
+``cpu_baseline`` leg may import it; the product package never does, and this
+module imports nothing from the product package.  It shares no code, tables or
+constants with the HIP path.
+
+Everything works on ONE slice (one layer, one sequence, one KV head): ``x`` is a
+``[tokens, channels]`` float64 array, K and V are treated identically.
+
+Notation (paper, Sec. 3.1.2 and Sec. 4.1):
+    M        DFT length = number of tokens transformed at prefill
+    T        number of tokens absorbed so far (T == M right after prefill)
+    W_k      exp(-j 2 pi k / M)                               (Eq. sliding-dft)
+    S_T[k]   normalised coefficient the IWDFT recursion carries (Eq. infi-dft)
+    U_T[k]   T * S_T[k], the un-normalised accumulator
+    B        sorted kept bins of the layer                     (Sec. 3.2, 4.2)
+
+Readings of the paper this oracle fixes (the paper leaves them open):
+  * hand-over prefill -> streaming: the state after prefill is Eq. dft-full
+    divided by M, every later token applies Eq. infi-dft exactly as printed,
+    with N = token count after the append.
+  * reconstruction takes the real part of the masked inverse DFT of the
+    UN-normalised spectrum U_T (gain T/M on S_T), output length M.
+  * tokens beyond M alias onto the M slots (W_k^M = 1).
+Parity unpinned: the choice among those readings (slot map, real part, gain)
+is not fixed by anything the paper prints; every function below is pinned by
+identities in tests/test_oracle_pins.py.
+"""
+from __future__ import annotations
+
+import numpy as np
+
+__all__ = [
+    "W", "prefill", "append", "append_many", "slot", "fold_to_slots",
+    "closed_form", "reconstruct", "attention", "decode_attention",
+    "stream_decode",
+]
+
+
+def W(bins, M):
+    """Twiddle W_k = exp(-j 2 pi k / M) for each kept bin (Eq. sliding-dft)."""
+    k = np.asarray(bins, dtype=np.int64) % M
+    return np.exp(-2j * np.pi * k.astype(np.float64) / float(M))
+
+
+def prefill(x, bins):
+    """Normalised prefill state S_M[k] = (1/M) sum_n x[n] W_k^n, k in B.
+
+    Eq. dft-full applied to the M prefill tokens (Eq. prefill-dft), kept bins
+    only (Eq. freq-zero), divided by M so that Eq. infi-dft can carry it on.
+    x: [M, d] float64.  Returns [|B|, d] complex128.
+    """
+    x = np.asarray(x, dtype=np.float64)
+    M = x.shape[0]
+    bins = np.asarray(bins, dtype=np.int64)
+    return np.fft.fft(x, axis=0)[bins] / M
+
+
+def append(S, x_new, T, bins, M):
+    """One IWDFT update, Eq. infi-dft, literally.
+
+    S: state after T tokens, [|B|, d] complex.  x_new: [d], token number T
+    (0-based).  N = T + 1 is the sequence length after the append.
+    Returns S_{T+1} = W_k * ((N-1)/N * S_T + x_new / N).
+    """
+    N = float(T + 1)
+    w = W(bins, M)[:, None]
+    x_new = np.asarray(x_new, dtype=np.float64)
+    return w * (((N - 1.0) / N) * S + x_new[None, :] / N)
+
+
+def append_many(S, xs, T, bins, M):
+    """Apply `append` for every row of xs in order. Returns (S, T)."""
+    for row in np.asarray(xs, dtype=np.float64):
+        S = append(S, row, T, bins, M)
+        T += 1
+    return S, T
+
+
+def slot(n, T, M):
+    """Time slot (0..M-1) token n occupies once T tokens have been absorbed.
+
+    Follows from unrolling Eq. infi-dft from the Eq. dft-full prefill state:
+    each update multiplies the whole state by W_k (one slot later) and the new
+    token enters with a single factor W_k (slot 1).
+    """
+    n = np.asarray(n, dtype=np.int64)
+    return np.where(n < M, (n + (T - M)) % M, (T - n) % M)
+
+
+def fold_to_slots(xs, M):
+    """y[a] = sum of all tokens currently sitting in slot a.  xs: [T, d]."""
+    xs = np.asarray(xs, dtype=np.float64)
+    T = xs.shape[0]
+    y = np.zeros((M, xs.shape[1]), dtype=np.float64)
+    np.add.at(y, slot(np.arange(T), T, M), xs)
+    return y
+
+
+def closed_form(xs, M, bins):
+    """From-scratch recompute of S_T from all T >= M tokens seen so far.
+
+    U_T[k] = sum_a y[a] W_k^a with y = fold_to_slots(xs), S_T = U_T / T:
+    every token enters with weight exactly 1/T.
+    """
+    xs = np.asarray(xs, dtype=np.float64)
+    T = xs.shape[0]
+    assert T >= M
+    bins = np.asarray(bins, dtype=np.int64)
+    return np.fft.fft(fold_to_slots(xs, M), axis=0)[bins] / T
+
+
+def reconstruct(S, T, M, bins, weights=None):
+    """Time-domain reconstruction, Eq. inverse-swdft on the masked spectrum.
+
+    x~[a] = (1/M) Re sum_{k in B} w_k U_T[k] exp(+j 2 pi k a / M), U_T = T S_T,
+    a = 0..M-1.  Returns [M, d] float64.
+    """
+    bins = np.asarray(bins, dtype=np.int64)
+    w = np.ones(len(bins)) if weights is None else np.asarray(weights, np.float64)
+    full = np.zeros((M, S.shape[1]), dtype=np.complex128)
+    full[bins] = (w[:, None] * float(T)) * S
+    return np.fft.ifft(full, axis=0).real
+
+
+def attention(q, K, V, scale=None):
+    """Softmax attention of Eq. kv-attn for a group of query heads.
+
+    q: [G, d]; K, V: [n, d].  o = softmax(q K^T * scale) V, scale = 1/sqrt(d).
+    """
+    q = np.asarray(q, dtype=np.float64)
+    d = q.shape[-1]
+    if scale is None or scale <= 0:
+        scale = 1.0 / np.sqrt(d)
+    logits = (q @ K.T) * scale
+    logits = logits - logits.max(axis=-1, keepdims=True)
+    p = np.exp(logits)
+    p /= p.sum(axis=-1, keepdims=True)
+    return p @ V
+
+
+def decode_attention(q, SK, SV, T, M, bins, weights=None, scale=None):
+    """Attention over the reconstructed segment (Eq. kv-concat with S = R = 0)."""
+    Kt = reconstruct(SK, T, M, bins, weights)
+    Vt = reconstruct(SV, T, M, bins, weights)
+    return attention(q, Kt, Vt, scale)
+
+
+def stream_decode(K0, V0, bins, k_new, v_new, q_new, weights=None, scale=None):
+    """Prefill, then per step: append (k_i, v_i), attend with q_i.
+
+    K0, V0: [M, d]; k_new, v_new: [steps, d]; q_new: [steps, G, d].
+    Returns (outs [steps, G, d], SK, SV, T).
+    """
+    M = K0.shape[0]
+    SK, SV, T = prefill(K0, bins), prefill(V0, bins), M
+    outs = []
+    for i in range(len(k_new)):
+        SK = append(SK, k_new[i], T, bins, M)
+        SV = append(SV, v_new[i], T, bins, M)
+        T += 1
+        outs.append(decode_attention(q_new[i], SK, SV, T, M, bins, weights, scale))
+    return np.stack(outs) if outs else np.zeros((0,) + q_new.shape[1:]), SK, SV, T

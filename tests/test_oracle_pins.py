@@ -1,0 +1,277 @@
+"""Pins for the float64 oracle: every function is checked against something
+other than itself -- brute-force sums written out here with cmath, textbook
+closed forms, exact inversion, library routines, invariants.  CPU only.
+"""
+import cmath
+import math
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import iwdft_oracle as orc
+
+
+def rng(seed):
+    return np.random.default_rng(seed)
+
+
+# ---------------------------------------------------------------- brute force
+def brute_prefill(x, bins):
+    """(1/M) sum_n x[n] exp(-j 2 pi k n / M), plain loops (Eq. dft-full)."""
+    M, d = len(x), len(x[0])
+    out = [[0j] * d for _ in bins]
+    for i, k in enumerate(bins):
+        for c in range(d):
+            acc = 0j
+            for n in range(M):
+                acc += x[n][c] * cmath.exp(-2j * math.pi * k * n / M)
+            out[i][c] = acc / M
+    return np.array(out)
+
+
+def brute_stream(xs, M, bins):
+    """Eq. infi-dft run token by token with Python complex scalars."""
+    d = len(xs[0])
+    S = brute_prefill([list(r) for r in xs[:M]], bins)
+    S = [[complex(S[i][c]) for c in range(d)] for i in range(len(bins))]
+    T = M
+    for row in xs[M:]:
+        N = T + 1
+        for i, k in enumerate(bins):
+            wk = cmath.exp(-2j * math.pi * k / M)
+            for c in range(d):
+                S[i][c] = wk * ((N - 1) / N * S[i][c] + row[c] / N)
+        T = N
+    return np.array(S), T
+
+
+def brute_reconstruct(S, T, M, bins, weights=None):
+    d = S.shape[1]
+    out = np.zeros((M, d))
+    for a in range(M):
+        for c in range(d):
+            acc = 0j
+            for i, k in enumerate(bins):
+                w = 1.0 if weights is None else weights[i]
+                acc += w * T * S[i, c] * cmath.exp(2j * math.pi * k * a / M)
+            out[a, c] = (acc / M).real
+    return out
+
+
+# -------------------------------------------------------------------- prefill
+@pytest.mark.parametrize("M,bins", [(8, [0, 1, 2, 7]), (12, [0, 3, 5, 6, 11]), (16, list(range(16)))])
+def test_prefill_matches_brute_force(M, bins):
+    x = rng(1).normal(size=(M, 3))
+    np.testing.assert_allclose(orc.prefill(x, bins), brute_prefill(x.tolist(), bins), atol=1e-13)
+
+
+def test_prefill_textbook_cases():
+    M, bins = 32, np.arange(32)
+    const = np.full((M, 1), 2.5)
+    S = orc.prefill(const, bins)[:, 0]
+    assert abs(S[0] - 2.5) < 1e-14 and np.abs(S[1:]).max() < 1e-14
+    n0 = 5
+    imp = np.zeros((M, 1)); imp[n0] = 1.0
+    np.testing.assert_allclose(orc.prefill(imp, bins)[:, 0],
+                               np.exp(-2j * np.pi * bins * n0 / M) / M, atol=1e-15)
+    k0 = 3
+    cosx = np.cos(2 * np.pi * k0 * np.arange(M) / M)[:, None]
+    S = orc.prefill(cosx, bins)[:, 0]
+    expect = np.zeros(M, complex); expect[k0] = expect[M - k0] = 0.5
+    np.testing.assert_allclose(S, expect, atol=1e-14)
+    # a sine has a purely imaginary coefficient of sign -j/2 at +k0 (fixes the sign of W_k)
+    sinx = np.sin(2 * np.pi * k0 * np.arange(M) / M)[:, None]
+    S = orc.prefill(sinx, bins)[:, 0]
+    assert abs(S[k0] - (-0.5j)) < 1e-14 and abs(S[M - k0] - 0.5j) < 1e-14
+
+
+def test_prefill_keeps_only_requested_bins_in_order():
+    x = rng(2).normal(size=(16, 2))
+    full = orc.prefill(x, np.arange(16))
+    bins = [1, 4, 9, 15]
+    np.testing.assert_array_equal(orc.prefill(x, bins), full[bins])
+
+
+# ------------------------------------------------------------------ streaming
+@pytest.mark.parametrize("M,extra", [(8, 1), (8, 5), (8, 8), (8, 27), (12, 30)])
+def test_recursion_matches_brute_and_closed_form(M, extra):
+    bins = sorted(rng(3).choice(M, size=M // 2 + 1, replace=False).tolist())
+    xs = rng(4).normal(size=(M + extra, 2))
+    S, T = orc.append_many(orc.prefill(xs[:M], bins), xs[M:], M, bins, M)
+    Sb, Tb = brute_stream(xs.tolist(), M, bins)
+    assert T == Tb == M + extra
+    np.testing.assert_allclose(S, Sb, atol=1e-13)
+    np.testing.assert_allclose(S, orc.closed_form(xs, M, bins), atol=1e-12)
+
+
+def test_closed_form_is_the_explicit_slot_sum():
+    M, T = 8, 21
+    bins = [0, 1, 3, 6]
+    xs = rng(5).normal(size=(T, 2))
+    # U_T[k] = sum_n x[n] W_k^{e(n)}, e = n+T-M for prefill tokens, T-n after
+    U = np.zeros((len(bins), 2), complex)
+    for n in range(T):
+        e = n + T - M if n < M else T - n
+        for i, k in enumerate(bins):
+            U[i] += xs[n] * cmath.exp(-2j * math.pi * k * e / M)
+    np.testing.assert_allclose(orc.closed_form(xs, M, bins), U / T, atol=1e-13)
+    assert list(orc.slot(np.arange(T), T, M)) == [
+        (n + T - M) % M if n < M else (T - n) % M for n in range(T)]
+
+
+def test_dc_bin_is_running_mean():
+    M = 16
+    xs = rng(6).normal(size=(M + 40, 3))
+    S, T = orc.append_many(orc.prefill(xs[:M], [0, 5]), xs[M:], M, [0, 5], M)
+    np.testing.assert_allclose(S[0], xs.mean(axis=0), atol=1e-13)
+
+
+def test_every_token_has_weight_one_over_T():
+    # perturbing any single token by delta moves |S_T[k]| by exactly delta/T
+    M, T, bins = 8, 19, [1, 2, 5]
+    xs = rng(7).normal(size=(T, 1))
+    base = orc.closed_form(xs, M, bins)
+    for n in (0, 3, 7, 8, 13, 18):
+        ys = xs.copy(); ys[n] += 1.0
+        S, _ = orc.append_many(orc.prefill(ys[:M], bins), ys[M:], M, bins, M)
+        np.testing.assert_allclose(np.abs(S - base), 1.0 / T, atol=1e-13)
+
+
+def test_linearity():
+    M, bins = 8, [0, 2, 3]
+    xa, xb = rng(8).normal(size=(M + 9, 2)), rng(9).normal(size=(M + 9, 2))
+    f = lambda x: orc.append_many(orc.prefill(x[:M], bins), x[M:], M, bins, M)[0]
+    np.testing.assert_allclose(f(2.0 * xa - 0.75 * xb), 2.0 * f(xa) - 0.75 * f(xb), atol=1e-13)
+
+
+@pytest.mark.parametrize("j,i", [(0, 0), (2, 3), (1, 11)])
+def test_appended_impulse_lands_in_slot_i_plus_one(j, i):
+    M, bins = 8, np.arange(8)
+    zeros = np.zeros((M, 1))
+    S, T = orc.prefill(zeros, bins), M
+    S, T = orc.append_many(S, np.zeros((j, 1)), T, bins, M)
+    S, T = orc.append_many(S, np.ones((1, 1)), T, bins, M)
+    S, T = orc.append_many(S, np.zeros((i, 1)), T, bins, M)
+    np.testing.assert_allclose(S[:, 0], np.exp(-2j * np.pi * bins * (i + 1) / M) / T, atol=1e-14)
+
+
+# ------------------------------------------------------------- reconstruction
+def test_reconstruct_matches_brute_force():
+    M, bins = 8, [0, 1, 3, 6]
+    xs = rng(10).normal(size=(M + 3, 2))
+    S, T = orc.append_many(orc.prefill(xs[:M], bins), xs[M:], M, bins, M)
+    w = [1.0, 2.0, 0.5, 1.5]
+    np.testing.assert_allclose(orc.reconstruct(S, T, M, bins), brute_reconstruct(S, T, M, bins), atol=1e-13)
+    np.testing.assert_allclose(orc.reconstruct(S, T, M, bins, w), brute_reconstruct(S, T, M, bins, w), atol=1e-13)
+
+
+def test_all_bins_exact_inverse_at_prefill():
+    x = rng(11).normal(size=(32, 4))
+    bins = np.arange(32)
+    np.testing.assert_allclose(orc.reconstruct(orc.prefill(x, bins), 32, 32, bins), x, atol=1e-13)
+
+
+def test_all_bins_after_appends_gives_folded_sums():
+    M, T = 8, 8 + 13
+    xs = rng(12).normal(size=(T, 2))
+    bins = np.arange(M)
+    S, _ = orc.append_many(orc.prefill(xs[:M], bins), xs[M:], M, bins, M)
+    expect = np.zeros((M, 2))
+    for n in range(T):
+        a = (n + T - M) % M if n < M else (T - n) % M
+        expect[a] += xs[n]
+    np.testing.assert_allclose(orc.reconstruct(S, T, M, bins), expect, atol=1e-12)
+
+
+def test_hermitian_closed_mask_is_a_projection():
+    M = 16
+    bins = [0, 1, 2, 5, 8, 11, 14, 15]           # closed under k -> M-k
+    x = rng(13).normal(size=(M, 2))
+    S = orc.prefill(x, bins)
+    np.testing.assert_allclose(orc.prefill(orc.reconstruct(S, M, M, bins), bins), S, atol=1e-14)
+
+
+def test_unmirrored_bin_reconstructs_at_half_amplitude():
+    M, k0 = 16, 3
+    x = np.cos(2 * np.pi * k0 * np.arange(M) / M)[:, None]
+    np.testing.assert_allclose(orc.reconstruct(orc.prefill(x, [k0]), M, M, [k0]), 0.5 * x, atol=1e-14)
+
+
+def test_one_sided_weights_give_exact_inverse():
+    M = 16
+    bins = np.arange(M // 2 + 1)
+    w = np.where((bins == 0) | (bins == M // 2), 1.0, 2.0)
+    x = rng(14).normal(size=(M, 3))
+    np.testing.assert_allclose(orc.reconstruct(orc.prefill(x, bins), M, M, bins, w), x, atol=1e-13)
+
+
+# ------------------------------------------------------------------ attention
+def test_attention_matches_library_sdpa():
+    q, K, V = rng(15).normal(size=(4, 16)), rng(16).normal(size=(40, 16)), rng(17).normal(size=(40, 16))
+    ref = torch.nn.functional.scaled_dot_product_attention(
+        torch.from_numpy(q)[None], torch.from_numpy(K)[None], torch.from_numpy(V)[None])[0].numpy()
+    np.testing.assert_allclose(orc.attention(q, K, V), ref, atol=1e-12)
+    np.testing.assert_allclose(orc.attention(q, K, V, 0.3),
+                               torch.softmax(torch.from_numpy(q @ K.T * 0.3), -1).numpy() @ V, atol=1e-12)
+
+
+def test_attention_large_logits_do_not_overflow():
+    q, K, V = np.full((1, 4), 300.0), rng(18).normal(size=(6, 4)), rng(19).normal(size=(6, 4))
+    assert np.isfinite(orc.attention(q, K, V)).all()
+
+
+def test_decode_attention_all_bins_equals_full_attention():
+    M, d = 32, 8
+    K, V, q = rng(20).normal(size=(M, d)), rng(21).normal(size=(M, d)), rng(22).normal(size=(2, d))
+    bins = np.arange(M)
+    o = orc.decode_attention(q, orc.prefill(K, bins), orc.prefill(V, bins), M, M, bins)
+    np.testing.assert_allclose(o, orc.attention(q, K, V), atol=1e-12)
+
+
+def test_decode_attention_shift_invariance_and_dc_only():
+    M, d = 16, 4
+    K, V, q = rng(23).normal(size=(M, d)), rng(24).normal(size=(M, d)), rng(25).normal(size=(3, d))
+    bins = [0, 1, 2, 14, 15]
+    a = orc.decode_attention(q, orc.prefill(K, bins), orc.prefill(V, bins), M, M, bins)
+    Kr, Vr = np.roll(K, 5, axis=0), np.roll(V, 5, axis=0)
+    b = orc.decode_attention(q, orc.prefill(Kr, bins), orc.prefill(Vr, bins), M, M, bins)
+    np.testing.assert_allclose(a, b, atol=1e-13)
+    o = orc.decode_attention(q, orc.prefill(K, [0]), orc.prefill(V, [0]), M, M, [0])
+    np.testing.assert_allclose(o, np.broadcast_to(V.mean(axis=0), o.shape), atol=1e-13)
+
+
+def test_fast_path_identities():
+    """Identities a kernel may use instead of materialising K~ and V~."""
+    M, d, G = 16, 4, 2
+    bins = np.array([0, 1, 3, 9, 15]); w = np.array([1.0, 2.0, 1.0, 0.5, 1.0])
+    xs = rng(26).normal(size=(M + 5, d)); vs = rng(27).normal(size=(M + 5, d))
+    q = rng(28).normal(size=(G, d))
+    SK, T = orc.append_many(orc.prefill(xs[:M], bins), xs[M:], M, bins, M)
+    SV, _ = orc.append_many(orc.prefill(vs[:M], bins), vs[M:], M, bins, M)
+    Kt, Vt = orc.reconstruct(SK, T, M, bins, w), orc.reconstruct(SV, T, M, bins, w)
+    theta = 2 * np.pi * np.outer(bins, np.arange(M)) / M          # [k, a]
+    qc = SK @ q.T                                                  # [k, G]
+    scores = (T / M) * np.einsum("k,kg,ka->ga", w, qc, np.exp(1j * theta)).real
+    np.testing.assert_allclose(scores, q @ Kt.T, atol=1e-12)
+    p = rng(29).random(size=(G, M))
+    P = p @ np.exp(-1j * theta).T                                  # [G, k]
+    o = (T / M) * np.einsum("k,kd,gk->gd", w, SV, np.conj(P)).real
+    np.testing.assert_allclose(o, p @ Vt, atol=1e-12)
+
+
+def test_stream_decode_order_append_then_attend():
+    M, d, steps = 8, 4, 3
+    bins = [0, 1, 2, 7]
+    r = rng(30)
+    K0, V0 = r.normal(size=(M, d)), r.normal(size=(M, d))
+    kn, vn, qn = r.normal(size=(steps, d)), r.normal(size=(steps, d)), r.normal(size=(steps, 2, d))
+    outs, SK, SV, T = orc.stream_decode(K0, V0, bins, kn, vn, qn)
+    assert T == M + steps
+    allK, allV = np.vstack([K0, kn]), np.vstack([V0, vn])
+    np.testing.assert_allclose(SK, orc.closed_form(allK, M, bins), atol=1e-13)
+    last = orc.decode_attention(qn[-1], orc.closed_form(allK, M, bins), orc.closed_form(allV, M, bins), T, M, bins)
+    np.testing.assert_allclose(outs[-1], last, atol=1e-12)
+    first = orc.decode_attention(qn[0], orc.closed_form(allK[:M + 1], M, bins),
+                                 orc.closed_form(allV[:M + 1], M, bins), M + 1, M, bins)
+    np.testing.assert_allclose(outs[0], first, atol=1e-12)
