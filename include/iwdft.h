@@ -1,0 +1,146 @@
+/*
+ * libiwdft -- the Infinite-Window DFT (IWDFT) K/V-cache hot path of FAEDKV
+ * (arxiv 2507.20030) for AMD MI355X (gfx950).  C ABI, plain pointers and sizes.
+ *
+ * One *slice* is one (layer, sequence, KV head).  Along the token axis every
+ * channel of K and of V is a real signal x[n].  With M the DFT length fixed at
+ * prefill, T the number of tokens absorbed so far and W_k = exp(-j 2 pi k / M),
+ * the library keeps, for every kept bin k of the layer, the coefficient
+ *
+ *     S_T[k] = (1/T) * U_T[k],
+ *     U_M[k]     = sum_{n<M} x[n] W_k^n                  (Sec. 3.1.2, Eq. dft-full;
+ *                                                        Sec. 4.2.1, Eq. prefill-dft)
+ *     S_{T+1}[k] = W_k ( T/(T+1) S_T[k] + x_T/(T+1) )    (Sec. 4.1, Eq. infi-dft)
+ *
+ * so every token ever seen contributes with weight exactly 1/T.  Only kept
+ * bins are computed or stored (Sec. 3.2 Eq. freq-zero; Sec. 4.2.2 "Updating
+ * Cache").  The state is reconstructed with the inverse DFT over the kept bins
+ * (Sec. 3.1.2 Eq. inverse-swdft; Sec. 4.2.2 Eq. reconstruct-idft) and consumed
+ * by softmax attention (Sec. 3.1.1 Eq. kv-attn; Sec. 4.2.2 Eq. kv-concat, middle
+ * segment).
+ *
+ * Memory: every d_* pointer is DEVICE memory owned by the caller; the library
+ * never allocates or frees device memory.  Pointers inside iwdft_desc are HOST
+ * memory and are copied by iwdft_create.  Hot calls (prefill, append,
+ * reconstruct, attention, export) only enqueue kernels on the given HIP stream
+ * (a hipStream_t passed as void*, NULL = default stream) and never synchronise;
+ * T advances when the call is enqueued.  Calls on one context from several host
+ * threads, or on different streams without caller-side ordering, race.
+ *
+ * Errors: every call returns IWDFT_OK or a negative code, validates all
+ * arguments before launching anything, and never throws or aborts.
+ * iwdft_last_error() returns a thread-local description of the last failure.
+ *
+ * Dtypes: K, V, appended tokens, queries, attention output and reconstruction
+ * output share desc.kv_dtype (fp32 or bf16, round-to-nearest-even on output);
+ * coefficients are complex fp32 and all arithmetic accumulates in fp32.
+ */
+#ifndef IWDFT_H_
+#define IWDFT_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct iwdft_ctx iwdft_ctx; /* opaque, host memory, owned by the library */
+
+enum {
+  IWDFT_OK = 0,
+  IWDFT_ERR_ARG = -1,         /* null pointer, non-positive dimension, bad dtype ...   */
+  IWDFT_ERR_BINS = -2,        /* bins not strictly increasing / out of [0,M) / empty   */
+  IWDFT_ERR_SIZE = -3,        /* state or workspace buffer smaller than queried        */
+  IWDFT_ERR_STATE = -4,       /* call out of order (e.g. append before prefill)        */
+  IWDFT_ERR_HIP = -5,         /* a HIP runtime call or kernel launch failed            */
+  IWDFT_ERR_UNSUPPORTED = -6  /* valid request this build has no kernel for            */
+};
+
+enum { IWDFT_F32 = 0, IWDFT_BF16 = 1 };
+
+/* desc.flags */
+enum {
+  IWDFT_FLAG_DIRECT_SYNTHESIS = 1u /* decode attention evaluates the O(M*|B|) sums
+                                      directly instead of through FFTs (always used
+                                      when M is not a power of two)               */
+};
+
+typedef struct {
+  int32_t n_layers;
+  int32_t batch;
+  int32_t n_kv_heads;
+  int32_t n_q_heads;          /* multiple of n_kv_heads; query head hq reads KV head
+                                 hq / (n_q_heads / n_kv_heads)                      */
+  int32_t head_dim;           /* this build: 128                                    */
+  int32_t kv_dtype;           /* IWDFT_F32 or IWDFT_BF16                            */
+  int64_t M;                  /* DFT length = tokens given to iwdft_prefill,
+                                 1 <= M <= 2^30                                     */
+  const int64_t* bin_offsets; /* HOST [n_layers+1], bin_offsets[0] = 0; layer l keeps
+                                 bins[bin_offsets[l] .. bin_offsets[l+1])           */
+  const int32_t* bins;        /* HOST, per layer strictly increasing, each in [0,M) */
+  const float* bin_weights;   /* HOST, same indexing as bins, or NULL (= all 1).
+                                 w_k multiplies bin k in every inverse transform;
+                                 w = 2 for 0 < k < M/2 with bins <= M/2 gives the
+                                 one-sided (real-signal) synthesis                  */
+  uint32_t flags;
+  uint32_t reserved;          /* must be 0 */
+} iwdft_desc;
+
+/* Sizes of the two caller-provided device buffers for this descriptor. */
+int iwdft_query_bytes(const iwdft_desc* desc, size_t* state_bytes, size_t* workspace_bytes);
+
+/* Validates desc, copies the bin lists into d_state and zeroes the coefficients
+ * (synchronous; not a hot call).  Both buffers must be 256-byte aligned and stay
+ * alive and untouched by the caller until iwdft_destroy.  The HIP device that is
+ * current at this call owns the context. */
+int iwdft_create(const iwdft_desc* desc, void* d_state, size_t state_bytes, void* d_workspace,
+                 size_t workspace_bytes, iwdft_ctx** out);
+
+int iwdft_destroy(iwdft_ctx* ctx); /* frees host memory only; NULL is accepted */
+
+/* Prefill transform (Eq. dft-full at the kept bins, Eq. prefill-dft, Eq. freq-zero).
+ * d_K, d_V: [n_layers][batch][n_kv_heads][M][head_dim] contiguous, kv_dtype.
+ * Overwrites the state; T becomes M. */
+int iwdft_prefill(iwdft_ctx* ctx, const void* d_K, const void* d_V, void* hip_stream);
+
+/* Streaming update with one new token per sequence (Eq. infi-dft, Eq. update-iwdft).
+ * d_tok_k, d_tok_v: [n_layers][batch][n_kv_heads][head_dim], kv_dtype.  T -> T+1.
+ * Requires a prior prefill (IWDFT_ERR_STATE otherwise). */
+int iwdft_append(iwdft_ctx* ctx, const void* d_tok_k, const void* d_tok_v, void* hip_stream);
+
+/* Reconstruction of time slots a0 .. a0+n_slots-1 of one layer (Eq. inverse-swdft over
+ * the kept bins, real part, gain T/M on S_T; Eq. reconstruct-idft):
+ *   x~[a] = (1/M) Re sum_{k in B} w_k T S_T[k] exp(+j 2 pi k a / M).
+ * d_Kt, d_Vt: [batch][n_kv_heads][n_slots][head_dim], kv_dtype; either may be NULL.
+ * 0 <= a0, a0 + n_slots <= M. */
+int iwdft_reconstruct(iwdft_ctx* ctx, int32_t layer, int64_t a0, int64_t n_slots, void* d_Kt,
+                      void* d_Vt, void* hip_stream);
+
+/* Decode attention over the M reconstructed slots of every layer (Eq. kv-attn applied to
+ * the reconstructed segment of Eq. kv-concat): o = softmax(q K~^T * scale) V~ without
+ * writing K~, V~ to memory.  d_q, d_out: [n_layers][batch][n_q_heads][head_dim], kv_dtype.
+ * scale <= 0 selects 1/sqrt(head_dim). */
+int compressed_decode_attn(iwdft_ctx* ctx, const void* d_q, void* d_out, float scale,
+                           void* hip_stream);
+
+/* The paper-convention coefficients S_T of one layer, for inspection and parity:
+ * d_SK, d_SV: [batch][n_kv_heads][|B_layer|][head_dim][2] (re, im) fp32; either may be NULL. */
+int iwdft_export_coeffs(iwdft_ctx* ctx, int32_t layer, float* d_SK, float* d_SV,
+                        void* hip_stream);
+
+/* Device copy of the kept bins of one layer, int32 [|B_layer|] (for bit-exact mask checks). */
+int iwdft_export_bins(iwdft_ctx* ctx, int32_t layer, int32_t* d_bins, void* hip_stream);
+
+int64_t iwdft_num_tokens(const iwdft_ctx* ctx); /* T; 0 before prefill; -1 if ctx is NULL */
+
+/* Sets T after the caller restored a saved copy of the state buffer (checkpoint / resume).
+ * T >= M. */
+int iwdft_set_num_tokens(iwdft_ctx* ctx, int64_t T);
+
+const char* iwdft_last_error(void); /* thread-local, static storage, never NULL */
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* IWDFT_H_ */

@@ -1,0 +1,333 @@
+// C ABI of libiwdft: descriptor validation, buffer layout, call ordering, error reporting.
+// All arithmetic lives in the kernels; this file only decides what to launch.
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <new>
+#include <vector>
+
+#include "../../include/iwdft.h"
+#include "common.h"
+
+using namespace iwdft;
+
+namespace {
+
+thread_local char g_err[512] = "";
+
+int fail(int code, const char* fmt, ...) {
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(g_err, sizeof(g_err), fmt, ap);
+  va_end(ap);
+  return code;
+}
+
+size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
+
+struct Plan {  // byte offsets inside the two caller buffers, derived from a descriptor
+  std::vector<LayerInfo> layers;
+  int64_t n_bins_total = 0;
+  int64_t coef_total = 0;  // float2 per tensor
+  int64_t ws_total = 0;    // float2 per workspace array
+  int32_t G = 1, max_nb = 0, max_Bp = 0;
+  bool use_fft = false;
+  size_t off_layers = 0, off_bins = 0, off_weights = 0, off_FK = 0, off_FV = 0, state_bytes = 0;
+  size_t off_qc = 0, off_Pn = 0, off_direct = 0, ws_bytes = 0;
+};
+
+// Largest problem the FFT attention kernel keeps in registers / LDS.
+constexpr int kFftMaxBins = 4096;
+constexpr uint32_t kFftMinM = 256;
+
+int make_plan(const iwdft_desc* d, Plan* pl) {
+  if (!d) return fail(IWDFT_ERR_ARG, "desc is NULL");
+  if (d->n_layers <= 0 || d->batch <= 0 || d->n_kv_heads <= 0 || d->n_q_heads <= 0)
+    return fail(IWDFT_ERR_ARG, "n_layers, batch, n_kv_heads, n_q_heads must be positive");
+  if (d->n_q_heads % d->n_kv_heads != 0)
+    return fail(IWDFT_ERR_ARG, "n_q_heads (%d) is not a multiple of n_kv_heads (%d)", d->n_q_heads,
+                d->n_kv_heads);
+  if (d->kv_dtype != IWDFT_F32 && d->kv_dtype != IWDFT_BF16)
+    return fail(IWDFT_ERR_ARG, "kv_dtype %d is neither IWDFT_F32 nor IWDFT_BF16", d->kv_dtype);
+  if (d->reserved != 0) return fail(IWDFT_ERR_ARG, "reserved must be 0");
+  if (d->flags & ~(uint32_t)IWDFT_FLAG_DIRECT_SYNTHESIS)
+    return fail(IWDFT_ERR_ARG, "unknown bits in flags: 0x%x", d->flags);
+  if (d->M < 1 || d->M > ((int64_t)1 << 30))
+    return fail(IWDFT_ERR_ARG, "M = %lld outside [1, 2^30]", (long long)d->M);
+  if (d->head_dim <= 0) return fail(IWDFT_ERR_ARG, "head_dim must be positive");
+  if (d->head_dim != kHeadDim)
+    return fail(IWDFT_ERR_UNSUPPORTED, "head_dim %d: this build has kernels for head_dim 128 only",
+                d->head_dim);
+  pl->G = d->n_q_heads / d->n_kv_heads;
+  if (pl->G > 64) return fail(IWDFT_ERR_UNSUPPORTED, "more than 64 query heads per KV head");
+  if ((int64_t)d->n_layers * d->batch * d->n_kv_heads > ((int64_t)1 << 24))
+    return fail(IWDFT_ERR_UNSUPPORTED, "more than 2^24 slices");
+  if (!d->bin_offsets || !d->bins) return fail(IWDFT_ERR_ARG, "bin_offsets / bins is NULL");
+  if (d->bin_offsets[0] != 0) return fail(IWDFT_ERR_BINS, "bin_offsets[0] must be 0");
+
+  const int64_t slices_per_layer = (int64_t)d->batch * d->n_kv_heads;
+  pl->layers.resize(d->n_layers);
+  int64_t coef = 0, ws = 0;
+  for (int l = 0; l < d->n_layers; ++l) {
+    int64_t b0 = d->bin_offsets[l], b1 = d->bin_offsets[l + 1];
+    if (b1 <= b0) return fail(IWDFT_ERR_BINS, "layer %d keeps no bins (or offsets decrease)", l);
+    if (b1 - b0 > d->M) return fail(IWDFT_ERR_BINS, "layer %d keeps more than M bins", l);
+    if (b1 > ((int64_t)1 << 30)) return fail(IWDFT_ERR_UNSUPPORTED, "more than 2^30 bins in total");
+    int64_t prev = -1;
+    for (int64_t i = b0; i < b1; ++i) {
+      int64_t k = d->bins[i];
+      if (k < 0 || k >= d->M)
+        return fail(IWDFT_ERR_BINS, "layer %d: bin %lld outside [0, M)", l, (long long)k);
+      if (k <= prev)
+        return fail(IWDFT_ERR_BINS, "layer %d: bins not strictly increasing at entry %lld", l,
+                    (long long)(i - b0));
+      prev = k;
+      if (d->bin_weights && !std::isfinite(d->bin_weights[i]))
+        return fail(IWDFT_ERR_BINS, "layer %d: non-finite bin weight", l);
+    }
+    LayerInfo& L = pl->layers[l];
+    L.bin_off = (int32_t)b0;
+    L.nb = (int32_t)(b1 - b0);
+    L.Bp = (L.nb + kRowPad - 1) / kRowPad * kRowPad;
+    L.pad_ = 0;
+    L.coef_off = coef;
+    L.ws_off = ws;
+    coef += slices_per_layer * kHeadDim * L.Bp;
+    ws += slices_per_layer * pl->G * L.Bp;
+    if (L.nb > pl->max_nb) pl->max_nb = L.nb;
+    if (L.Bp > pl->max_Bp) pl->max_Bp = L.Bp;
+  }
+  pl->n_bins_total = d->bin_offsets[d->n_layers];
+  pl->coef_total = coef;
+  pl->ws_total = ws;
+
+  const bool pow2 = (d->M & (d->M - 1)) == 0;
+  pl->use_fft = pow2 && (uint64_t)d->M >= kFftMinM && pl->max_nb <= kFftMaxBins &&
+                !(d->flags & IWDFT_FLAG_DIRECT_SYNTHESIS);
+
+  size_t o = 0;
+  pl->off_layers = o;  o = align256(o + sizeof(LayerInfo) * (size_t)d->n_layers);
+  pl->off_bins = o;    o = align256(o + sizeof(int32_t) * (size_t)pl->n_bins_total);
+  pl->off_weights = o; o = align256(o + sizeof(float) * (size_t)pl->n_bins_total);
+  pl->off_FK = o;      o = align256(o + sizeof(float2) * (size_t)coef);
+  pl->off_FV = o;      o = align256(o + sizeof(float2) * (size_t)coef);
+  pl->state_bytes = o;
+
+  o = 0;
+  pl->off_qc = o; o = align256(o + sizeof(float2) * (size_t)ws);
+  pl->off_Pn = o; o = align256(o + sizeof(float2) * (size_t)ws);
+  pl->off_direct = o;
+  if (!pl->use_fft)
+    o = align256(o + sizeof(float) * (size_t)d->n_layers * (size_t)slices_per_layer *
+                         (size_t)pl->G * (size_t)d->M);
+  pl->ws_bytes = o;
+  return IWDFT_OK;
+}
+
+}  // namespace
+
+struct iwdft_ctx {
+  iwdft_desc desc;  // host pointers inside are cleared after create
+  Plan plan;
+  Params P;
+  int device = 0;
+  int64_t T = 0;
+  char* state = nullptr;
+  char* ws = nullptr;
+};
+
+namespace {
+
+int check_ctx(const iwdft_ctx* c) {
+  if (!c) return fail(IWDFT_ERR_ARG, "ctx is NULL");
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess) return fail(IWDFT_ERR_HIP, "hipGetDevice failed");
+  if (dev != c->device)
+    return fail(IWDFT_ERR_STATE, "context belongs to device %d but device %d is current", c->device,
+                dev);
+  return IWDFT_OK;
+}
+
+int launched(hipError_t e, const char* what) {
+  if (e != hipSuccess) return fail(IWDFT_ERR_HIP, "%s: %s", what, hipGetErrorString(e));
+  return IWDFT_OK;
+}
+
+uint32_t t_shift(const iwdft_ctx* c) {  // (T - M) mod M
+  return (uint32_t)((c->T - c->desc.M) % c->desc.M);
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* iwdft_last_error(void) { return g_err; }
+
+int iwdft_query_bytes(const iwdft_desc* desc, size_t* state_bytes, size_t* workspace_bytes) {
+  if (!state_bytes || !workspace_bytes) return fail(IWDFT_ERR_ARG, "output pointer is NULL");
+  Plan pl;
+  int rc = make_plan(desc, &pl);
+  if (rc != IWDFT_OK) return rc;
+  *state_bytes = pl.state_bytes;
+  *workspace_bytes = pl.ws_bytes < 256 ? 256 : pl.ws_bytes;
+  return IWDFT_OK;
+}
+
+int iwdft_create(const iwdft_desc* desc, void* d_state, size_t state_bytes, void* d_workspace,
+                 size_t workspace_bytes, iwdft_ctx** out) {
+  if (!out) return fail(IWDFT_ERR_ARG, "out is NULL");
+  *out = nullptr;
+  iwdft_ctx* c = new (std::nothrow) iwdft_ctx();
+  if (!c) return fail(IWDFT_ERR_ARG, "out of host memory");
+  int rc = make_plan(desc, &c->plan);
+  if (rc != IWDFT_OK) { delete c; return rc; }
+  const Plan& pl = c->plan;
+  size_t need_ws = pl.ws_bytes < 256 ? 256 : pl.ws_bytes;
+  if (!d_state || !d_workspace) { delete c; return fail(IWDFT_ERR_ARG, "d_state / d_workspace is NULL"); }
+  if (((uintptr_t)d_state & 255) || ((uintptr_t)d_workspace & 255)) {
+    delete c;
+    return fail(IWDFT_ERR_ARG, "d_state and d_workspace must be 256-byte aligned");
+  }
+  if (state_bytes < pl.state_bytes) {
+    delete c;
+    return fail(IWDFT_ERR_SIZE, "state buffer has %zu bytes, %zu needed", state_bytes, pl.state_bytes);
+  }
+  if (workspace_bytes < need_ws) {
+    delete c;
+    return fail(IWDFT_ERR_SIZE, "workspace has %zu bytes, %zu needed", workspace_bytes, need_ws);
+  }
+  c->desc = *desc;
+  c->state = (char*)d_state;
+  c->ws = (char*)d_workspace;
+  if (hipGetDevice(&c->device) != hipSuccess) { delete c; return fail(IWDFT_ERR_HIP, "hipGetDevice failed"); }
+
+  // Device copies of geometry, bins and weights live at the head of the state buffer.
+  std::vector<float> w((size_t)pl.n_bins_total, 1.0f);
+  if (desc->bin_weights) memcpy(w.data(), desc->bin_weights, sizeof(float) * w.size());
+  hipError_t e = hipMemset(c->state, 0, pl.state_bytes);
+  if (e == hipSuccess)
+    e = hipMemcpy(c->state + pl.off_layers, pl.layers.data(), sizeof(LayerInfo) * pl.layers.size(),
+                  hipMemcpyHostToDevice);
+  if (e == hipSuccess)
+    e = hipMemcpy(c->state + pl.off_bins, desc->bins, sizeof(int32_t) * (size_t)pl.n_bins_total,
+                  hipMemcpyHostToDevice);
+  if (e == hipSuccess)
+    e = hipMemcpy(c->state + pl.off_weights, w.data(), sizeof(float) * w.size(), hipMemcpyHostToDevice);
+  if (e != hipSuccess) {
+    delete c;
+    return fail(IWDFT_ERR_HIP, "initialising the state buffer: %s", hipGetErrorString(e));
+  }
+  c->desc.bin_offsets = nullptr;
+  c->desc.bins = nullptr;
+  c->desc.bin_weights = nullptr;
+
+  Params& P = c->P;
+  P.n_layers = desc->n_layers;
+  P.batch = desc->batch;
+  P.n_kv = desc->n_kv_heads;
+  P.G = pl.G;
+  P.n_slices = desc->n_layers * desc->batch * desc->n_kv_heads;
+  P.kv_dtype = desc->kv_dtype;
+  P.M = (uint32_t)desc->M;
+  P.Mmask = ((desc->M & (desc->M - 1)) == 0) ? (uint32_t)(desc->M - 1) : 0u;
+  if (desc->M == 1) P.Mmask = 0;  // M = 1: "mod 1" through the generic path
+  P.max_nb = pl.max_nb;
+  P.max_Bp = pl.max_Bp;
+  P.layers = (const LayerInfo*)(c->state + pl.off_layers);
+  P.bins = (const int32_t*)(c->state + pl.off_bins);
+  P.weights = (const float*)(c->state + pl.off_weights);
+  P.FK = (float2*)(c->state + pl.off_FK);
+  P.FV = (float2*)(c->state + pl.off_FV);
+  c->T = 0;
+  *out = c;
+  return IWDFT_OK;
+}
+
+int iwdft_destroy(iwdft_ctx* ctx) {
+  delete ctx;
+  return IWDFT_OK;
+}
+
+int64_t iwdft_num_tokens(const iwdft_ctx* ctx) { return ctx ? ctx->T : -1; }
+
+int iwdft_set_num_tokens(iwdft_ctx* ctx, int64_t T) {
+  if (!ctx) return fail(IWDFT_ERR_ARG, "ctx is NULL");
+  if (T < ctx->desc.M) return fail(IWDFT_ERR_ARG, "T = %lld is below M", (long long)T);
+  ctx->T = T;
+  return IWDFT_OK;
+}
+
+int iwdft_prefill(iwdft_ctx* ctx, const void* d_K, const void* d_V, void* hip_stream) {
+  int rc = check_ctx(ctx);
+  if (rc != IWDFT_OK) return rc;
+  if (!d_K || !d_V) return fail(IWDFT_ERR_ARG, "d_K / d_V is NULL");
+  rc = launched(launch_prefill(ctx->P, d_K, d_V, (hipStream_t)hip_stream), "prefill launch");
+  if (rc != IWDFT_OK) return rc;
+  ctx->T = ctx->desc.M;
+  return IWDFT_OK;
+}
+
+int iwdft_append(iwdft_ctx* ctx, const void* d_tok_k, const void* d_tok_v, void* hip_stream) {
+  int rc = check_ctx(ctx);
+  if (rc != IWDFT_OK) return rc;
+  if (!d_tok_k || !d_tok_v) return fail(IWDFT_ERR_ARG, "d_tok_k / d_tok_v is NULL");
+  if (ctx->T < ctx->desc.M) return fail(IWDFT_ERR_STATE, "iwdft_append before iwdft_prefill");
+  rc = launched(launch_append(ctx->P, d_tok_k, d_tok_v, t_shift(ctx), (hipStream_t)hip_stream),
+                "append launch");
+  if (rc != IWDFT_OK) return rc;
+  ctx->T += 1;
+  return IWDFT_OK;
+}
+
+int iwdft_export_coeffs(iwdft_ctx* ctx, int32_t layer, float* d_SK, float* d_SV, void* hip_stream) {
+  int rc = check_ctx(ctx);
+  if (rc != IWDFT_OK) return rc;
+  if (layer < 0 || layer >= ctx->desc.n_layers) return fail(IWDFT_ERR_ARG, "layer %d out of range", layer);
+  if (ctx->T < ctx->desc.M) return fail(IWDFT_ERR_STATE, "iwdft_export_coeffs before iwdft_prefill");
+  if (!d_SK && !d_SV) return IWDFT_OK;
+  return launched(launch_export(ctx->P, layer, d_SK, d_SV, t_shift(ctx), (float)(1.0 / (double)ctx->T),
+                                (hipStream_t)hip_stream),
+                  "export launch");
+}
+
+int iwdft_export_bins(iwdft_ctx* ctx, int32_t layer, int32_t* d_bins, void* hip_stream) {
+  int rc = check_ctx(ctx);
+  if (rc != IWDFT_OK) return rc;
+  if (layer < 0 || layer >= ctx->desc.n_layers) return fail(IWDFT_ERR_ARG, "layer %d out of range", layer);
+  if (!d_bins) return fail(IWDFT_ERR_ARG, "d_bins is NULL");
+  const LayerInfo& L = ctx->plan.layers[layer];
+  return launched(hipMemcpyAsync(d_bins, ctx->P.bins + L.bin_off, sizeof(int32_t) * (size_t)L.nb,
+                                 hipMemcpyDeviceToDevice, (hipStream_t)hip_stream),
+                  "export bins");
+}
+
+int iwdft_reconstruct(iwdft_ctx* ctx, int32_t layer, int64_t a0, int64_t n_slots, void* d_Kt, void* d_Vt,
+                      void* hip_stream) {
+  int rc = check_ctx(ctx);
+  if (rc != IWDFT_OK) return rc;
+  if (layer < 0 || layer >= ctx->desc.n_layers) return fail(IWDFT_ERR_ARG, "layer %d out of range", layer);
+  if (a0 < 0 || n_slots < 0 || a0 + n_slots > ctx->desc.M)
+    return fail(IWDFT_ERR_ARG, "slots [%lld, %lld) outside [0, M)", (long long)a0, (long long)(a0 + n_slots));
+  if (ctx->T < ctx->desc.M) return fail(IWDFT_ERR_STATE, "iwdft_reconstruct before iwdft_prefill");
+  if (n_slots == 0 || (!d_Kt && !d_Vt)) return IWDFT_OK;
+  return launched(launch_reconstruct(ctx->P, layer, (uint32_t)a0, (uint32_t)n_slots, d_Kt, d_Vt,
+                                     t_shift(ctx), (hipStream_t)hip_stream),
+                  "reconstruct launch");
+}
+
+int compressed_decode_attn(iwdft_ctx* ctx, const void* d_q, void* d_out, float scale, void* hip_stream) {
+  int rc = check_ctx(ctx);
+  if (rc != IWDFT_OK) return rc;
+  if (!d_q || !d_out) return fail(IWDFT_ERR_ARG, "d_q / d_out is NULL");
+  if (ctx->T < ctx->desc.M) return fail(IWDFT_ERR_STATE, "compressed_decode_attn before iwdft_prefill");
+  if (!std::isfinite(scale)) return fail(IWDFT_ERR_ARG, "scale is not finite");
+  if (scale <= 0.0f) scale = 1.0f / std::sqrt((float)ctx->desc.head_dim);
+  const Plan& pl = ctx->plan;
+  return launched(launch_attn(ctx->P, d_q, d_out, scale, (float2*)(ctx->ws + pl.off_qc),
+                              (float2*)(ctx->ws + pl.off_Pn), (float*)(ctx->ws + pl.off_direct),
+                              pl.use_fft, (hipStream_t)hip_stream),
+                  "decode attention launch");
+}
+
+}  // extern "C"

@@ -1,0 +1,98 @@
+// Shared device-side definitions of libiwdft: state layout, exact phase arithmetic,
+// dtype conversion.  gfx950 only.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace iwdft {
+
+constexpr int kHeadDim = 128;  // channels per head the kernels are written for
+constexpr int kRowPad = 32;    // a coefficient row is padded to a multiple of this many bins
+
+// Per-layer geometry, one entry per layer in device memory.
+struct LayerInfo {
+  int32_t bin_off;   // first entry of this layer in the bins / weights arrays
+  int32_t nb;        // number of kept bins |B_l|
+  int32_t Bp;        // nb rounded up to kRowPad: length of one coefficient row (in float2)
+  int32_t pad_;
+  int64_t coef_off;  // float2 offset of the layer's first slice plane inside FK / FV
+  int64_t ws_off;    // float2 offset of the layer's first (slice, query-head) row in qc / Pn
+};
+
+// Everything a kernel needs to find its data.  Passed by value.
+//
+// Coefficient storage ("fixed frame"): for tensor X in {K, V}, slice s of layer l, channel c,
+// kept-bin index i (bin k = bins[bin_off + i]):
+//     F[coef_off + (s * 128 + c) * Bp + i] = F_T[k] = exp(+j 2 pi k (T-M) / M) * U_T[k]
+// where U_T = T * S_T is the un-normalised accumulator of the IWDFT recursion (Sec. 4.1).
+// In this frame one recursion step is F_{T+1}[k] = F_T[k] + x_T * exp(+j 2 pi k (T-M) / M):
+// the rotation by W_k and the factors (N-1)/N, 1/N of Eq. infi-dft are folded into the phase
+// of the added term and into the 1/T applied whenever S_T is read out, so the stored numbers
+// never pass through a rounded rotation and old tokens keep exactly their weight.
+// Row entries with i >= nb are padding and stay zero.
+struct Params {
+  int32_t n_layers, batch, n_kv, G, n_slices;  // n_slices = n_layers * batch * n_kv
+  int32_t kv_dtype;                            // IWDFT_F32 / IWDFT_BF16
+  uint32_t M;                                  // DFT length
+  uint32_t Mmask;                              // M-1 when M is a power of two, else 0
+  int32_t max_nb, max_Bp;
+  const LayerInfo* layers;
+  const int32_t* bins;
+  const float* weights;
+  float2* FK;
+  float2* FV;
+};
+
+// (a * b) mod M, exact.
+__device__ __forceinline__ uint32_t mulmod(uint32_t a, uint32_t b, uint32_t M, uint32_t Mmask) {
+  uint64_t p = (uint64_t)a * (uint64_t)b;
+  return Mmask ? ((uint32_t)p & Mmask) : (uint32_t)(p % M);
+}
+
+// exp(+j 2 pi p / M) for an already reduced phase 0 <= p < M.  For power-of-two M the
+// argument handed to sincospi is exact, so the result is correct to ~1 ulp at any M.
+__device__ __forceinline__ float2 cis(uint32_t p, uint32_t M) {
+  float x = 2.0f * (float)p / (float)M;
+  float s, c;
+  sincospif(x, &s, &c);
+  return make_float2(c, s);
+}
+
+__device__ __forceinline__ float2 cmul(float2 a, float2 b) {
+  return make_float2(a.x * b.x - a.y * b.y, a.x * b.y + a.y * b.x);
+}
+
+__device__ __forceinline__ float bf16_to_f32(uint16_t h) { return __uint_as_float((uint32_t)h << 16); }
+
+__device__ __forceinline__ uint16_t f32_to_bf16(float f) {  // round to nearest even
+  uint32_t u = __float_as_uint(f);
+  if ((u & 0x7fffffffu) > 0x7f800000u) return (uint16_t)((u >> 16) | 0x40u);  // NaN stays NaN
+  u += 0x7fffu + ((u >> 16) & 1u);
+  return (uint16_t)(u >> 16);
+}
+
+template <bool BF16>
+__device__ __forceinline__ float load_kv(const void* p, int64_t i) {
+  if constexpr (BF16) return bf16_to_f32(((const uint16_t*)p)[i]);
+  else return ((const float*)p)[i];
+}
+
+template <bool BF16>
+__device__ __forceinline__ void store_kv(void* p, int64_t i, float v) {
+  if constexpr (BF16) ((uint16_t*)p)[i] = f32_to_bf16(v);
+  else ((float*)p)[i] = v;
+}
+
+// Host-side launchers (defined next to their kernels).  Each validates nothing: the C ABI
+// layer has already checked every shape.  They return the hipError_t of the launch.
+hipError_t launch_prefill(const Params& P, const void* K, const void* V, hipStream_t st);
+hipError_t launch_append(const Params& P, const void* tok_k, const void* tok_v, uint32_t t_shift,
+                         hipStream_t st);
+hipError_t launch_export(const Params& P, int layer, float* SK, float* SV, uint32_t t_shift,
+                         float inv_T, hipStream_t st);
+hipError_t launch_reconstruct(const Params& P, int layer, uint32_t a0, uint32_t n_slots, void* Kt,
+                              void* Vt, uint32_t t_shift, hipStream_t st);
+hipError_t launch_attn(const Params& P, const void* q, void* out, float scale, float2* qc,
+                       float2* Pn, float* direct_scratch, bool use_fft, hipStream_t st);
+
+}  // namespace iwdft

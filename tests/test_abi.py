@@ -1,0 +1,80 @@
+"""Boundary checks that need no GPU: the library loads, exports every symbol the
+header declares, and rejects bad descriptors with the documented error codes."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+from paper_2507_20030_amd import binding as B
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def header_functions():
+    src = open(os.path.join(ROOT, "include", "iwdft.h")).read()
+    src = re.sub(r"/\*.*?\*/", "", src, flags=re.S)
+    return sorted(set(re.findall(r"\b((?:iwdft_|compressed_)\w+)\s*\(", src)))
+
+
+def test_library_exports_every_declared_symbol():
+    lib = B.load_library()
+    names = header_functions()
+    assert set(names) == set(B.EXPORTED)
+    for n in names:
+        assert hasattr(lib, n), n
+
+
+def desc(**kw):
+    args = dict(n_layers=2, batch=1, n_kv_heads=2, n_q_heads=4, head_dim=128, kv_dtype=B.IWDFT_BF16,
+                M=64, bins=[np.arange(8), np.array([0, 3, 9, 63])])
+    args.update(kw)
+    return B.Descriptor(**args)
+
+
+def test_query_bytes_accounts_for_padded_rows():
+    d = desc()
+    state, ws = B.iwdft_query_bytes(d)
+    # rows are padded to 32 bins: 2 layers * 2 slices * 128 channels * 32 * 8 B per tensor
+    coef = 2 * 2 * 128 * 32 * 8
+    assert state >= 2 * coef and state < 2 * coef + 4096
+    assert ws >= 2 * (2 * 2 * 2 * 32 * 8)
+    assert state % 256 == 0 and ws % 256 == 0
+
+
+@pytest.mark.parametrize("kw,code", [
+    (dict(n_layers=0, bins=[]), B.IWDFT_ERR_ARG),
+    (dict(n_q_heads=3), B.IWDFT_ERR_ARG),
+    (dict(kv_dtype=7), B.IWDFT_ERR_ARG),
+    (dict(M=0), B.IWDFT_ERR_ARG),
+    (dict(M=(1 << 30) + 1), B.IWDFT_ERR_ARG),
+    (dict(flags=8), B.IWDFT_ERR_ARG),
+    (dict(head_dim=64), B.IWDFT_ERR_UNSUPPORTED),
+    (dict(bins=[np.arange(8), np.array([0, 3, 3, 9])]), B.IWDFT_ERR_BINS),
+    (dict(bins=[np.arange(8), np.array([5, 3])]), B.IWDFT_ERR_BINS),
+    (dict(bins=[np.arange(8), np.array([0, 64])]), B.IWDFT_ERR_BINS),
+    (dict(bins=[np.arange(8), np.array([-1, 2])]), B.IWDFT_ERR_BINS),
+    (dict(bins=[np.arange(8), np.zeros(0, np.int32)]), B.IWDFT_ERR_BINS),
+    (dict(bins=[np.arange(8), np.arange(4)], bin_weights=[np.ones(8), np.array([1, np.nan, 1, 1])]),
+     B.IWDFT_ERR_BINS),
+])
+def test_bad_descriptors_are_rejected(kw, code):
+    with pytest.raises(B.IwdftError) as e:
+        B.iwdft_query_bytes(desc(**kw))
+    assert e.value.code == code
+    assert B.iwdft_last_error()
+
+
+def test_null_pointers_and_null_ctx():
+    lib = B.load_library()
+    assert lib.iwdft_query_bytes(None, None, None) == B.IWDFT_ERR_ARG
+    s = ctypes.c_size_t()
+    assert lib.iwdft_query_bytes(None, ctypes.byref(s), ctypes.byref(s)) == B.IWDFT_ERR_ARG
+    assert lib.iwdft_num_tokens(None) == -1
+    assert lib.iwdft_destroy(None) == B.IWDFT_OK
+    assert lib.iwdft_set_num_tokens(None, 5) == B.IWDFT_ERR_ARG
+    d = desc()
+    out = ctypes.c_void_p()
+    assert lib.iwdft_create(ctypes.byref(d.c), None, 0, None, 0, ctypes.byref(out)) == B.IWDFT_ERR_ARG
+    assert lib.iwdft_create(ctypes.byref(d.c), None, 0, None, 0, None) == B.IWDFT_ERR_ARG

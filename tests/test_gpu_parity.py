@@ -1,0 +1,250 @@
+"""GPU parity: every C-ABI call against the float64 oracle on the same seeded inputs.
+
+Tolerances (relative L2 over the compared tensor):
+  coefficients (fp32 complex)            1e-4   (stated target)
+  attention output, bf16 storage         2e-2   (stated target)
+  attention output, fp32 storage         1e-4   (fp32 arithmetic: FFT + exp of scores of
+                                                 magnitude <~ 50 gives ~1e-5; one decade of slack)
+  reconstruction, fp32 / bf16 storage    1e-4 / 4e-3 (bf16 rounding alone is 2^-9 per element)
+Kept-bin masks read back from the device must be bit-exact.
+"""
+import numpy as np
+import pytest
+import torch
+
+from oracle import iwdft_oracle as orc
+from paper_2507_20030_amd import binding as B
+from paper_2507_20030_amd import workload as wl
+
+pytestmark = pytest.mark.gpu
+
+TOL_COEF = 1e-4
+TOL_ATTN = {torch.float32: 1e-4, torch.bfloat16: 2e-2}
+TOL_REC = {torch.float32: 1e-4, torch.bfloat16: 4e-3}
+DEV = "cuda:0"
+
+
+def rel_l2(a, ref):
+    return float(np.linalg.norm(np.asarray(a) - ref) / max(np.linalg.norm(ref), 1e-300))
+
+
+def f64(t):
+    return t.detach().to("cpu").to(torch.float64).numpy()
+
+
+def c128(t):
+    return t.detach().to("cpu").numpy().astype(np.complex128)
+
+
+def make_cache(cfg, bins, weights=None, flags=0):
+    return B.Cache(cfg.n_layers, cfg.batch, cfg.n_kv_heads, cfg.n_q_heads, cfg.head_dim, cfg.torch_dtype,
+                   cfg.L, bins, weights, flags, DEV)
+
+
+class SliceOracle:
+    """Float64 state of a few sampled slices, advanced next to the GPU cache."""
+
+    def __init__(self, cfg, bins, weights, K, V, slices):
+        self.cfg, self.bins, self.weights, self.slices = cfg, bins, weights, slices
+        self.M = cfg.L
+        self.T = cfg.L
+        self.S = {}
+        for (l, b, h) in slices:
+            self.S[(l, b, h)] = [orc.prefill(f64(K[l, b, h]), bins[l]), orc.prefill(f64(V[l, b, h]), bins[l])]
+
+    def append(self, tk, tv):
+        for (l, b, h), st in self.S.items():
+            st[0] = orc.append(st[0], f64(tk[l, b, h]), self.T, self.bins[l], self.M)
+            st[1] = orc.append(st[1], f64(tv[l, b, h]), self.T, self.bins[l], self.M)
+        self.T += 1
+
+    def attend(self, q):
+        G = self.cfg.group
+        out = {}
+        for (l, b, h), st in self.S.items():
+            w = None if self.weights is None else self.weights[l]
+            out[(l, b, h)] = orc.decode_attention(f64(q[l, b, h * G:(h + 1) * G]), st[0], st[1], self.T, self.M,
+                                                  self.bins[l], w)
+        return out
+
+    def reconstruct(self, key, which):
+        l = key[0]
+        w = None if self.weights is None else self.weights[l]
+        return orc.reconstruct(self.S[key][which], self.T, self.M, self.bins[l], w)
+
+
+def check_coeffs(cache, ora, tag):
+    worst = 0.0
+    for l in sorted({k[0] for k in ora.S}):
+        SK, SV = cache.export_coeffs(l)
+        for (ll, b, h), st in ora.S.items():
+            if ll != l:
+                continue
+            worst = max(worst, rel_l2(c128(SK[b, h]), st[0]), rel_l2(c128(SV[b, h]), st[1]))
+    assert worst < TOL_COEF, f"{tag}: coefficient rel-L2 {worst:.3e}"
+    return worst
+
+
+def check_attn(cfg, cache, ora, q, tag):
+    out = cache.attend(q)
+    ref = ora.attend(q)
+    G = cfg.group
+    worst = 0.0
+    for (l, b, h), r in ref.items():
+        worst = max(worst, rel_l2(f64(out[l, b, h * G:(h + 1) * G]), r))
+    assert worst < TOL_ATTN[cfg.torch_dtype], f"{tag}: attention rel-L2 {worst:.3e}"
+    return worst
+
+
+def check_reconstruct(cfg, cache, ora, a0, n, tag):
+    worst = 0.0
+    for l in sorted({k[0] for k in ora.S}):
+        Kt, Vt = cache.reconstruct(l, a0, n)
+        for key in ora.S:
+            if key[0] != l:
+                continue
+            _, b, h = key
+            worst = max(worst, rel_l2(f64(Kt[b, h]), ora.reconstruct(key, 0)[a0:a0 + n]),
+                        rel_l2(f64(Vt[b, h]), ora.reconstruct(key, 1)[a0:a0 + n]))
+    assert worst < TOL_REC[cfg.torch_dtype], f"{tag}: reconstruction rel-L2 {worst:.3e}"
+    return worst
+
+
+def check_masks(cache, bins):
+    for l, b in enumerate(bins):
+        got = cache.export_bins(l).cpu().numpy()
+        assert got.dtype == np.int32 and np.array_equal(got, np.asarray(b, np.int32)), f"mask of layer {l}"
+
+
+def run_stream(cfg, bins, weights=None, flags=0, steps=None, slices=None, rec=(0, 64), tag=""):
+    steps = cfg.steps if steps is None else steps
+    slices = wl.sample_slices(cfg) if slices is None else slices
+    K, V = wl.prefill_tensors(cfg, DEV)
+    cache = make_cache(cfg, bins, weights, flags)
+    check_masks(cache, bins)
+    cache.prefill(K, V)
+    assert cache.T == cfg.L
+    ora = SliceOracle(cfg, bins, weights, K, V, slices)
+    del K, V
+    stats = {"coef0": check_coeffs(cache, ora, tag + " prefill")}
+    stats["rec0"] = check_reconstruct(cfg, cache, ora, rec[0], rec[1], tag + " prefill")
+    worst_attn = 0.0
+    for i in range(steps):
+        tk, tv, q = wl.decode_step(cfg, i, DEV)
+        cache.append(tk, tv)
+        ora.append(tk, tv)
+        worst_attn = max(worst_attn, check_attn(cfg, cache, ora, q, f"{tag} step {i}"))
+    assert cache.T == cfg.L + steps
+    stats["attn"] = worst_attn
+    stats["coefN"] = check_coeffs(cache, ora, tag + " after appends")
+    stats["recN"] = check_reconstruct(cfg, cache, ora, max(0, cfg.L - rec[1]), min(rec[1], cfg.L), tag + " end")
+    torch.cuda.synchronize()
+    print(f"\n[{tag}] " + " ".join(f"{k}={v:.2e}" for k, v in stats.items()), flush=True)
+    cache.close()
+    return stats
+
+
+def small_cfg(**kw):
+    base = dict(name="small", n_layers=2, batch=2, n_kv_heads=2, group=2, head_dim=128, L=256, n_bins=40,
+                steps=5, dtype="f32", mask="low", seed=3)
+    base.update(kw)
+    return wl.Config(**base)
+
+
+def random_bins(cfg, seed):
+    rng = np.random.default_rng(seed)
+    return [np.sort(rng.choice(cfg.L, size=cfg.n_bins - (l % 2), replace=False)).astype(np.int32)
+            for l in range(cfg.n_layers)]
+
+
+def test_cfg1_full_stream_fft_path():
+    cfg = wl.CONFIGS["cfg1"]
+    run_stream(cfg, wl.layer_bins(cfg), tag="cfg1")
+
+
+def test_cfg1_direct_synthesis_path():
+    cfg = wl.CONFIGS["cfg1"]
+    run_stream(cfg, wl.layer_bins(cfg), flags=B.IWDFT_FLAG_DIRECT_SYNTHESIS, steps=3, tag="cfg1-direct")
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("L,group", [(256, 2), (1024, 3), (96, 1), (2048, 8)])
+def test_ragged_random_masks(dtype, L, group):
+    # odd bin counts (ragged rows), scattered bins (folding collisions), batch > 1, odd group size,
+    # non-power-of-two M (direct synthesis), wrap-around of the slot shift (steps > 0 with small M)
+    cfg = small_cfg(L=L, group=group, dtype=dtype, n_bins=min(77, L // 2 + 5))
+    run_stream(cfg, random_bins(cfg, 11), rec=(3, 50), tag=f"ragged-{dtype}-L{L}-G{group}")
+
+
+def test_bin_weights_one_sided():
+    cfg = small_cfg(L=512, n_bins=257, group=2)
+    bins = [np.arange(257, dtype=np.int32) for _ in range(cfg.n_layers)]
+    w = [np.where((b == 0) | (b == 256), 1.0, 2.0).astype(np.float32) for b in bins]
+    st = run_stream(cfg, bins, weights=w, steps=2, tag="one-sided")
+    # with every bin of a real signal represented, reconstruction at T = M is the input itself
+    K, V = wl.prefill_tensors(cfg, DEV)
+    cache = make_cache(cfg, bins, w)
+    cache.prefill(K, V)
+    Kt, Vt = cache.reconstruct(1, 0, cfg.L)
+    assert rel_l2(f64(Kt), f64(K[1])) < 1e-5 and rel_l2(f64(Vt), f64(V[1])) < 1e-5
+    cache.close()
+
+
+def test_many_wraps_slot_shift():
+    # more appends than M: the shift (T - M) mod M wraps several times
+    cfg = small_cfg(L=64, n_bins=20, group=1, steps=150, n_layers=1, batch=1)
+    run_stream(cfg, random_bins(cfg, 5), rec=(0, 64), tag="wraps")
+
+
+def test_call_order_and_argument_errors():
+    cfg = small_cfg()
+    bins = random_bins(cfg, 1)
+    cache = make_cache(cfg, bins)
+    tk, tv, q = wl.decode_step(cfg, 0, DEV)
+    for fn in (lambda: cache.append(tk, tv), lambda: cache.attend(q), lambda: cache.export_coeffs(0),
+               lambda: cache.reconstruct(0, 0, 4)):
+        with pytest.raises(B.IwdftError) as e:
+            fn()
+        assert e.value.code == B.IWDFT_ERR_STATE
+    K, V = wl.prefill_tensors(cfg, DEV)
+    cache.prefill(K, V)
+    for fn, code in ((lambda: cache.reconstruct(5, 0, 4), B.IWDFT_ERR_ARG),
+                     (lambda: cache.reconstruct(0, cfg.L - 2, 4), B.IWDFT_ERR_ARG),
+                     (lambda: cache.export_coeffs(-1), B.IWDFT_ERR_ARG),
+                     (lambda: B.iwdft_set_num_tokens(cache.ctx, cfg.L - 1), B.IWDFT_ERR_ARG)):
+        with pytest.raises(B.IwdftError) as e:
+            fn()
+        assert e.value.code == code
+    small = torch.empty(256, dtype=torch.uint8, device=DEV)
+    with pytest.raises(B.IwdftError) as e:
+        B.iwdft_create(cache.desc, small, cache.workspace)
+    assert e.value.code == B.IWDFT_ERR_SIZE
+    cache.close()
+
+
+def test_checkpoint_resume_is_bitwise():
+    cfg = small_cfg(steps=6)
+    bins = random_bins(cfg, 2)
+    K, V = wl.prefill_tensors(cfg, DEV)
+    cache = make_cache(cfg, bins)
+    cache.prefill(K, V)
+    steps = [wl.decode_step(cfg, i, DEV) for i in range(6)]
+    for tk, tv, _ in steps[:2]:
+        cache.append(tk, tv)
+    saved, T = cache.state.clone(), cache.T
+    for tk, tv, _ in steps[2:]:
+        cache.append(tk, tv)
+    a = cache.attend(steps[5][2]).clone()
+    end = cache.state.clone()
+    cache.state.copy_(saved)
+    B.iwdft_set_num_tokens(cache.ctx, T)
+    for tk, tv, _ in steps[2:]:
+        cache.append(tk, tv)
+    assert torch.equal(cache.state, end)
+    assert torch.equal(cache.attend(steps[5][2]), a)
+    cache.close()
+
+
+def test_cfg2_full_size_sampled_slices():
+    cfg = wl.CONFIGS["cfg2"]
+    run_stream(cfg, wl.layer_bins(cfg), steps=3, tag="cfg2")
