@@ -103,8 +103,18 @@ def layer_bins(cfg: Config) -> List[np.ndarray]:
 
 
 # ---------------------------------------------------------------------------- values
+_SCALE_CACHE: dict = {}
+
+
 def k_channel_scale(cfg: Config, layer: int, device) -> torch.Tensor:
     """Per (kv head, channel) scale of K: log-uniform in [0.1, 10], optional x20 outliers."""
+    key = (cfg, layer, str(device))
+    if key not in _SCALE_CACHE:
+        _SCALE_CACHE[key] = _k_channel_scale(cfg, layer, device)
+    return _SCALE_CACHE[key]
+
+
+def _k_channel_scale(cfg: Config, layer: int, device) -> torch.Tensor:
     g = _gen("cpu", _seed(cfg, 3, layer))
     s = 10.0 ** (2.0 * torch.rand((cfg.n_kv_heads, cfg.head_dim), generator=g) - 1.0)
     for h in range(cfg.n_kv_heads):
@@ -139,7 +149,10 @@ def decode_step(cfg: Config, step: int, device):
     """Token K/V [n_layers, batch, n_kv_heads, d] and queries [n_layers, batch, n_q_heads, d]."""
     g = _gen(device, _seed(cfg, 7, step))
     kv_shape = (cfg.n_layers, cfg.batch, cfg.n_kv_heads, cfg.head_dim)
-    scale = torch.stack([k_channel_scale(cfg, l, device) for l in range(cfg.n_layers)])[:, None]
+    key = (cfg, "all", str(device))
+    if key not in _SCALE_CACHE:
+        _SCALE_CACHE[key] = torch.stack([k_channel_scale(cfg, l, device) for l in range(cfg.n_layers)])[:, None]
+    scale = _SCALE_CACHE[key]
     tk = (torch.randn(kv_shape, generator=g, device=device, dtype=torch.float32) * scale).to(cfg.torch_dtype)
     tv = torch.randn(kv_shape, generator=g, device=device, dtype=torch.float32).to(cfg.torch_dtype)
     q = torch.randn((cfg.n_layers, cfg.batch, cfg.n_q_heads, cfg.head_dim), generator=g, device=device,
