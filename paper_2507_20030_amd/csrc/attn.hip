@@ -175,7 +175,7 @@ __global__ __launch_bounds__(kOutThreads) void attn_out_kernel(Params P, const f
 
 // ------------------------------------------------------------------------------------- B (FFT)
 constexpr int kFftThreads = 512;
-constexpr int kFftNBT = 8;   // kept bins per thread held in registers  (|B| <= 4096)
+constexpr int kFftNBT = 8;   // kept bins per thread                     (|B| <= 4096)
 constexpr int kFftEPT = 16;  // time samples per thread                  (Q   <= 8192)
 constexpr int kFftMaxLogQ = 13;
 
@@ -185,68 +185,148 @@ __device__ __forceinline__ float2 cadd(float2 a, float2 b) { return make_float2(
 __device__ __forceinline__ float2 csub(float2 a, float2 b) { return make_float2(a.x - b.x, a.y - b.y); }
 __device__ __forceinline__ float2 conjf2(float2 a) { return make_float2(a.x, -a.y); }
 
-// In-place inverse (sign +) decimation-in-frequency transform, natural order in, digit-reversed
-// order out.  Radix-4 stages with spans Q/4, Q/16, ...; one final radix-2 stage when log2 Q is odd.
-__device__ void ifft_dif(float2* buf, int logQ, int tid) {
-  const int Q = 1 << logQ;
-  int ls = logQ;  // log2 of the current span
-  for (int st = 0; st < logQ / 2; ++st) {
-    ls -= 2;
-    const int s = 1 << ls;
-    for (int bf = tid; bf < Q / 4; bf += kFftThreads) {
-      const int j = bf & (s - 1);
-      const int p0 = ((bf >> ls) << (ls + 2)) + j;
-      const float2 a0 = buf[p0], a1 = buf[p0 + s], a2 = buf[p0 + 2 * s], a3 = buf[p0 + 3 * s];
-      const float2 t0 = cadd(a0, a2), t1 = csub(a0, a2), t2 = cadd(a1, a3), t3 = mul_i(csub(a1, a3));
-      const float2 w1 = cis((uint32_t)j, (uint32_t)(4 * s));
-      const float2 w2 = cmul(w1, w1), w3 = cmul(w2, w1);
-      buf[p0] = cadd(t0, t2);
-      buf[p0 + s] = cmul(cadd(t1, t3), w1);
-      buf[p0 + 2 * s] = cmul(csub(t0, t2), w2);
-      buf[p0 + 3 * s] = cmul(csub(t1, t3), w3);
-    }
-    __syncthreads();
-  }
-  if (logQ & 1) {
-    for (int bf = tid; bf < Q / 2; bf += kFftThreads) {
-      const float2 a = buf[2 * bf], b = buf[2 * bf + 1];
-      buf[2 * bf] = cadd(a, b);
-      buf[2 * bf + 1] = csub(a, b);
-    }
-    __syncthreads();
-  }
+// exp(+j 2 pi p / M) through the hardware sine / cosine (argument in revolutions, exact for the
+// power-of-two M this path requires; ~1e-6 absolute error, used only for the block twiddles of the
+// score synthesis where 1e-6 of a score is far below the output tolerance).
+__device__ __forceinline__ float2 cis_fast(uint32_t p, uint32_t M) {
+  const float f = (float)p / (float)M;
+  return make_float2(__builtin_amdgcn_cosf(f), __builtin_amdgcn_sinf(f));
 }
 
-// The transpose of ifft_dif with conjugated constants: forward (sign -) transform that takes the
-// digit-reversed order ifft_dif produces and returns natural order.
-__device__ void fft_dit(float2* buf, int logQ, int tid) {
-  const int Q = 1 << logQ;
-  if (logQ & 1) {
-    for (int bf = tid; bf < Q / 2; bf += kFftThreads) {
-      const float2 a = buf[2 * bf], b = buf[2 * bf + 1];
-      buf[2 * bf] = cadd(a, b);
-      buf[2 * bf + 1] = csub(a, b);
+// LDS index of logical sample i: one float2 of padding after every 32 keeps the strided
+// accesses of the late passes spread over all banks.
+__device__ __forceinline__ int pad(int i) { return i + (i >> 5); }
+__host__ __device__ constexpr int fft_lds_float2(int logQ) {
+  return (1 << logQ) + (1 << logQ) / 32 + ((1 << logQ) / 8 + 1);
+}
+
+// tab[m] = exp(+j 2 pi m / Q) for m = 0 .. Q/8; any m in [0, Q/4] by reflection about pi/4.
+__device__ __forceinline__ float2 tw_get(const float2* tab, int m, int q8) {
+  if (m <= q8) return tab[m];
+  const float2 t = tab[2 * q8 - m];
+  return make_float2(t.y, t.x);
+}
+
+// Radix-4 butterfly of the inverse (sign +) decimation-in-frequency transform: combine, then
+// multiply output m by w^m.
+__device__ __forceinline__ void r4_dif(float2& a0, float2& a1, float2& a2, float2& a3, float2 w1) {
+  const float2 w2 = cmul(w1, w1), w3 = cmul(w2, w1);
+  const float2 t0 = cadd(a0, a2), t1 = csub(a0, a2), t2 = cadd(a1, a3), t3 = mul_i(csub(a1, a3));
+  a0 = cadd(t0, t2);
+  a1 = cmul(cadd(t1, t3), w1);
+  a2 = cmul(csub(t0, t2), w2);
+  a3 = cmul(csub(t1, t3), w3);
+}
+// Its transpose with conjugated constants (forward, decimation in time): multiply input m by
+// conj(w)^m, then combine.  w1c is already conjugated.
+__device__ __forceinline__ void r4_dit(float2& a0, float2& a1, float2& a2, float2& a3, float2 w1c) {
+  const float2 w2 = cmul(w1c, w1c), w3 = cmul(w2, w1c);
+  a1 = cmul(a1, w1c);
+  a2 = cmul(a2, w2);
+  a3 = cmul(a3, w3);
+  const float2 t0 = cadd(a0, a2), t1 = csub(a0, a2), t2 = cadd(a1, a3), t3 = mul_mi(csub(a1, a3));
+  a0 = cadd(t0, t2);
+  a1 = cadd(t1, t3);
+  a2 = csub(t0, t2);
+  a3 = csub(t1, t3);
+}
+
+// Thread -> butterfly assignment of a pass whose innermost index j has LS bits: for LS < 4 the j
+// bits are taken from lane bits 4.. so that 16 consecutive lanes (one LDS access phase) touch 16
+// different butterfly groups, whose padded addresses fall into distinct banks.
+template <int LS>
+__device__ __forceinline__ int butterfly_of(int t) {
+  if constexpr (LS >= 4 || LS == 0) return t;
+  else return ((t >> (4 + LS)) << (4 + LS)) | ((t & 15) << LS) | ((t >> 4) & ((1 << LS) - 1));
+}
+
+// Two consecutive radix-4 stages (spans 4*s2 and s2) on the 16 samples p0 + m*s2 held in
+// registers: one LDS round trip instead of two.  INV: inverse DIF order (wide span first);
+// otherwise the forward DIT order (narrow span first, conjugated twiddles).
+template <int LOGQ, int LS2, bool INV>
+__device__ __forceinline__ void fft_pass16(float2* buf, const float2* tab, int tid) {
+  constexpr int Q = 1 << LOGQ, q8 = Q >> 3, s2 = 1 << LS2, NB = Q / 16;
+  constexpr int sh1 = LOGQ - LS2 - 4, sh2 = LOGQ - LS2 - 2;
+#pragma unroll
+  for (int it = 0; it < (NB + kFftThreads - 1) / kFftThreads; ++it) {
+    const int t = it * kFftThreads + tid;
+    if (NB % kFftThreads == 0 || t < NB) {
+      const int bf = butterfly_of<LS2>(t);
+      const int j = bf & (s2 - 1);
+      float2* base = buf + pad(((bf >> LS2) << (LS2 + 4)) + j);
+      float2 x[16];
+#pragma unroll
+      for (int m = 0; m < 16; ++m) x[m] = base[m * s2 + ((m * s2) >> 5)];
+      if constexpr (INV) {
+#pragma unroll
+        for (int b = 0; b < 4; ++b)
+          r4_dif(x[b], x[b + 4], x[b + 8], x[b + 12], tw_get(tab, ((b << LS2) + j) << sh1, q8));
+        const float2 w = tw_get(tab, j << sh2, q8);
+#pragma unroll
+        for (int a = 0; a < 4; ++a) r4_dif(x[4 * a], x[4 * a + 1], x[4 * a + 2], x[4 * a + 3], w);
+      } else {
+        const float2 w = conjf2(tw_get(tab, j << sh2, q8));
+#pragma unroll
+        for (int a = 0; a < 4; ++a) r4_dit(x[4 * a], x[4 * a + 1], x[4 * a + 2], x[4 * a + 3], w);
+#pragma unroll
+        for (int b = 0; b < 4; ++b)
+          r4_dit(x[b], x[b + 4], x[b + 8], x[b + 12], conjf2(tw_get(tab, ((b << LS2) + j) << sh1, q8)));
+      }
+#pragma unroll
+      for (int m = 0; m < 16; ++m) base[m * s2 + ((m * s2) >> 5)] = x[m];
     }
-    __syncthreads();
   }
-  int ls = (logQ & 1) - 2;
-  for (int st = 0; st < logQ / 2; ++st) {
-    ls += 2;
-    const int s = 1 << ls;
-    for (int bf = tid; bf < Q / 4; bf += kFftThreads) {
+  __syncthreads();
+}
+
+// One radix-4 stage of span 1 << LS.
+template <int LOGQ, int LS, bool INV>
+__device__ __forceinline__ void fft_pass4(float2* buf, const float2* tab, int tid) {
+  constexpr int Q = 1 << LOGQ, q8 = Q >> 3, s = 1 << LS, NB = Q / 4;
+#pragma unroll
+  for (int it = 0; it < (NB + kFftThreads - 1) / kFftThreads; ++it) {
+    const int t = it * kFftThreads + tid;
+    if (NB % kFftThreads == 0 || t < NB) {
+      const int bf = butterfly_of<LS>(t);
       const int j = bf & (s - 1);
-      const int p0 = ((bf >> ls) << (ls + 2)) + j;
-      const float2 w1 = conjf2(cis((uint32_t)j, (uint32_t)(4 * s)));
-      const float2 w2 = cmul(w1, w1), w3 = cmul(w2, w1);
-      const float2 a0 = buf[p0], a1 = cmul(buf[p0 + s], w1), a2 = cmul(buf[p0 + 2 * s], w2),
-                   a3 = cmul(buf[p0 + 3 * s], w3);
-      const float2 t0 = cadd(a0, a2), t1 = csub(a0, a2), t2 = cadd(a1, a3), t3 = mul_mi(csub(a1, a3));
-      buf[p0] = cadd(t0, t2);
-      buf[p0 + s] = cadd(t1, t3);
-      buf[p0 + 2 * s] = csub(t0, t2);
-      buf[p0 + 3 * s] = csub(t1, t3);
+      float2* base = buf + pad(((bf >> LS) << (LS + 2)) + j);
+      const float2 w = tw_get(tab, j << (LOGQ - LS - 2), q8);
+      float2 a0 = base[0], a1 = base[s + (s >> 5)], a2 = base[2 * s + ((2 * s) >> 5)],
+             a3 = base[3 * s + ((3 * s) >> 5)];
+      if constexpr (INV) r4_dif(a0, a1, a2, a3, w);
+      else r4_dit(a0, a1, a2, a3, conjf2(w));
+      base[0] = a0;
+      base[s + (s >> 5)] = a1;
+      base[2 * s + ((2 * s) >> 5)] = a2;
+      base[3 * s + ((3 * s) >> 5)] = a3;
     }
-    __syncthreads();
+  }
+  __syncthreads();
+}
+
+// Stage plan for Q = 2^LOGQ: n4 = LOGQ/2 radix-4 stages with spans Q/4, Q/16, ..., taken two at a
+// time (one single stage if n4 is odd), then one radix-2 stage of span 1 if LOGQ is odd.  The
+// radix-2 stage is not run here: the caller applies it to the sample pairs it holds in registers.
+// Inverse: natural order in, digit-reversed order out.
+template <int LOGQ, int P = 0>
+__device__ __forceinline__ void ifft_dif(float2* buf, const float2* tab, int tid) {
+  constexpr int n4 = LOGQ >> 1;
+  if constexpr (P < (n4 >> 1)) {
+    fft_pass16<LOGQ, LOGQ - 4 * (P + 1), true>(buf, tab, tid);
+    ifft_dif<LOGQ, P + 1>(buf, tab, tid);
+  } else if constexpr (n4 & 1) {
+    fft_pass4<LOGQ, (LOGQ & 1), true>(buf, tab, tid);
+  }
+}
+// Forward: the transpose of the above with conjugated constants; takes the digit-reversed order the
+// inverse produces (after the caller's radix-2 stage) and returns natural order.
+template <int LOGQ, int P = ((LOGQ >> 1) >> 1)>
+__device__ __forceinline__ void fft_dit(float2* buf, const float2* tab, int tid) {
+  constexpr int n4 = LOGQ >> 1;
+  if constexpr (P == (n4 >> 1) && (n4 & 1)) fft_pass4<LOGQ, (LOGQ & 1), false>(buf, tab, tid);
+  if constexpr (P > 0) {
+    fft_pass16<LOGQ, LOGQ - 4 * P, false>(buf, tab, tid);
+    fft_dit<LOGQ, P - 1>(buf, tab, tid);
   }
 }
 
@@ -282,13 +362,18 @@ __device__ __forceinline__ float2 block_sum2(float2 v, float2* scratch, int tid)
 // the real part, head g0+1 in the imaginary part (each head's spectrum is made Hermitian first,
 // so its time-domain signal is real).  Time index a = Pb * a' + b: block b of Q = M / Pb samples
 // comes from the spectrum folded modulo Q with twiddle e^{j 2 pi k b / M}; softmax runs online
-// across the Pb blocks.
-__global__ __launch_bounds__(kFftThreads) void attn_fft_kernel(Params P, const float2* __restrict__ qc,
-                                                              float2* __restrict__ Pn, float scale,
-                                                              int pairs, int logQ) {
-  extern __shared__ float2 buf[];
+// across the Pb blocks (MULTI); with Pb == 1 nothing is carried between iterations.
+template <int LOGQ, bool MULTI>
+__global__ __launch_bounds__(kFftThreads, 4) void attn_fft_kernel(Params P, const float2* __restrict__ qc,
+                                                                 float2* __restrict__ Pn, float scale,
+                                                                 int pairs) {
+  extern __shared__ float2 smem[];
   __shared__ float2 scratch[kFftThreads / 64];
   const int tid = threadIdx.x;
+  constexpr int logQ = LOGQ;
+  constexpr int Q = 1 << LOGQ;
+  float2* buf = smem;                 // Q samples, padded
+  float2* tab = smem + Q + (Q >> 5);  // Q/8 + 1 twiddles
   const int pair = blockIdx.x % pairs;
   const int slice = blockIdx.x / pairs;
   const int spl = P.batch * P.n_kv;
@@ -297,90 +382,107 @@ __global__ __launch_bounds__(kFftThreads) void attn_fft_kernel(Params P, const f
   const LayerInfo L = P.layers[layer];
   const int g0 = pair * 2;
   const bool has1 = (g0 + 1) < P.G;
-  const int Q = 1 << logQ;
-  const uint32_t Pb = P.M >> logQ;
+  const uint32_t Pb = MULTI ? (P.M >> logQ) : 1u;
   const float2* q0 = qc + L.ws_off + ((int64_t)s * P.G + g0) * L.Bp;
   const float2* q1 = q0 + L.Bp;
-
-  float2 Y0[kFftNBT], Y1[kFftNBT], A0[kFftNBT], A1[kFftNBT];
-  uint32_t kk[kFftNBT];
+  const int32_t* bins = P.bins + L.bin_off;
+  const float* wts = P.weights + L.bin_off;
   const float gain = 0.5f * scale / (float)P.M;  // 0.5: each bin is split into k and its mirror
+
+  for (int m = tid; m <= (Q >> 3); m += kFftThreads) tab[m] = cis((uint32_t)m, (uint32_t)Q);
+
+  float2 A0[kFftNBT], A1[kFftNBT];  // running conj-less sums over blocks (MULTI only)
 #pragma unroll
-  for (int j = 0; j < kFftNBT; ++j) {
-    const int i = j * kFftThreads + tid;
-    Y0[j] = Y1[j] = A0[j] = A1[j] = make_float2(0.f, 0.f);
-    kk[j] = 0;
-    if (i < L.nb) {
-      kk[j] = (uint32_t)P.bins[L.bin_off + i];
-      const float w = P.weights[L.bin_off + i] * gain;
-      const float2 a = q0[i];
-      Y0[j] = make_float2(a.x * w, a.y * w);
-      if (has1) {
-        const float2 b = q1[i];
-        Y1[j] = make_float2(b.x * w, b.y * w);
-      }
-    }
-  }
-  float2 m = make_float2(-INFINITY, -INFINITY), Z = make_float2(0.f, 0.f);
+  for (int j = 0; j < kFftNBT; ++j) A0[j] = A1[j] = make_float2(0.f, 0.f);
+  float2 mx = make_float2(-INFINITY, -INFINITY), Z = make_float2(0.f, 0.f);
 
   for (uint32_t b = 0; b < Pb; ++b) {
-    for (int e = tid; e < Q; e += kFftThreads) buf[e] = make_float2(0.f, 0.f);
+    if (MULTI) {
+      // Keep per-bin inputs out of registers between iterations: they are re-read (L2 hits)
+      // instead of being hoisted out of the loop, which would cost ~100 VGPRs and an occupancy step.
+      asm volatile("" : "+s"(q0), "+s"(q1), "+s"(bins), "+s"(wts));
+    }
+    for (int e = tid; e < Q + (Q >> 5); e += kFftThreads) buf[e] = make_float2(0.f, 0.f);
     __syncthreads();
 #pragma unroll
     for (int j = 0; j < kFftNBT; ++j) {
-      if (j * kFftThreads + tid < L.nb) {
-        const float2 tw = cis(mulmod(kk[j], b, P.M, P.Mmask), P.M);
-        const float2 z0 = cmul(Y0[j], tw), z1 = cmul(Y1[j], tw);
-        const int r = kk[j] & (Q - 1), rm = (Q - r) & (Q - 1);
-        atomicAdd(&buf[r].x, z0.x - z1.y);   //      z0  + j z1
-        atomicAdd(&buf[r].y, z0.y + z1.x);
-        atomicAdd(&buf[rm].x, z0.x + z1.y);  // conj z0  + j conj z1
-        atomicAdd(&buf[rm].y, z1.x - z0.y);
+      const int i = j * kFftThreads + tid;
+      float2 twj = make_float2(1.f, 0.f);
+      if (i < L.nb) {
+        const uint32_t k = (uint32_t)bins[i];
+        if (MULTI) twj = cis_fast(mulmod(k, b, P.M, P.Mmask), P.M);
+        const float w = wts[i] * gain;
+        const float2 y0 = q0[i];
+        const float2 y1 = has1 ? q1[i] : make_float2(0.f, 0.f);
+        const float2 z0 = cmul(make_float2(y0.x * w, y0.y * w), twj);
+        const float2 z1 = cmul(make_float2(y1.x * w, y1.y * w), twj);
+        const int r = k & (Q - 1), rm = (Q - r) & (Q - 1);
+        atomicAdd(&buf[pad(r)].x, z0.x - z1.y);   //      z0  + j z1
+        atomicAdd(&buf[pad(r)].y, z0.y + z1.x);
+        atomicAdd(&buf[pad(rm)].x, z0.x + z1.y);  // conj z0  + j conj z1
+        atomicAdd(&buf[pad(rm)].y, z1.x - z0.y);
       }
     }
     __syncthreads();
-    ifft_dif(buf, logQ, tid);
+    ifft_dif<LOGQ>(buf, tab, tid);
 
+    // Softmax on sample pairs held in registers; the radix-2 stage that ends the inverse transform
+    // and the one that starts the forward transform (odd log2 Q) are applied right here.
     float2 v[kFftEPT];
     float2 lm = make_float2(-INFINITY, -INFINITY);
 #pragma unroll
-    for (int j = 0; j < kFftEPT; ++j) {
-      const int e = j * kFftThreads + tid;
-      if (e < Q) {
-        v[j] = buf[e];
-        lm.x = fmaxf(lm.x, v[j].x);
-        lm.y = fmaxf(lm.y, v[j].y);
+    for (int j = 0; j < kFftEPT / 2; ++j) {
+      const int bf = j * kFftThreads + tid;
+      if (2 * bf < Q) {
+        float2 a = buf[pad(2 * bf)], c = buf[pad(2 * bf + 1)];
+        if (logQ & 1) {
+          const float2 t = a;
+          a = cadd(t, c);
+          c = csub(t, c);
+        }
+        v[2 * j] = a;
+        v[2 * j + 1] = c;
+        lm.x = fmaxf(lm.x, fmaxf(a.x, c.x));
+        lm.y = fmaxf(lm.y, fmaxf(a.y, c.y));
       }
     }
     const float2 bm = block_max2(lm, scratch, tid);
-    const float2 mn = make_float2(fmaxf(m.x, bm.x), fmaxf(m.y, bm.y));
-    const float2 f = make_float2(__expf(m.x - mn.x), __expf(m.y - mn.y));  // exp(-inf) = 0 first time
-    m = mn;
+    const float2 mn = make_float2(fmaxf(mx.x, bm.x), fmaxf(mx.y, bm.y));
+    const float2 f = make_float2(__expf(mx.x - mn.x), __expf(mx.y - mn.y));  // exp(-inf) = 0 first time
+    mx = mn;
     float2 ls = make_float2(0.f, 0.f);
 #pragma unroll
-    for (int j = 0; j < kFftEPT; ++j) {
-      const int e = j * kFftThreads + tid;
-      if (e < Q) {
-        const float2 p = make_float2(__expf(v[j].x - mn.x), has1 ? __expf(v[j].y - mn.y) : 0.f);
-        ls.x += p.x;
-        ls.y += p.y;
-        buf[e] = p;
+    for (int j = 0; j < kFftEPT / 2; ++j) {
+      const int bf = j * kFftThreads + tid;
+      if (2 * bf < Q) {
+        float2 a = make_float2(__expf(v[2 * j].x - mn.x), has1 ? __expf(v[2 * j].y - mn.y) : 0.f);
+        float2 c = make_float2(__expf(v[2 * j + 1].x - mn.x), has1 ? __expf(v[2 * j + 1].y - mn.y) : 0.f);
+        ls.x += a.x + c.x;
+        ls.y += a.y + c.y;
+        if (logQ & 1) {
+          const float2 t = a;
+          a = cadd(t, c);
+          c = csub(t, c);
+        }
+        buf[pad(2 * bf)] = a;
+        buf[pad(2 * bf + 1)] = c;
       }
     }
-    const float2 bs = block_sum2(ls, scratch, tid);
+    const float2 bs = block_sum2(ls, scratch, tid);  // its barriers also publish the writes above
     Z = make_float2(Z.x * f.x + bs.x, Z.y * f.y + bs.y);
-    __syncthreads();
-    fft_dit(buf, logQ, tid);
+    fft_dit<LOGQ>(buf, tab, tid);
 #pragma unroll
     for (int j = 0; j < kFftNBT; ++j) {
-      if (j * kFftThreads + tid < L.nb) {
-        const float2 tw = cis(mulmod(kk[j], b, P.M, P.Mmask), P.M);
-        const int r = kk[j] & (Q - 1), rm = (Q - r) & (Q - 1);
-        const float2 w1 = buf[r], w2 = buf[rm];
+      const int i = j * kFftThreads + tid;
+      if (i < L.nb) {
+        const uint32_t k = (uint32_t)bins[i];
+        const int r = k & (Q - 1), rm = (Q - r) & (Q - 1);
+        const float2 w1 = buf[pad(r)], w2 = buf[pad(rm)];
         const float2 p0 = make_float2(0.5f * (w1.x + w2.x), 0.5f * (w1.y - w2.y));
         const float2 p1 = make_float2(0.5f * (w1.y + w2.y), 0.5f * (w2.x - w1.x));
-        A0[j] = cadd(make_float2(A0[j].x * f.x, A0[j].y * f.x), cmul(conjf2(tw), p0));
-        A1[j] = cadd(make_float2(A1[j].x * f.y, A1[j].y * f.y), cmul(conjf2(tw), p1));
+        const float2 twc = MULTI ? conjf2(cis_fast(mulmod(k, b, P.M, P.Mmask), P.M)) : make_float2(1.f, 0.f);
+        A0[j] = cadd(make_float2(A0[j].x * f.x, A0[j].y * f.x), cmul(twc, p0));
+        A1[j] = cadd(make_float2(A1[j].x * f.y, A1[j].y * f.y), cmul(twc, p1));
       }
     }
     __syncthreads();
@@ -395,7 +497,7 @@ __global__ __launch_bounds__(kFftThreads) void attn_fft_kernel(Params P, const f
     if (i < L.Bp) {  // padding entries are written as zeros: kernel C reads whole rows
       float2 r0 = make_float2(0.f, 0.f), r1 = r0;
       if (i < L.nb) {
-        const float w = P.weights[L.bin_off + i] * inv_M;
+        const float w = wts[i] * inv_M;
         const float c0 = w / Z.x;
         r0 = make_float2(A0[j].x * c0, -A0[j].y * c0);
         if (has1) {
@@ -524,16 +626,29 @@ static hipError_t launch_attn_t(const Params& P, const void* q, void* out, float
     while ((1u << logM) < P.M) ++logM;
     const int logQ = logM < kFftMaxLogQ ? logM : kFftMaxLogQ;
     const int pairs = (P.G + 1) / 2;
-    const size_t lds = sizeof(float2) << logQ;
-    static bool attr_set = false;  // raising the limit is idempotent; a race only repeats it
-    if (!attr_set) {
-      e = hipFuncSetAttribute((const void*)attn_fft_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
-                              (int)(sizeof(float2) << kFftMaxLogQ));
-      if (e != hipSuccess) return e;
-      attr_set = true;
+    const size_t lds = sizeof(float2) * (size_t)fft_lds_float2(logQ);
+    const uint32_t gridB = (uint32_t)((uint64_t)P.n_slices * pairs);
+#define IWDFT_FFT_CASE(LQ, MULTI)                                                                        \
+  {                                                                                                      \
+    static bool attr_set = false; /* raising the limit is idempotent; a race only repeats it */          \
+    if (!attr_set) {                                                                                     \
+      e = hipFuncSetAttribute((const void*)attn_fft_kernel<LQ, MULTI>,                                   \
+                              hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);                     \
+      if (e != hipSuccess) return e;                                                                     \
+      attr_set = true;                                                                                   \
+    }                                                                                                    \
+    attn_fft_kernel<LQ, MULTI><<<dim3(gridB), dim3(kFftThreads), lds, st>>>(P, qc, Pn, scale, pairs);    \
+  }
+    if (logM > logQ) IWDFT_FFT_CASE(kFftMaxLogQ, true)
+    else switch (logQ) {
+      case 8: IWDFT_FFT_CASE(8, false) break;
+      case 9: IWDFT_FFT_CASE(9, false) break;
+      case 10: IWDFT_FFT_CASE(10, false) break;
+      case 11: IWDFT_FFT_CASE(11, false) break;
+      case 12: IWDFT_FFT_CASE(12, false) break;
+      default: IWDFT_FFT_CASE(13, false) break;
     }
-    attn_fft_kernel<<<dim3((uint32_t)((uint64_t)P.n_slices * pairs)), dim3(kFftThreads), lds, st>>>(
-        P, qc, Pn, scale, pairs, logQ);
+#undef IWDFT_FFT_CASE
   } else {
     attn_direct_kernel<<<dim3((uint32_t)gridBd), dim3(kDirThreads), 0, st>>>(P, qc, Pn, scale, direct_scratch);
   }
