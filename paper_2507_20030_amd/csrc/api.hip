@@ -1,5 +1,6 @@
 // C ABI of libiwdft: descriptor validation, buffer layout, call ordering, error reporting.
 // All arithmetic lives in the kernels; this file only decides what to launch.
+#include <algorithm>
 #include <cmath>
 #include <cstdarg>
 #include <cstdio>
@@ -28,18 +29,20 @@ size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 
 struct Plan {  // byte offsets inside the two caller buffers, derived from a descriptor
   std::vector<LayerInfo> layers;
+  std::vector<uint16_t> fold;  // see Params::fold
   int64_t n_bins_total = 0;
   int64_t coef_total = 0;  // float2 per tensor
   int64_t ws_total = 0;    // float2 per workspace array
   int32_t G = 1, max_nb = 0, max_Bp = 0;
   bool use_fft = false;
-  size_t off_layers = 0, off_bins = 0, off_weights = 0, off_FK = 0, off_FV = 0, state_bytes = 0;
+  size_t off_layers = 0, off_bins = 0, off_weights = 0, off_fold = 0, off_FK = 0, off_FV = 0, state_bytes = 0;
   size_t off_qc = 0, off_Pn = 0, off_direct = 0, ws_bytes = 0;
 };
 
 // Largest problem the FFT attention kernel keeps in registers / LDS.
 constexpr int kFftMaxBins = 4096;
 constexpr uint32_t kFftMinM = 256;
+constexpr int64_t kFftMaxQ = 8192;  // longest transform the FFT attention kernel holds in LDS
 
 int make_plan(const iwdft_desc* d, Plan* pl) {
   if (!d) return fail(IWDFT_ERR_ARG, "desc is NULL");
@@ -90,7 +93,7 @@ int make_plan(const iwdft_desc* d, Plan* pl) {
     L.bin_off = (int32_t)b0;
     L.nb = (int32_t)(b1 - b0);
     L.Bp = (L.nb + kRowPad - 1) / kRowPad * kRowPad;
-    L.pad_ = 0;
+    L.fold_rounds = 0;
     L.coef_off = coef;
     L.ws_off = ws;
     coef += slices_per_layer * kHeadDim * L.Bp;
@@ -105,11 +108,37 @@ int make_plan(const iwdft_desc* d, Plan* pl) {
   const bool pow2 = (d->M & (d->M - 1)) == 0;
   pl->use_fft = pow2 && (uint64_t)d->M >= kFftMinM && pl->max_nb <= kFftMaxBins &&
                 !(d->flags & IWDFT_FLAG_DIRECT_SYNTHESIS);
+  pl->fold.assign((size_t)pl->n_bins_total, 0);
+  if (pl->use_fft) {
+    // The FFT attention kernel folds the sparse spectrum (each bin k and its mirror -k) modulo the
+    // transform length Q.  Entries that land on the same slot are added in separate rounds, so the
+    // kernel needs no atomics and sums in a fixed order: round = how many earlier entries of the
+    // layer already use that slot.
+    const int64_t Q = d->M < kFftMaxQ ? d->M : kFftMaxQ;
+    std::vector<uint16_t> cnt((size_t)Q);
+    for (int l = 0; l < d->n_layers && pl->use_fft; ++l) {
+      std::fill(cnt.begin(), cnt.end(), 0);
+      LayerInfo& L = pl->layers[l];
+      int rounds = 0;
+      for (int i = 0; i < L.nb; ++i) {
+        const int64_t k = d->bins[L.bin_off + i];
+        const int64_t r = k & (Q - 1), rm = (Q - r) & (Q - 1);
+        const int fd = cnt[r]++;
+        const int fm = cnt[rm]++;
+        if (fd > 255 || fm > 255) { pl->use_fft = false; break; }
+        pl->fold[L.bin_off + i] = (uint16_t)(fd | (fm << 8));
+        if (fd + 1 > rounds) rounds = fd + 1;
+        if (fm + 1 > rounds) rounds = fm + 1;
+      }
+      L.fold_rounds = rounds;
+    }
+  }
 
   size_t o = 0;
   pl->off_layers = o;  o = align256(o + sizeof(LayerInfo) * (size_t)d->n_layers);
   pl->off_bins = o;    o = align256(o + sizeof(int32_t) * (size_t)pl->n_bins_total);
   pl->off_weights = o; o = align256(o + sizeof(float) * (size_t)pl->n_bins_total);
+  pl->off_fold = o;    o = align256(o + sizeof(uint16_t) * (size_t)pl->n_bins_total);
   pl->off_FK = o;      o = align256(o + sizeof(float2) * (size_t)coef);
   pl->off_FV = o;      o = align256(o + sizeof(float2) * (size_t)coef);
   pl->state_bytes = o;
@@ -214,6 +243,9 @@ int iwdft_create(const iwdft_desc* desc, void* d_state, size_t state_bytes, void
                   hipMemcpyHostToDevice);
   if (e == hipSuccess)
     e = hipMemcpy(c->state + pl.off_weights, w.data(), sizeof(float) * w.size(), hipMemcpyHostToDevice);
+  if (e == hipSuccess)
+    e = hipMemcpy(c->state + pl.off_fold, pl.fold.data(), sizeof(uint16_t) * pl.fold.size(),
+                  hipMemcpyHostToDevice);
   if (e != hipSuccess) {
     delete c;
     return fail(IWDFT_ERR_HIP, "initialising the state buffer: %s", hipGetErrorString(e));
@@ -237,6 +269,7 @@ int iwdft_create(const iwdft_desc* desc, void* d_state, size_t state_bytes, void
   P.layers = (const LayerInfo*)(c->state + pl.off_layers);
   P.bins = (const int32_t*)(c->state + pl.off_bins);
   P.weights = (const float*)(c->state + pl.off_weights);
+  P.fold = (const uint16_t*)(c->state + pl.off_fold);
   P.FK = (float2*)(c->state + pl.off_FK);
   P.FV = (float2*)(c->state + pl.off_FV);
   c->T = 0;

@@ -175,7 +175,7 @@ __global__ __launch_bounds__(kOutThreads) void attn_out_kernel(Params P, const f
 
 // ------------------------------------------------------------------------------------- B (FFT)
 constexpr int kFftThreads = 512;
-constexpr int kFftNBT = 8;   // kept bins per thread                     (|B| <= 4096)
+constexpr int kFftNBT = 8;   // most kept bins per thread                (|B| <= 4096)
 constexpr int kFftEPT = 16;  // time samples per thread                  (Q   <= 8192)
 constexpr int kFftMaxLogQ = 13;
 
@@ -363,14 +363,15 @@ __device__ __forceinline__ float2 block_sum2(float2 v, float2* scratch, int tid)
 // so its time-domain signal is real).  Time index a = Pb * a' + b: block b of Q = M / Pb samples
 // comes from the spectrum folded modulo Q with twiddle e^{j 2 pi k b / M}; softmax runs online
 // across the Pb blocks (MULTI); with Pb == 1 nothing is carried between iterations.
-template <int LOGQ, bool MULTI>
+// Folding uses no atomics: entries that share a slot are added in successive rounds (host-made
+// schedule in P.fold), which also fixes the summation order.  NBT = kept bins per thread.
+template <int LOGQ, int NBT, bool MULTI>
 __global__ __launch_bounds__(kFftThreads, 4) void attn_fft_kernel(Params P, const float2* __restrict__ qc,
                                                                  float2* __restrict__ Pn, float scale,
                                                                  int pairs) {
   extern __shared__ float2 smem[];
   __shared__ float2 scratch[kFftThreads / 64];
   const int tid = threadIdx.x;
-  constexpr int logQ = LOGQ;
   constexpr int Q = 1 << LOGQ;
   float2* buf = smem;                 // Q samples, padded
   float2* tab = smem + Q + (Q >> 5);  // Q/8 + 1 twiddles
@@ -382,49 +383,84 @@ __global__ __launch_bounds__(kFftThreads, 4) void attn_fft_kernel(Params P, cons
   const LayerInfo L = P.layers[layer];
   const int g0 = pair * 2;
   const bool has1 = (g0 + 1) < P.G;
-  const uint32_t Pb = MULTI ? (P.M >> logQ) : 1u;
+  const uint32_t Pb = MULTI ? (P.M >> LOGQ) : 1u;
   const float2* q0 = qc + L.ws_off + ((int64_t)s * P.G + g0) * L.Bp;
-  const float2* q1 = q0 + L.Bp;
+  const float2* q1 = has1 ? q0 + L.Bp : q0;
   const int32_t* bins = P.bins + L.bin_off;
   const float* wts = P.weights + L.bin_off;
-  const float gain = 0.5f * scale / (float)P.M;  // 0.5: each bin is split into k and its mirror
+  const uint16_t* fold = P.fold + L.bin_off;
+  // log2(e) is folded into the scores so that softmax can use the bare exp2 instruction;
+  // 0.5: each bin is split into k and its mirror.
+  const float gain = 0.5f * 1.44269504088896341f * scale / (float)P.M;
 
   for (int m = tid; m <= (Q >> 3); m += kFftThreads) tab[m] = cis((uint32_t)m, (uint32_t)Q);
 
-  float2 A0[kFftNBT], A1[kFftNBT];  // running conj-less sums over blocks (MULTI only)
+  float2 A0[NBT], A1[NBT];  // running sums over blocks (MULTI) / the single result
+  uint32_t kk[NBT];
 #pragma unroll
-  for (int j = 0; j < kFftNBT; ++j) A0[j] = A1[j] = make_float2(0.f, 0.f);
+  for (int j = 0; j < NBT; ++j) {
+    A0[j] = A1[j] = make_float2(0.f, 0.f);
+    const int i = j * kFftThreads + tid;
+    kk[j] = (uint32_t)bins[i < L.nb ? i : L.nb - 1];
+  }
   float2 mx = make_float2(-INFINITY, -INFINITY), Z = make_float2(0.f, 0.f);
 
   for (uint32_t b = 0; b < Pb; ++b) {
     if (MULTI) {
-      // Keep per-bin inputs out of registers between iterations: they are re-read (L2 hits)
-      // instead of being hoisted out of the loop, which would cost ~100 VGPRs and an occupancy step.
-      asm volatile("" : "+s"(q0), "+s"(q1), "+s"(bins), "+s"(wts));
+      // Per-bin inputs are re-read every iteration (L2 hits) instead of being kept in ~50 VGPRs.
+      asm volatile("" : "+s"(q0), "+s"(q1), "+s"(wts), "+s"(fold));
     }
+    // The thread index is made opaque per iteration so that the address arithmetic of the six
+    // transform passes is recomputed (a few instructions) instead of being hoisted out of the
+    // block loop into ~40 long-lived registers.
+    int lt = tid;
+    if (MULTI) asm volatile("" : "+v"(lt));
     for (int e = tid; e < Q + (Q >> 5); e += kFftThreads) buf[e] = make_float2(0.f, 0.f);
     __syncthreads();
+    for (int round = 0; round < L.fold_rounds; ++round) {
+      // Loads are issued in groups (one latency per group, not per bin); MULTI uses smaller groups
+      // to stay inside its register budget.
+      constexpr int GRP = (MULTI && NBT > 4) ? 4 : NBT;
 #pragma unroll
-    for (int j = 0; j < kFftNBT; ++j) {
-      const int i = j * kFftThreads + tid;
-      float2 twj = make_float2(1.f, 0.f);
-      if (i < L.nb) {
-        const uint32_t k = (uint32_t)bins[i];
-        if (MULTI) twj = cis_fast(mulmod(k, b, P.M, P.Mmask), P.M);
-        const float w = wts[i] * gain;
-        const float2 y0 = q0[i];
-        const float2 y1 = has1 ? q1[i] : make_float2(0.f, 0.f);
-        const float2 z0 = cmul(make_float2(y0.x * w, y0.y * w), twj);
-        const float2 z1 = cmul(make_float2(y1.x * w, y1.y * w), twj);
-        const int r = k & (Q - 1), rm = (Q - r) & (Q - 1);
-        atomicAdd(&buf[pad(r)].x, z0.x - z1.y);   //      z0  + j z1
-        atomicAdd(&buf[pad(r)].y, z0.y + z1.x);
-        atomicAdd(&buf[pad(rm)].x, z0.x + z1.y);  // conj z0  + j conj z1
-        atomicAdd(&buf[pad(rm)].y, z1.x - z0.y);
+      for (int jb = 0; jb < NBT; jb += GRP) {
+        float ww[GRP];
+        float2 y0[GRP], y1[GRP];
+        uint32_t fr[GRP];
+#pragma unroll
+        for (int jj = 0; jj < GRP; ++jj) {
+          const int i = (jb + jj) * kFftThreads + tid;
+          const int ic = i < L.nb ? i : L.nb - 1;
+          ww[jj] = wts[ic] * gain;
+          y0[jj] = q0[ic];
+          y1[jj] = q1[ic];
+          fr[jj] = i < L.nb ? (uint32_t)fold[ic] : 0xffffu;  // 0xff: no round matches
+        }
+#pragma unroll
+        for (int jj = 0; jj < GRP; ++jj) {
+          const int j = jb + jj;
+          float2 twj = make_float2(1.f, 0.f);
+          if (MULTI) twj = cis_fast((kk[j] * b) & (P.M - 1u), P.M);
+          const float w = ww[jj];
+          const float2 z0 = cmul(make_float2(y0[jj].x * w, y0[jj].y * w), twj);
+          const float2 z1 =
+              has1 ? cmul(make_float2(y1[jj].x * w, y1[jj].y * w), twj) : make_float2(0.f, 0.f);
+          const int r = kk[j] & (Q - 1), rm = (Q - r) & (Q - 1);
+          if ((fr[jj] & 0xffu) == (uint32_t)round) {  //      z0  + j z1
+            float2 v = make_float2(z0.x - z1.y, z0.y + z1.x);
+            if (round) v = cadd(v, buf[pad(r)]);
+            buf[pad(r)] = v;
+          }
+          if ((fr[jj] >> 8) == (uint32_t)round) {     // conj z0  + j conj z1
+            float2 v = make_float2(z0.x + z1.y, z1.x - z0.y);
+            if (round) v = cadd(v, buf[pad(rm)]);
+            buf[pad(rm)] = v;
+          }
+        }
+        if (GRP < NBT) __builtin_amdgcn_sched_barrier(0);
       }
+      __syncthreads();
     }
-    __syncthreads();
-    ifft_dif<LOGQ>(buf, tab, tid);
+    ifft_dif<LOGQ>(buf, tab, lt);
 
     // Softmax on sample pairs held in registers; the radix-2 stage that ends the inverse transform
     // and the one that starts the forward transform (odd log2 Q) are applied right here.
@@ -435,7 +471,7 @@ __global__ __launch_bounds__(kFftThreads, 4) void attn_fft_kernel(Params P, cons
       const int bf = j * kFftThreads + tid;
       if (2 * bf < Q) {
         float2 a = buf[pad(2 * bf)], c = buf[pad(2 * bf + 1)];
-        if (logQ & 1) {
+        if (LOGQ & 1) {
           const float2 t = a;
           a = cadd(t, c);
           c = csub(t, c);
@@ -448,18 +484,20 @@ __global__ __launch_bounds__(kFftThreads, 4) void attn_fft_kernel(Params P, cons
     }
     const float2 bm = block_max2(lm, scratch, tid);
     const float2 mn = make_float2(fmaxf(mx.x, bm.x), fmaxf(mx.y, bm.y));
-    const float2 f = make_float2(__expf(mx.x - mn.x), __expf(mx.y - mn.y));  // exp(-inf) = 0 first time
+    const float2 f = make_float2(exp2f(mx.x - mn.x), exp2f(mx.y - mn.y));  // exp2(-inf) = 0 first time
     mx = mn;
     float2 ls = make_float2(0.f, 0.f);
 #pragma unroll
     for (int j = 0; j < kFftEPT / 2; ++j) {
       const int bf = j * kFftThreads + tid;
       if (2 * bf < Q) {
-        float2 a = make_float2(__expf(v[2 * j].x - mn.x), has1 ? __expf(v[2 * j].y - mn.y) : 0.f);
-        float2 c = make_float2(__expf(v[2 * j + 1].x - mn.x), has1 ? __expf(v[2 * j + 1].y - mn.y) : 0.f);
+        float2 a = make_float2(__builtin_amdgcn_exp2f(v[2 * j].x - mn.x),
+                               has1 ? __builtin_amdgcn_exp2f(v[2 * j].y - mn.y) : 0.f);
+        float2 c = make_float2(__builtin_amdgcn_exp2f(v[2 * j + 1].x - mn.x),
+                               has1 ? __builtin_amdgcn_exp2f(v[2 * j + 1].y - mn.y) : 0.f);
         ls.x += a.x + c.x;
         ls.y += a.y + c.y;
-        if (logQ & 1) {
+        if (LOGQ & 1) {
           const float2 t = a;
           a = cadd(t, c);
           c = csub(t, c);
@@ -470,19 +508,20 @@ __global__ __launch_bounds__(kFftThreads, 4) void attn_fft_kernel(Params P, cons
     }
     const float2 bs = block_sum2(ls, scratch, tid);  // its barriers also publish the writes above
     Z = make_float2(Z.x * f.x + bs.x, Z.y * f.y + bs.y);
-    fft_dit<LOGQ>(buf, tab, tid);
+    fft_dit<LOGQ>(buf, tab, lt);
 #pragma unroll
-    for (int j = 0; j < kFftNBT; ++j) {
-      const int i = j * kFftThreads + tid;
-      if (i < L.nb) {
-        const uint32_t k = (uint32_t)bins[i];
-        const int r = k & (Q - 1), rm = (Q - r) & (Q - 1);
-        const float2 w1 = buf[pad(r)], w2 = buf[pad(rm)];
-        const float2 p0 = make_float2(0.5f * (w1.x + w2.x), 0.5f * (w1.y - w2.y));
-        const float2 p1 = make_float2(0.5f * (w1.y + w2.y), 0.5f * (w2.x - w1.x));
-        const float2 twc = MULTI ? conjf2(cis_fast(mulmod(k, b, P.M, P.Mmask), P.M)) : make_float2(1.f, 0.f);
+    for (int j = 0; j < NBT; ++j) {
+      const int r = kk[j] & (Q - 1), rm = (Q - r) & (Q - 1);
+      const float2 w1 = buf[pad(r)], w2 = buf[pad(rm)];
+      const float2 p0 = make_float2(0.5f * (w1.x + w2.x), 0.5f * (w1.y - w2.y));
+      const float2 p1 = make_float2(0.5f * (w1.y + w2.y), 0.5f * (w2.x - w1.x));
+      if (MULTI) {
+        const float2 twc = conjf2(cis_fast((kk[j] * b) & (P.M - 1u), P.M));
         A0[j] = cadd(make_float2(A0[j].x * f.x, A0[j].y * f.x), cmul(twc, p0));
         A1[j] = cadd(make_float2(A1[j].x * f.y, A1[j].y * f.y), cmul(twc, p1));
+      } else {
+        A0[j] = p0;
+        A1[j] = p1;
       }
     }
     __syncthreads();
@@ -491,19 +530,16 @@ __global__ __launch_bounds__(kFftThreads, 4) void attn_fft_kernel(Params P, cons
   float2* o0 = Pn + L.ws_off + ((int64_t)s * P.G + g0) * L.Bp;
   float2* o1 = o0 + L.Bp;
   const float inv_M = 1.0f / (float)P.M;
+  const float iz0 = inv_M / Z.x, iz1 = has1 ? inv_M / Z.y : 0.f;
 #pragma unroll
-  for (int j = 0; j < kFftNBT; ++j) {
+  for (int j = 0; j < NBT; ++j) {
     const int i = j * kFftThreads + tid;
     if (i < L.Bp) {  // padding entries are written as zeros: kernel C reads whole rows
       float2 r0 = make_float2(0.f, 0.f), r1 = r0;
       if (i < L.nb) {
-        const float w = wts[i] * inv_M;
-        const float c0 = w / Z.x;
-        r0 = make_float2(A0[j].x * c0, -A0[j].y * c0);
-        if (has1) {
-          const float c1 = w / Z.y;
-          r1 = make_float2(A1[j].x * c1, -A1[j].y * c1);
-        }
+        const float w = wts[i];
+        r0 = make_float2(A0[j].x * (w * iz0), -A0[j].y * (w * iz0));
+        r1 = make_float2(A1[j].x * (w * iz1), -A1[j].y * (w * iz1));
       }
       o0[i] = r0;
       if (has1) o1[i] = r1;
@@ -628,26 +664,34 @@ static hipError_t launch_attn_t(const Params& P, const void* q, void* out, float
     const int pairs = (P.G + 1) / 2;
     const size_t lds = sizeof(float2) * (size_t)fft_lds_float2(logQ);
     const uint32_t gridB = (uint32_t)((uint64_t)P.n_slices * pairs);
-#define IWDFT_FFT_CASE(LQ, MULTI)                                                                        \
+    const int per_thread = (P.max_Bp + kFftThreads - 1) / kFftThreads;  // <= 8 (checked at create)
+#define IWDFT_FFT_CASE(LQ, NBT, MULTI)                                                                   \
   {                                                                                                      \
     static bool attr_set = false; /* raising the limit is idempotent; a race only repeats it */          \
     if (!attr_set) {                                                                                     \
-      e = hipFuncSetAttribute((const void*)attn_fft_kernel<LQ, MULTI>,                                   \
+      e = hipFuncSetAttribute((const void*)attn_fft_kernel<LQ, NBT, MULTI>,                              \
                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);                     \
       if (e != hipSuccess) return e;                                                                     \
       attr_set = true;                                                                                   \
     }                                                                                                    \
-    attn_fft_kernel<LQ, MULTI><<<dim3(gridB), dim3(kFftThreads), lds, st>>>(P, qc, Pn, scale, pairs);    \
+    attn_fft_kernel<LQ, NBT, MULTI><<<dim3(gridB), dim3(kFftThreads), lds, st>>>(P, qc, Pn, scale, pairs); \
   }
-    if (logM > logQ) IWDFT_FFT_CASE(kFftMaxLogQ, true)
+#define IWDFT_FFT_NBT(LQ, MULTI)                                                                         \
+  {                                                                                                      \
+    if (per_thread <= 2) IWDFT_FFT_CASE(LQ, 2, MULTI)                                                    \
+    else if (per_thread <= 4) IWDFT_FFT_CASE(LQ, 4, MULTI)                                               \
+    else IWDFT_FFT_CASE(LQ, 8, MULTI)                                                                    \
+  }
+    if (logM > logQ) IWDFT_FFT_NBT(kFftMaxLogQ, true)
     else switch (logQ) {
-      case 8: IWDFT_FFT_CASE(8, false) break;
-      case 9: IWDFT_FFT_CASE(9, false) break;
-      case 10: IWDFT_FFT_CASE(10, false) break;
-      case 11: IWDFT_FFT_CASE(11, false) break;
-      case 12: IWDFT_FFT_CASE(12, false) break;
-      default: IWDFT_FFT_CASE(13, false) break;
+      case 8: IWDFT_FFT_CASE(8, 8, false) break;
+      case 9: IWDFT_FFT_CASE(9, 8, false) break;
+      case 10: IWDFT_FFT_CASE(10, 8, false) break;
+      case 11: IWDFT_FFT_CASE(11, 8, false) break;
+      case 12: IWDFT_FFT_CASE(12, 8, false) break;
+      default: IWDFT_FFT_NBT(13, false) break;
     }
+#undef IWDFT_FFT_NBT
 #undef IWDFT_FFT_CASE
   } else {
     attn_direct_kernel<<<dim3((uint32_t)gridBd), dim3(kDirThreads), 0, st>>>(P, qc, Pn, scale, direct_scratch);

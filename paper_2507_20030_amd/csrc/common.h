@@ -14,7 +14,7 @@ struct LayerInfo {
   int32_t bin_off;   // first entry of this layer in the bins / weights arrays
   int32_t nb;        // number of kept bins |B_l|
   int32_t Bp;        // nb rounded up to kRowPad: length of one coefficient row (in float2)
-  int32_t pad_;
+  int32_t fold_rounds;  // largest number of spectrum entries that fold onto one FFT slot (FFT attention)
   int64_t coef_off;  // float2 offset of the layer's first slice plane inside FK / FV
   int64_t ws_off;    // float2 offset of the layer's first (slice, query-head) row in qc / Pn
 };
@@ -39,6 +39,7 @@ struct Params {
   const LayerInfo* layers;
   const int32_t* bins;
   const float* weights;
+  const uint16_t* fold;  // per kept bin: low byte = round of its direct slot, high byte = round of its mirror slot
   float2* FK;
   float2* FV;
 };
