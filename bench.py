@@ -32,6 +32,8 @@ def main():
     ap.add_argument("--config", default="cfg2")
     ap.add_argument("--decode-steps", type=int, default=None, help="override the workload's decode steps")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="only run a plain 1 GiB device copy (reference for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE)")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on ONE GPU; --gpus N with N > 1 is not supported "
@@ -41,6 +43,15 @@ def main():
     import torch
     from paper_2507_20030_amd import binding as B
     from paper_2507_20030_amd import workload as wl
+
+    if args.copy_calibration:
+        a = torch.ones(1 << 28, dtype=torch.float32, device="cuda:0")  # 1 GiB
+        b = torch.empty_like(a)
+        for _ in range(3):
+            b.copy_(a)
+        torch.cuda.synchronize()
+        print(json.dumps({"copy_calibration_bytes_read": a.numel() * 4, "copy_calibration_bytes_written": a.numel() * 4}))
+        return
 
     cfg = wl.CONFIGS[args.config]
     dsteps = cfg.steps if args.decode_steps is None else args.decode_steps
