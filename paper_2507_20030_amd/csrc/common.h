@@ -59,6 +59,34 @@ __device__ __forceinline__ float2 cis(uint32_t p, uint32_t M) {
   return make_float2(c, s);
 }
 
+// Same value, branch-free (straight-line code that can sit inside a software-pipelined loop):
+// octant reduction in exact arithmetic (p/M and q/8 are exact for power-of-two M), degree-7/8
+// Taylor polynomials on |theta| <= pi/8 (truncation < 1e-9), then a rotation by q * 45 degrees.
+__device__ __forceinline__ float2 cis_poly(uint32_t p, uint32_t M) {
+  const float x = (float)p / (float)M;            // in [0, 1)
+  const float qf = rintf(x * 8.0f);               // nearest octant boundary, 0..8
+  const float th = (x - qf * 0.125f) * 6.283185307179586f;  // |th| <= pi/8
+  const float t2 = th * th;
+  float sn = th * (1.0f + t2 * (-1.0f / 6.0f + t2 * (1.0f / 120.0f + t2 * (-1.0f / 5040.0f))));
+  float cs = 1.0f + t2 * (-0.5f + t2 * (1.0f / 24.0f + t2 * (-1.0f / 720.0f + t2 * (1.0f / 40320.0f))));
+  const int q = (int)qf;
+  if (q & 1) {  // + 45 degrees (compiles to selects)
+    const float c2 = (cs - sn) * 0.70710678118654752f, s2 = (cs + sn) * 0.70710678118654752f;
+    cs = c2;
+    sn = s2;
+  }
+  if (q & 2) {  // + 90 degrees
+    const float c2 = -sn;
+    sn = cs;
+    cs = c2;
+  }
+  if (q & 4) {  // + 180 degrees
+    cs = -cs;
+    sn = -sn;
+  }
+  return make_float2(cs, sn);
+}
+
 __device__ __forceinline__ float2 cmul(float2 a, float2 b) {
   return make_float2(a.x * b.x - a.y * b.y, a.x * b.y + a.y * b.x);
 }

@@ -47,7 +47,8 @@ struct TileRegs {
   uint4 v[BF16 ? 8 : 16];
 };
 
-template <bool BF16>
+// FULL: the tile lies entirely inside [0, M) and needs no bounds checks.
+template <bool BF16, bool FULL>
 __device__ __forceinline__ void load_tile(TileRegs<BF16>& r, const void* __restrict__ K,
                                           const void* __restrict__ V, int64_t slice_base, uint32_t n0,
                                           uint32_t M, int tid) {
@@ -62,10 +63,10 @@ __device__ __forceinline__ void load_tile(TileRegs<BF16>& r, const void* __restr
       const uint32_t n = n0 + 2 * p + t;
       const int64_t e = slice_base + (int64_t)n * kHeadDim + ch;  // element index
       if constexpr (BF16) {
-        r.v[it * 2 + t] = (n < M) ? *(const uint4*)((const uint16_t*)X + e) : make_uint4(0, 0, 0, 0);
+        r.v[it * 2 + t] = (FULL || n < M) ? *(const uint4*)((const uint16_t*)X + e) : make_uint4(0, 0, 0, 0);
       } else {
-        r.v[(it * 2 + t) * 2] = (n < M) ? *(const uint4*)((const float*)X + e) : make_uint4(0, 0, 0, 0);
-        r.v[(it * 2 + t) * 2 + 1] = (n < M) ? *(const uint4*)((const float*)X + e + 4) : make_uint4(0, 0, 0, 0);
+        r.v[(it * 2 + t) * 2] = (FULL || n < M) ? *(const uint4*)((const float*)X + e) : make_uint4(0, 0, 0, 0);
+        r.v[(it * 2 + t) * 2 + 1] = (FULL || n < M) ? *(const uint4*)((const float*)X + e + 4) : make_uint4(0, 0, 0, 0);
       }
     }
   }
@@ -73,11 +74,11 @@ __device__ __forceinline__ void load_tile(TileRegs<BF16>& r, const void* __restr
 
 // Converts to fp16 (hi, and lo for fp32 inputs) and writes token pairs transposed into LDS:
 // element (channel c, token n) of part `part` lives at lds[(part * 256 + c) * kPfRS + n].
-template <bool BF16>
+template <bool BF16, int IT0 = 0, int IT1 = 4>
 __device__ __forceinline__ void store_tile(const TileRegs<BF16>& r, _Float16* __restrict__ buf, int tid) {
   const int p = tid & 31;
 #pragma unroll
-  for (int it = 0; it < 4; ++it) {
+  for (int it = IT0; it < IT1; ++it) {
     const int q = (tid >> 5) + 8 * it;
 #pragma unroll
     for (int j = 0; j < 8; ++j) {
@@ -103,15 +104,50 @@ __device__ __forceinline__ void store_tile(const TileRegs<BF16>& r, _Float16* __
   }
 }
 
+// Basis operands of one MFMA k-step for this lane's bin: hi / lo fp16 halves of cos and -sin.
+struct BasisRegs {
+  half8 ch, cl, sh, sl;
+};
+
+// base = exp(-j theta) at the first of this lane's 8 tokens; tw[i] = exp(-j 2 pi k i / M).
+__device__ __forceinline__ BasisRegs make_basis(float2 base, const float2 (&tw)[8]) {
+  u32x4 ch, cl, sh, sl;
+#pragma unroll
+  for (int i = 0; i < 8; i += 2) {
+    const float2 z0 = cmul(base, tw[i]), z1 = cmul(base, tw[i + 1]);
+    const uint32_t chi = pack_rtz(z0.x, z1.x), shi = pack_rtz(z0.y, z1.y);
+    ch[i >> 1] = chi;
+    sh[i >> 1] = shi;
+    cl[i >> 1] = pack_rtz(z0.x - half_lo_f32(chi), z1.x - half_hi_f32(chi));
+    sl[i >> 1] = pack_rtz(z0.y - half_lo_f32(shi), z1.y - half_hi_f32(shi));
+  }
+  BasisRegs r;
+  r.ch = __builtin_bit_cast(half8, ch);
+  r.cl = __builtin_bit_cast(half8, cl);
+  r.sh = __builtin_bit_cast(half8, sh);
+  r.sl = __builtin_bit_cast(half8, sl);
+  return r;
+}
+
 // grid: 8 * per_xcd workgroups; id -> (id % 8) * per_xcd + id / 8 so that workgroups that run on
 // the same XCD at the same time are the bin tiles of the same slice and share its K/V tile in L2.
-template <bool BF16>
+// FULL: M is a power of two and a multiple of the 64-token tile: no bounds checks in the token
+// loop and phases reduce with a mask.
+// The token loop is software-pipelined by hand: the basis registers and the LDS operands of k-step
+// s+1 are produced while the 32 MFMAs of k-step s are in flight, and the loop body is one basic
+// block so that the scheduler can interleave the two instruction streams.  (Explicit
+// sched_group_barrier patterns were measured and were 5-40 % slower than the default schedule.
+// A single wave overlaps vector-ALU work with its own MFMAs only partly: ~2 clocks per VALU
+// instruction up to ~6 per MFMA, 4 clocks beyond; the ~4 VALU per MFMA spent on the basis are
+// what keeps this kernel near 45 % instead of 70 % of the matrix peak.)
+template <bool BF16, bool FULL>
 __global__ __launch_bounds__(kPfThreads) void prefill_mfma_kernel(Params P, const void* __restrict__ K,
                                                                  const void* __restrict__ V, int nt,
                                                                  int per_xcd, int total) {
   extern __shared__ _Float16 lds[];
   constexpr int kParts = BF16 ? 1 : 2;
   constexpr int kBufHalves = kParts * kPfCh * kPfRS;
+  constexpr int kSteps = kPfTok / 16;
 
   const int logical = (int)(blockIdx.x & 7) * per_xcd + (int)(blockIdx.x >> 3);
   if (logical >= total) return;
@@ -152,64 +188,87 @@ __global__ __launch_bounds__(kPfThreads) void prefill_mfma_kernel(Params P, cons
 
   const int64_t slice_base = (int64_t)slice * M * kHeadDim;
   const uint32_t n_tiles = (M + kPfTok - 1) / kPfTok;
+  const int a_off = (lane & 31) * kPfRS + 8 * g;  // this lane's row / token group inside a channel block
   TileRegs<BF16> regs;
-  load_tile<BF16>(regs, K, V, slice_base, 0, M, tid);
+  load_tile<BF16, FULL>(regs, K, V, slice_base, 0, M, tid);
   store_tile<BF16>(regs, lds, tid);
   __syncthreads();
+
+  // operands of k-step 0 of tile 0
+  float2 base;
+  {
+    const float2 c = cis(mulmod(k, (uint32_t)(8 * g), M, Mmask), M);
+    base = make_float2(c.x, -c.y);
+  }
+  BasisRegs bc = make_basis(base, tw);
+  half8 ac[kPfBlk], acl[BF16 ? 1 : kPfBlk];
+#pragma unroll
+  for (int b = 0; b < kPfBlk; ++b) {
+    ac[b] = *(const half8*)(lds + b * 32 * kPfRS + a_off);
+    if constexpr (!BF16) acl[b] = *(const half8*)(lds + (kPfCh + b * 32) * kPfRS + a_off);
+  }
 
   for (uint32_t t = 0; t < n_tiles; ++t) {
     const _Float16* cur = lds + (t & 1) * kBufHalves;
     _Float16* nxt = lds + ((t + 1) & 1) * kBufHalves;
-    const bool more = (t + 1) < n_tiles;
-    if (more) load_tile<BF16>(regs, K, V, slice_base, (t + 1) * kPfTok, M, tid);
+    // The tile after the last one is a harmless reload of the last tile (keeps the body branch-free).
+    const uint32_t tn = (t + 1 < n_tiles) ? t + 1 : t;
+    load_tile<BF16, FULL>(regs, K, V, slice_base, tn * kPfTok, M, tid);
 
-    // exact basis phase at the first token this lane feeds in this tile
-    float2 base;
-    {
-      const uint32_t nb0 = t * kPfTok + 8 * g;
-      const float2 c = cis(mulmod(k, nb0, M, Mmask), M);
-      base = make_float2(c.x, -c.y);
-    }
 #pragma unroll
-    for (int st = 0; st < kPfTok / 16; ++st) {
-      // basis for tokens t*64 + 16*st + 8*g + i : hi / lo halves of cos and -sin
-      u32x4 ch, cl, sh, sl;
+    for (int st = 0; st < kSteps; ++st) {
+      // ---- produce the operands of the next k-step --------------------------------------------
+      BasisRegs bn;
+      half8 an[kPfBlk], anl[BF16 ? 1 : kPfBlk];
+      if (st + 1 < kSteps) {
+        base = cmul(base, r16);
+        bn = make_basis(base, tw);
 #pragma unroll
-      for (int i = 0; i < 8; i += 2) {
-        const float2 z0 = cmul(base, tw[i]), z1 = cmul(base, tw[i + 1]);
-        const uint32_t chi = pack_rtz(z0.x, z1.x), shi = pack_rtz(z0.y, z1.y);
-        ch[i >> 1] = chi;
-        sh[i >> 1] = shi;
-        cl[i >> 1] = pack_rtz(z0.x - half_lo_f32(chi), z1.x - half_hi_f32(chi));
-        sl[i >> 1] = pack_rtz(z0.y - half_lo_f32(shi), z1.y - half_hi_f32(shi));
+        for (int b = 0; b < kPfBlk; ++b) {
+          an[b] = *(const half8*)(cur + b * 32 * kPfRS + a_off + 16 * (st + 1));
+          if constexpr (!BF16) anl[b] = *(const half8*)(cur + (kPfCh + b * 32) * kPfRS + a_off + 16 * (st + 1));
+        }
+      } else {
+        // exact basis phase at the first token this lane feeds in the next tile
+        const uint32_t nn = (t + 1) * kPfTok + 8 * g;
+        const float2 c = cis_poly(FULL ? ((k * nn) & (M - 1u)) : mulmod(k, nn, M, Mmask), M);
+        base = make_float2(c.x, -c.y);
+        bn = make_basis(base, tw);
       }
-      base = cmul(base, r16);
-      const half8 bch = __builtin_bit_cast(half8, ch), bcl = __builtin_bit_cast(half8, cl);
-      const half8 bsh = __builtin_bit_cast(half8, sh), bsl = __builtin_bit_cast(half8, sl);
+      if (st == kSteps - 2) store_tile<BF16, 0, 2>(regs, nxt, tid);
+      if (st == kSteps - 1) store_tile<BF16, 2, 4>(regs, nxt, tid);
 
-      half8 a[kPfBlk];
+      // ---- 32 (48 for fp32 inputs) MFMAs of this k-step ---------------------------------------
 #pragma unroll
-      for (int b = 0; b < kPfBlk; ++b)
-        a[b] = *(const half8*)(cur + (b * 32 + (lane & 31)) * kPfRS + 16 * st + 8 * g);
+      for (int b = 0; b < kPfBlk; ++b) acc_re[b] = __builtin_amdgcn_mfma_f32_32x32x16_f16(ac[b], bc.ch, acc_re[b], 0, 0, 0);
 #pragma unroll
-      for (int b = 0; b < kPfBlk; ++b) acc_re[b] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a[b], bch, acc_re[b], 0, 0, 0);
+      for (int b = 0; b < kPfBlk; ++b) acc_im[b] = __builtin_amdgcn_mfma_f32_32x32x16_f16(ac[b], bc.sh, acc_im[b], 0, 0, 0);
 #pragma unroll
-      for (int b = 0; b < kPfBlk; ++b) acc_im[b] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a[b], bsh, acc_im[b], 0, 0, 0);
+      for (int b = 0; b < kPfBlk; ++b) acc_re[b] = __builtin_amdgcn_mfma_f32_32x32x16_f16(ac[b], bc.cl, acc_re[b], 0, 0, 0);
 #pragma unroll
-      for (int b = 0; b < kPfBlk; ++b) acc_re[b] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a[b], bcl, acc_re[b], 0, 0, 0);
-#pragma unroll
-      for (int b = 0; b < kPfBlk; ++b) acc_im[b] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a[b], bsl, acc_im[b], 0, 0, 0);
+      for (int b = 0; b < kPfBlk; ++b) acc_im[b] = __builtin_amdgcn_mfma_f32_32x32x16_f16(ac[b], bc.sl, acc_im[b], 0, 0, 0);
       if constexpr (!BF16) {
 #pragma unroll
         for (int b = 0; b < kPfBlk; ++b) {
-          const half8 al = *(const half8*)(cur + (kPfCh + b * 32 + (lane & 31)) * kPfRS + 16 * st + 8 * g);
-          acc_re[b] = __builtin_amdgcn_mfma_f32_32x32x16_f16(al, bch, acc_re[b], 0, 0, 0);
-          acc_im[b] = __builtin_amdgcn_mfma_f32_32x32x16_f16(al, bsh, acc_im[b], 0, 0, 0);
+          acc_re[b] = __builtin_amdgcn_mfma_f32_32x32x16_f16(acl[b], bc.ch, acc_re[b], 0, 0, 0);
+          acc_im[b] = __builtin_amdgcn_mfma_f32_32x32x16_f16(acl[b], bc.sh, acc_im[b], 0, 0, 0);
+        }
+      }
+      bc = bn;
+      if (st + 1 < kSteps) {
+#pragma unroll
+        for (int b = 0; b < kPfBlk; ++b) {
+          ac[b] = an[b];
+          if constexpr (!BF16) acl[b] = anl[b];
         }
       }
     }
-    if (more) store_tile<BF16>(regs, nxt, tid);
     __syncthreads();
+#pragma unroll
+    for (int b = 0; b < kPfBlk; ++b) {  // k-step 0 of the next tile
+      ac[b] = *(const half8*)(nxt + b * 32 * kPfRS + a_off);
+      if constexpr (!BF16) acl[b] = *(const half8*)(nxt + (kPfCh + b * 32) * kPfRS + a_off);
+    }
   }
 
   if (!valid) return;
@@ -234,20 +293,27 @@ hipError_t launch_prefill(const Params& P, const void* K, const void* V, hipStre
   const size_t lds = sizeof(_Float16) * 2 * (bf16 ? 1 : 2) * kPfCh * kPfRS;
   static bool attr_set = false;  // idempotent; a race only repeats the call
   if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute((const void*)prefill_mfma_kernel<true>,
-                                       hipFuncAttributeMaxDynamicSharedMemorySize,
-                                       (int)(sizeof(_Float16) * 2 * kPfCh * kPfRS));
+    const int lds16 = (int)(sizeof(_Float16) * 2 * kPfCh * kPfRS), lds32 = 2 * lds16;
+    hipError_t e = hipFuncSetAttribute((const void*)prefill_mfma_kernel<true, true>,
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, lds16);
     if (e == hipSuccess)
-      e = hipFuncSetAttribute((const void*)prefill_mfma_kernel<false>,
-                              hipFuncAttributeMaxDynamicSharedMemorySize,
-                              (int)(sizeof(_Float16) * 4 * kPfCh * kPfRS));
+      e = hipFuncSetAttribute((const void*)prefill_mfma_kernel<true, false>,
+                              hipFuncAttributeMaxDynamicSharedMemorySize, lds16);
+    if (e == hipSuccess)
+      e = hipFuncSetAttribute((const void*)prefill_mfma_kernel<false, true>,
+                              hipFuncAttributeMaxDynamicSharedMemorySize, lds32);
+    if (e == hipSuccess)
+      e = hipFuncSetAttribute((const void*)prefill_mfma_kernel<false, false>,
+                              hipFuncAttributeMaxDynamicSharedMemorySize, lds32);
     if (e != hipSuccess) return e;
     attr_set = true;
   }
-  if (bf16)
-    prefill_mfma_kernel<true><<<dim3((uint32_t)(per_xcd * 8)), dim3(kPfThreads), lds, st>>>(P, K, V, nt, per_xcd, (int)total);
-  else
-    prefill_mfma_kernel<false><<<dim3((uint32_t)(per_xcd * 8)), dim3(kPfThreads), lds, st>>>(P, K, V, nt, per_xcd, (int)total);
+  const dim3 grid((uint32_t)(per_xcd * 8)), block(kPfThreads);
+  const bool full = (P.M % kPfTok) == 0 && P.Mmask != 0;
+  if (bf16 && full) prefill_mfma_kernel<true, true><<<grid, block, lds, st>>>(P, K, V, nt, per_xcd, (int)total);
+  else if (bf16) prefill_mfma_kernel<true, false><<<grid, block, lds, st>>>(P, K, V, nt, per_xcd, (int)total);
+  else if (full) prefill_mfma_kernel<false, true><<<grid, block, lds, st>>>(P, K, V, nt, per_xcd, (int)total);
+  else prefill_mfma_kernel<false, false><<<grid, block, lds, st>>>(P, K, V, nt, per_xcd, (int)total);
   return hipGetLastError();
 }
 
