@@ -372,8 +372,11 @@ __device__ __forceinline__ float2 block_sum2(float2 v, float2* scratch, int tid)
 // across the Pb blocks (MULTI); with Pb == 1 nothing is carried between iterations.
 // Folding uses no atomics: entries that share a slot are added in successive rounds (host-made
 // schedule in P.fold), which also fixes the summation order.  NBT = kept bins per thread.
+// Register budget: 128 VGPRs (two workgroups per CU) except for the multi-block kernel with 8 bins
+// per thread, whose per-bin inputs and running sums (~80 registers) then spill; that one gets 256
+// VGPRs and one workgroup per CU (measured 1.5x faster than spilling at two per CU).
 template <int LOGQ, int NBT, bool MULTI>
-__global__ __launch_bounds__(kFftThreads, 4) void attn_fft_kernel(Params P, const float2* __restrict__ qc,
+__global__ __launch_bounds__(kFftThreads, (MULTI && NBT > 4) ? 2 : 4) void attn_fft_kernel(Params P, const float2* __restrict__ qc,
                                                                  float2* __restrict__ Pn, float scale,
                                                                  int pairs) {
   extern __shared__ float2 smem[];
@@ -412,8 +415,9 @@ __global__ __launch_bounds__(kFftThreads, 4) void attn_fft_kernel(Params P, cons
   }
   float2 mx = make_float2(-INFINITY, -INFINITY), Z = make_float2(0.f, 0.f);
 
+  constexpr bool kTight = MULTI && NBT <= 4;  // 128-VGPR multi-block variant: fight hoisting
   for (uint32_t b = 0; b < Pb; ++b) {
-    if (MULTI) {
+    if (kTight) {
       // Per-bin inputs are re-read every iteration (L2 hits) instead of being kept in ~50 VGPRs.
       asm volatile("" : "+s"(q0), "+s"(q1), "+s"(wts), "+s"(fold));
     }
@@ -421,13 +425,12 @@ __global__ __launch_bounds__(kFftThreads, 4) void attn_fft_kernel(Params P, cons
     // transform passes is recomputed (a few instructions) instead of being hoisted out of the
     // block loop into ~40 long-lived registers.
     int lt = tid;
-    if (MULTI) asm volatile("" : "+v"(lt));
+    if (kTight) asm volatile("" : "+v"(lt));
     for (int e = tid; e < Q + (Q >> 5); e += kFftThreads) buf[e] = make_float2(0.f, 0.f);
     __syncthreads();
     for (int round = 0; round < L.fold_rounds; ++round) {
-      // Loads are issued in groups (one latency per group, not per bin); MULTI uses smaller groups
-      // to stay inside its register budget.
-      constexpr int GRP = (MULTI && NBT > 4) ? 4 : NBT;
+      // All loads of a group are issued before the first use (one latency per group, not per bin).
+      constexpr int GRP = NBT;
 #pragma unroll
       for (int jb = 0; jb < NBT; jb += GRP) {
         float ww[GRP];
