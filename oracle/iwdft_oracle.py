@@ -35,7 +35,7 @@ import numpy as np
 __all__ = [
     "W", "prefill", "append", "append_many", "slot", "fold_to_slots",
     "closed_form", "reconstruct", "attention", "decode_attention",
-    "stream_decode",
+    "stream_decode", "windowed_attention", "windowed_stream_decode",
 ]
 
 
@@ -163,3 +163,46 @@ def stream_decode(K0, V0, bins, k_new, v_new, q_new, weights=None, scale=None):
         T += 1
         outs.append(decode_attention(q_new[i], SK, SV, T, M, bins, weights, scale))
     return np.stack(outs) if outs else np.zeros((0,) + q_new.shape[1:]), SK, SV, T
+
+
+def windowed_attention(q, sinkK, sinkV, SK, SV, T, M, bins, recK, recV, weights=None, scale=None):
+    """Attention over the assembled cache of Eq. kv-concat: [sink tokens, reconstructed
+    middle segment, recent tokens] (the V line of that equation prints K~ where V~ is meant)."""
+    Kt = reconstruct(SK, T, M, bins, weights)
+    Vt = reconstruct(SV, T, M, bins, weights)
+    K = np.concatenate([sinkK, Kt, recK], axis=0)
+    V = np.concatenate([sinkV, Vt, recV], axis=0)
+    return attention(q, K, V, scale)
+
+
+def windowed_stream_decode(K0, V0, S, R, bins, k_new, v_new, q_new, weights=None, scale=None):
+    """The decoding stage of Sec. 4.2.2 with S sink and R recent tokens kept exact.
+
+    K0, V0: [N, d] prefill cache, N = S + M + R; the middle M tokens are transformed
+    (Eq. prefill-dft).  Per step: the new token (k_i, v_i) joins the recent window, the
+    token that ages out of it is absorbed by the IWDFT update (Eq. update-iwdft), and the
+    query attends over [sink, reconstruction, recent] (Eq. kv-concat, Eq. kv-attn), so
+    that every token seen so far sits in exactly one of the three parts.
+    Returns (outs [steps, G, d], SK, SV, T, recent_K [R, d], recent_V [R, d]).
+    """
+    K0, V0 = np.asarray(K0, np.float64), np.asarray(V0, np.float64)
+    N = K0.shape[0]
+    M = N - S - R
+    assert M >= 1
+    sinkK, sinkV = K0[:S], V0[:S]
+    SK, SV, T = prefill(K0[S:S + M], bins), prefill(V0[S:S + M], bins), M
+    recK, recV = [r for r in K0[S + M:]], [r for r in V0[S + M:]]
+    outs = []
+    for i in range(len(k_new)):
+        recK.append(np.asarray(k_new[i], np.float64))
+        recV.append(np.asarray(v_new[i], np.float64))
+        if len(recK) > R:                      # the oldest recent token ages out
+            SK = append(SK, recK.pop(0), T, bins, M)
+            SV = append(SV, recV.pop(0), T, bins, M)
+            T += 1
+        rk = np.stack(recK) if recK else np.zeros((0, K0.shape[1]))
+        rv = np.stack(recV) if recV else np.zeros((0, K0.shape[1]))
+        outs.append(windowed_attention(q_new[i], sinkK, sinkV, SK, SV, T, M, bins, rk, rv, weights, scale))
+    rk = np.stack(recK) if recK else np.zeros((0, K0.shape[1]))
+    rv = np.stack(recV) if recV else np.zeros((0, K0.shape[1]))
+    return (np.stack(outs) if outs else np.zeros((0,) + np.shape(q_new)[1:])), SK, SV, T, rk, rv

@@ -275,3 +275,65 @@ def test_stream_decode_order_append_then_attend():
     first = orc.decode_attention(qn[0], orc.closed_form(allK[:M + 1], M, bins),
                                  orc.closed_form(allV[:M + 1], M, bins), M + 1, M, bins)
     np.testing.assert_allclose(outs[0], first, atol=1e-12)
+
+
+# ------------------------------------------------------------ sink / recent windows
+def test_windowed_all_bins_at_prefill_is_full_attention_over_every_token():
+    # with every bin kept and nothing absorbed yet the middle segment is exact, so the assembled
+    # cache is the whole context (in some order) and softmax attention does not care about order
+    S, R, M, d = 3, 5, 16, 4
+    r = rng(40)
+    K0, V0 = r.normal(size=(S + M + R, d)), r.normal(size=(S + M + R, d))
+    q = r.normal(size=(2, d))
+    bins = np.arange(M)
+    o = orc.windowed_attention(q, K0[:S], V0[:S], orc.prefill(K0[S:S + M], bins), orc.prefill(V0[S:S + M], bins),
+                               M, M, bins, K0[S + M:], V0[S + M:])
+    np.testing.assert_allclose(o, orc.attention(q, K0, V0), atol=1e-12)
+
+
+def test_windowed_stream_every_token_sits_in_exactly_one_part():
+    S, R, M, d, steps = 2, 3, 8, 3, 7
+    r = rng(41)
+    N = S + M + R
+    K0, V0 = r.normal(size=(N, d)), r.normal(size=(N, d))
+    kn, vn, qn = r.normal(size=(steps, d)), r.normal(size=(steps, d)), r.normal(size=(steps, 2, d))
+    bins = [0, 1, 2, 6, 7]
+    outs, SK, SV, T, rk, rv = orc.windowed_stream_decode(K0, V0, S, R, bins, kn, vn, qn)
+    allK, allV = np.vstack([K0, kn]), np.vstack([V0, vn])
+    # spectral state = tokens S .. S+T-1 in arrival order, each with weight 1/T; recent = the last R
+    assert T == M + steps
+    np.testing.assert_allclose(SK, orc.closed_form(allK[S:S + T], M, bins), atol=1e-13)
+    np.testing.assert_allclose(SV, orc.closed_form(allV[S:S + T], M, bins), atol=1e-13)
+    np.testing.assert_array_equal(rk, allK[-R:])
+    np.testing.assert_array_equal(rv, allV[-R:])
+    # the newest token is visible at once: the last output is attention over sink + reconstruction + last R
+    ref = orc.attention(qn[-1], np.vstack([K0[:S], orc.reconstruct(SK, T, M, bins), allK[-R:]]),
+                        np.vstack([V0[:S], orc.reconstruct(SV, T, M, bins), allV[-R:]]))
+    np.testing.assert_allclose(outs[-1], ref, atol=1e-12)
+
+
+def test_windowed_stream_without_windows_is_the_plain_stream():
+    M, d, steps = 8, 4, 4
+    r = rng(42)
+    K0, V0 = r.normal(size=(M, d)), r.normal(size=(M, d))
+    kn, vn, qn = r.normal(size=(steps, d)), r.normal(size=(steps, d)), r.normal(size=(steps, 2, d))
+    bins = [0, 2, 3, 7]
+    a = orc.windowed_stream_decode(K0, V0, 0, 0, bins, kn, vn, qn)
+    b = orc.stream_decode(K0, V0, bins, kn, vn, qn)
+    np.testing.assert_allclose(a[0], b[0], atol=1e-13)
+    np.testing.assert_allclose(a[1], b[1], atol=1e-14)
+    assert a[3] == b[3]
+
+
+def test_windowed_attention_weights_split_between_parts():
+    # a sink key aligned with the query and scaled up takes (almost) all the probability mass,
+    # so the output tends to that sink token's value: exact tokens enter the same softmax
+    S, R, M, d = 2, 2, 8, 4
+    r = rng(43)
+    K0, V0 = r.normal(size=(S + M + R, d)), r.normal(size=(S + M + R, d))
+    q = r.normal(size=(1, d))
+    K0[1] = 50.0 * q[0]
+    bins = [0, 1, 7]
+    o = orc.windowed_attention(q, K0[:S], V0[:S], orc.prefill(K0[S:S + M], bins), orc.prefill(V0[S:S + M], bins),
+                               M, M, bins, K0[S + M:], V0[S + M:])
+    np.testing.assert_allclose(o[0], V0[1], atol=1e-9)
