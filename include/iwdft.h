@@ -84,6 +84,9 @@ typedef struct {
                                  w = 2 for 0 < k < M/2 with bins <= M/2 gives the
                                  one-sided (real-signal) synthesis                  */
   uint32_t flags;
+  int32_t n_sink;             /* S >= 0: first S prefill tokens kept exact (attention sinks) */
+  int32_t n_recent;           /* R >= 0: the R newest tokens kept exact (recent window);
+                                 S + R <= 1024                                         */
   uint32_t reserved;          /* must be 0 */
 } iwdft_desc;
 
@@ -100,13 +103,17 @@ int iwdft_create(const iwdft_desc* desc, void* d_state, size_t state_bytes, void
 int iwdft_destroy(iwdft_ctx* ctx); /* frees host memory only; NULL is accepted */
 
 /* Prefill transform (Eq. dft-full at the kept bins, Eq. prefill-dft, Eq. freq-zero).
- * d_K, d_V: [n_layers][batch][n_kv_heads][M][head_dim] contiguous, kv_dtype.
- * Overwrites the state; T becomes M. */
+ * d_K, d_V: [n_layers][batch][n_kv_heads][S + M + R][head_dim] contiguous, kv_dtype.
+ * Per slice the first S tokens are copied to the sink store, the last R to the recent
+ * window, and the middle M tokens are transformed (Sec. 4.2.1).  Overwrites the state;
+ * T becomes M. */
 int iwdft_prefill(iwdft_ctx* ctx, const void* d_K, const void* d_V, void* hip_stream);
 
 /* Streaming update with one new token per sequence (Eq. infi-dft, Eq. update-iwdft).
  * d_tok_k, d_tok_v: [n_layers][batch][n_kv_heads][head_dim], kv_dtype.  T -> T+1.
- * Requires a prior prefill (IWDFT_ERR_STATE otherwise). */
+ * With R > 0 the new token joins the recent window and the token that ages out of it is
+ * the one absorbed into the coefficients ("Updating Cache", Sec. 4.2.2); with R = 0 the
+ * new token itself is absorbed.  Requires a prior prefill (IWDFT_ERR_STATE otherwise). */
 int iwdft_append(iwdft_ctx* ctx, const void* d_tok_k, const void* d_tok_v, void* hip_stream);
 
 /* Reconstruction of time slots a0 .. a0+n_slots-1 of one layer (Eq. inverse-swdft over
@@ -117,9 +124,10 @@ int iwdft_append(iwdft_ctx* ctx, const void* d_tok_k, const void* d_tok_v, void*
 int iwdft_reconstruct(iwdft_ctx* ctx, int32_t layer, int64_t a0, int64_t n_slots, void* d_Kt,
                       void* d_Vt, void* hip_stream);
 
-/* Decode attention over the M reconstructed slots of every layer (Eq. kv-attn applied to
- * the reconstructed segment of Eq. kv-concat): o = softmax(q K~^T * scale) V~ without
- * writing K~, V~ to memory.  d_q, d_out: [n_layers][batch][n_q_heads][head_dim], kv_dtype.
+/* Decode attention over the assembled cache of every layer (Eq. kv-attn over Eq. kv-concat:
+ * the S sink tokens, the M reconstructed slots, the R recent tokens, one softmax):
+ * o = softmax(q [K_sink; K~; K_recent]^T * scale) [V_sink; V~; V_recent] without writing
+ * K~, V~ to memory.  d_q, d_out: [n_layers][batch][n_q_heads][head_dim], kv_dtype.
  * scale <= 0 selects 1/sqrt(head_dim). */
 int compressed_decode_attn(iwdft_ctx* ctx, const void* d_q, void* d_out, float scale,
                            void* hip_stream);
@@ -132,7 +140,9 @@ int iwdft_export_coeffs(iwdft_ctx* ctx, int32_t layer, float* d_SK, float* d_SV,
 /* Device copy of the kept bins of one layer, int32 [|B_layer|] (for bit-exact mask checks). */
 int iwdft_export_bins(iwdft_ctx* ctx, int32_t layer, int32_t* d_bins, void* hip_stream);
 
-int64_t iwdft_num_tokens(const iwdft_ctx* ctx); /* T; 0 before prefill; -1 if ctx is NULL */
+int64_t iwdft_num_tokens(const iwdft_ctx* ctx); /* T = tokens inside the coefficients (the sink and
+                                                    recent tokens are not counted); 0 before prefill;
+                                                    -1 if ctx is NULL */
 
 /* Sets T after the caller restored a saved copy of the state buffer (checkpoint / resume).
  * T >= M. */

@@ -42,7 +42,8 @@ class iwdft_desc(ctypes.Structure):
         ("bin_offsets", ctypes.POINTER(ctypes.c_int64)),
         ("bins", ctypes.POINTER(ctypes.c_int32)),
         ("bin_weights", ctypes.POINTER(ctypes.c_float)),
-        ("flags", ctypes.c_uint32), ("reserved", ctypes.c_uint32),
+        ("flags", ctypes.c_uint32), ("n_sink", ctypes.c_int32), ("n_recent", ctypes.c_int32),
+        ("reserved", ctypes.c_uint32),
     ]
 
 
@@ -110,7 +111,8 @@ class Descriptor:
 
     def __init__(self, n_layers: int, batch: int, n_kv_heads: int, n_q_heads: int, head_dim: int,
                  kv_dtype: int, M: int, bins: Sequence[np.ndarray],
-                 bin_weights: Optional[Sequence[np.ndarray]] = None, flags: int = 0):
+                 bin_weights: Optional[Sequence[np.ndarray]] = None, flags: int = 0,
+                 n_sink: int = 0, n_recent: int = 0):
         self.bins = [np.ascontiguousarray(b, dtype=np.int32) for b in bins]
         self._offsets = np.zeros(len(self.bins) + 1, dtype=np.int64)
         self._offsets[1:] = np.cumsum([len(b) for b in self.bins])
@@ -123,7 +125,7 @@ class Descriptor:
             self._offsets.ctypes.data_as(ctypes.POINTER(ctypes.c_int64)),
             self._flat.ctypes.data_as(ctypes.POINTER(ctypes.c_int32)),
             self._w.ctypes.data_as(ctypes.POINTER(ctypes.c_float)) if self._w is not None else None,
-            flags, 0)
+            flags, n_sink, n_recent, 0)
 
 
 def iwdft_query_bytes(desc: Descriptor):
@@ -180,12 +182,13 @@ class Cache:
     """Owns the torch buffers behind one iwdft_ctx; methods forward to the C calls."""
 
     def __init__(self, n_layers, batch, n_kv_heads, n_q_heads, head_dim, dtype: torch.dtype, M,
-                 bins, bin_weights=None, flags=0, device="cuda:0"):
+                 bins, bin_weights=None, flags=0, device="cuda:0", n_sink=0, n_recent=0):
         if dtype not in (torch.float32, torch.bfloat16):
             raise ValueError("dtype must be float32 or bfloat16")
         self.dtype, self.device = dtype, torch.device(device)
         self.desc = Descriptor(n_layers, batch, n_kv_heads, n_q_heads, head_dim,
-                               IWDFT_F32 if dtype == torch.float32 else IWDFT_BF16, M, bins, bin_weights, flags)
+                               IWDFT_F32 if dtype == torch.float32 else IWDFT_BF16, M, bins, bin_weights, flags,
+                               n_sink, n_recent)
         self.state_bytes, self.ws_bytes = iwdft_query_bytes(self.desc)
         with torch.cuda.device(self.device):
             self.state = torch.empty(self.state_bytes, dtype=torch.uint8, device=self.device)

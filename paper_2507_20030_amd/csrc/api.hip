@@ -36,11 +36,13 @@ struct Plan {  // byte offsets inside the two caller buffers, derived from a des
   int32_t G = 1, max_nb = 0, max_Bp = 0;
   bool use_fft = false;
   size_t off_layers = 0, off_bins = 0, off_weights = 0, off_fold = 0, off_FK = 0, off_FV = 0, state_bytes = 0;
-  size_t off_qc = 0, off_Pn = 0, off_direct = 0, ws_bytes = 0;
+  size_t off_sinkK = 0, off_sinkV = 0, off_ringK = 0, off_ringV = 0;
+  size_t off_qc = 0, off_Pn = 0, off_pe = 0, off_direct = 0, ws_bytes = 0;
 };
 
 // Largest problem the FFT attention kernel keeps in registers / LDS.
 constexpr int kFftMaxBins = 4096;
+constexpr int kMaxExact = 1024;  // most sink + recent tokens (their scores sit in LDS)
 constexpr uint32_t kFftMinM = 256;
 constexpr int64_t kFftMaxQ = 8192;  // longest transform the FFT attention kernel holds in LDS
 
@@ -58,6 +60,10 @@ int make_plan(const iwdft_desc* d, Plan* pl) {
     return fail(IWDFT_ERR_ARG, "unknown bits in flags: 0x%x", d->flags);
   if (d->M < 1 || d->M > ((int64_t)1 << 30))
     return fail(IWDFT_ERR_ARG, "M = %lld outside [1, 2^30]", (long long)d->M);
+  if (d->n_sink < 0 || d->n_recent < 0) return fail(IWDFT_ERR_ARG, "n_sink / n_recent is negative");
+  if ((int64_t)d->n_sink + d->n_recent > kMaxExact)
+    return fail(IWDFT_ERR_UNSUPPORTED, "n_sink + n_recent = %lld exceeds %d", (long long)d->n_sink + d->n_recent,
+                kMaxExact);
   if (d->head_dim <= 0) return fail(IWDFT_ERR_ARG, "head_dim must be positive");
   if (d->head_dim != kHeadDim)
     return fail(IWDFT_ERR_UNSUPPORTED, "head_dim %d: this build has kernels for head_dim 128 only",
@@ -141,11 +147,18 @@ int make_plan(const iwdft_desc* d, Plan* pl) {
   pl->off_fold = o;    o = align256(o + sizeof(uint16_t) * (size_t)pl->n_bins_total);
   pl->off_FK = o;      o = align256(o + sizeof(float2) * (size_t)coef);
   pl->off_FV = o;      o = align256(o + sizeof(float2) * (size_t)coef);
+  const size_t esz = d->kv_dtype == IWDFT_BF16 ? 2 : 4;
+  const size_t n_sl = (size_t)d->n_layers * (size_t)slices_per_layer;
+  pl->off_sinkK = o;   o = align256(o + esz * n_sl * (size_t)d->n_sink * kHeadDim);
+  pl->off_sinkV = o;   o = align256(o + esz * n_sl * (size_t)d->n_sink * kHeadDim);
+  pl->off_ringK = o;   o = align256(o + esz * n_sl * (size_t)d->n_recent * kHeadDim);
+  pl->off_ringV = o;   o = align256(o + esz * n_sl * (size_t)d->n_recent * kHeadDim);
   pl->state_bytes = o;
 
   o = 0;
   pl->off_qc = o; o = align256(o + sizeof(float2) * (size_t)ws);
   pl->off_Pn = o; o = align256(o + sizeof(float2) * (size_t)ws);
+  pl->off_pe = o; o = align256(o + sizeof(float) * n_sl * (size_t)pl->G * (size_t)(d->n_sink + d->n_recent));
   pl->off_direct = o;
   if (!pl->use_fft)
     o = align256(o + sizeof(float) * (size_t)d->n_layers * (size_t)slices_per_layer *
@@ -272,6 +285,12 @@ int iwdft_create(const iwdft_desc* desc, void* d_state, size_t state_bytes, void
   P.fold = (const uint16_t*)(c->state + pl.off_fold);
   P.FK = (float2*)(c->state + pl.off_FK);
   P.FV = (float2*)(c->state + pl.off_FV);
+  P.S = desc->n_sink;
+  P.R = desc->n_recent;
+  P.sinkK = c->state + pl.off_sinkK;
+  P.sinkV = c->state + pl.off_sinkV;
+  P.ringK = c->state + pl.off_ringK;
+  P.ringV = c->state + pl.off_ringV;
   c->T = 0;
   *out = c;
   return IWDFT_OK;
@@ -306,7 +325,10 @@ int iwdft_append(iwdft_ctx* ctx, const void* d_tok_k, const void* d_tok_v, void*
   if (rc != IWDFT_OK) return rc;
   if (!d_tok_k || !d_tok_v) return fail(IWDFT_ERR_ARG, "d_tok_k / d_tok_v is NULL");
   if (ctx->T < ctx->desc.M) return fail(IWDFT_ERR_STATE, "iwdft_append before iwdft_prefill");
-  rc = launched(launch_append(ctx->P, d_tok_k, d_tok_v, t_shift(ctx), (hipStream_t)hip_stream),
+  // The recent ring was filled oldest-first at prefill, so after T - M appends the oldest token
+  // sits in slot (T - M) mod R.
+  const uint32_t ring_pos = ctx->P.R ? (uint32_t)((ctx->T - ctx->desc.M) % ctx->P.R) : 0u;
+  rc = launched(launch_append(ctx->P, d_tok_k, d_tok_v, t_shift(ctx), ring_pos, (hipStream_t)hip_stream),
                 "append launch");
   if (rc != IWDFT_OK) return rc;
   ctx->T += 1;
@@ -358,7 +380,8 @@ int compressed_decode_attn(iwdft_ctx* ctx, const void* d_q, void* d_out, float s
   if (scale <= 0.0f) scale = 1.0f / std::sqrt((float)ctx->desc.head_dim);
   const Plan& pl = ctx->plan;
   return launched(launch_attn(ctx->P, d_q, d_out, scale, (float2*)(ctx->ws + pl.off_qc),
-                              (float2*)(ctx->ws + pl.off_Pn), (float*)(ctx->ws + pl.off_direct),
+                              (float2*)(ctx->ws + pl.off_Pn), (float*)(ctx->ws + pl.off_pe),
+                              (float*)(ctx->ws + pl.off_direct),
                               pl.use_fft, (hipStream_t)hip_stream),
                   "decode attention launch");
 }

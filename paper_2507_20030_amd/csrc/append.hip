@@ -18,7 +18,8 @@ constexpr int kAppendBinsPerBlock = kAppendThreads * 2;  // two bins (one 16-byt
 template <bool BF16, int DROWS>
 __global__ __launch_bounds__(kAppendThreads) void append_kernel(Params P, const void* __restrict__ tok_k,
                                                                const void* __restrict__ tok_v,
-                                                               uint32_t tsh, int chunks) {
+                                                               uint32_t tsh, int chunks,
+                                                               int64_t x_slice_stride) {
   constexpr int dsplit = kHeadDim / DROWS;
   uint32_t bid = blockIdx.x;
   const int tensor = bid & 1;
@@ -46,7 +47,7 @@ __global__ __launch_bounds__(kAppendThreads) void append_kernel(Params P, const 
   const int d0 = ds * DROWS;
   v4f* row = (v4f*)(F + L.coef_off + ((int64_t)s * kHeadDim + d0) * L.Bp + i0);
   const int64_t stride = L.Bp / 2;  // in 16-byte units
-  const int64_t xbase = (int64_t)slice * kHeadDim + d0;
+  const int64_t xbase = (int64_t)slice * x_slice_stride + d0;
 
   constexpr int U = 8;
 #pragma unroll 1
@@ -68,16 +69,44 @@ __global__ __launch_bounds__(kAppendThreads) void append_kernel(Params P, const 
   }
 }
 
+// Recent window: after the coefficients absorbed the oldest ring token, the new token takes its slot.
+// grid: slice ; z: tensor; 128 threads = channels.
+template <bool BF16>
+__global__ __launch_bounds__(kHeadDim) void ring_push_kernel(Params P, const void* __restrict__ tok_k,
+                                                            const void* __restrict__ tok_v, uint32_t pos) {
+  const int slice = blockIdx.x;
+  const void* tok = blockIdx.y ? tok_v : tok_k;
+  void* ring = blockIdx.y ? P.ringV : P.ringK;
+  const int64_t src = (int64_t)slice * kHeadDim + threadIdx.x;
+  const int64_t dst = ((int64_t)slice * P.R + pos) * kHeadDim + threadIdx.x;
+  if constexpr (BF16) ((uint16_t*)ring)[dst] = ((const uint16_t*)tok)[src];
+  else ((float*)ring)[dst] = ((const float*)tok)[src];
+}
+
 hipError_t launch_append(const Params& P, const void* tok_k, const void* tok_v, uint32_t tsh,
-                         hipStream_t st) {
+                         uint32_t ring_pos, hipStream_t st) {
   constexpr int DROWS = 32;
+  // What is absorbed: the new token (R == 0) or the token ageing out of the recent window.
+  const int esz = P.kv_dtype == 1 ? 2 : 4;
+  const void* xk = tok_k;
+  const void* xv = tok_v;
+  int64_t x_stride = kHeadDim;
+  if (P.R > 0) {
+    xk = (const char*)P.ringK + (size_t)ring_pos * kHeadDim * esz;
+    xv = (const char*)P.ringV + (size_t)ring_pos * kHeadDim * esz;
+    x_stride = (int64_t)P.R * kHeadDim;
+  }
   const int chunks = (P.max_nb + kAppendBinsPerBlock - 1) / kAppendBinsPerBlock;
   const uint64_t blocks = (uint64_t)P.n_slices * chunks * (kHeadDim / DROWS) * 2;
   if (blocks > 0x7fffffffull) return hipErrorInvalidConfiguration;
   if (P.kv_dtype == 1)
-    append_kernel<true, DROWS><<<dim3((uint32_t)blocks), dim3(kAppendThreads), 0, st>>>(P, tok_k, tok_v, tsh, chunks);
+    append_kernel<true, DROWS><<<dim3((uint32_t)blocks), dim3(kAppendThreads), 0, st>>>(P, xk, xv, tsh, chunks, x_stride);
   else
-    append_kernel<false, DROWS><<<dim3((uint32_t)blocks), dim3(kAppendThreads), 0, st>>>(P, tok_k, tok_v, tsh, chunks);
+    append_kernel<false, DROWS><<<dim3((uint32_t)blocks), dim3(kAppendThreads), 0, st>>>(P, xk, xv, tsh, chunks, x_stride);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess || P.R == 0) return e;
+  if (P.kv_dtype == 1) ring_push_kernel<true><<<dim3((uint32_t)P.n_slices, 2), dim3(kHeadDim), 0, st>>>(P, tok_k, tok_v, ring_pos);
+  else ring_push_kernel<false><<<dim3((uint32_t)P.n_slices, 2), dim3(kHeadDim), 0, st>>>(P, tok_k, tok_v, ring_pos);
   return hipGetLastError();
 }
 

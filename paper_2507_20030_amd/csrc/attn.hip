@@ -8,7 +8,9 @@
 //   output  o[c] = sum_a p[a] V~[a][c] / Z  = Re sum_k F_V[c][k] * Pn[k],
 //                                             Pn[k] = (w_k / (M Z)) * conj( sum_a p[a] e^{-j 2 pi k a / M} )
 // The common slot shift (T-M) of the fixed-frame storage moves K~ and V~ together and drops out
-// of softmax attention.  Three kernels:
+// of softmax attention.  The S sink and R recent tokens that Eq. kv-concat keeps exact join the same
+// softmax: kernel A also writes their raw scores q.k_e, kernel B folds them into max / Z and turns
+// them into weights p_e / Z, kernel C adds sum_e (p_e / Z) v_e.  Three kernels:
 //   A  attn_qc_kernel   streams F_K once, produces qc[k] = sum_c q[c] F_K[c][k]    (HBM-bound)
 //   B  attn_fft_kernel  per (slice, pair of query heads): sparse spectrum -> M scores by
 //                       inverse FFT in LDS, softmax, forward FFT, gather the kept bins -> Pn
@@ -31,6 +33,23 @@ __device__ __forceinline__ float wave_sum(float v) {
   return v;
 }
 
+// Row e of the exact tokens of a slice: sink tokens first, then the recent ring (slot order; the
+// order is irrelevant to softmax attention as long as K and V use the same one).
+template <bool BF16>
+__device__ __forceinline__ const void* exact_row(const Params& P, bool value, int slice, int e) {
+  constexpr int kElem = BF16 ? 2 : 4;
+  const char* base;
+  int64_t row;
+  if (e < P.S) {
+    base = (const char*)(value ? P.sinkV : P.sinkK);
+    row = (int64_t)slice * P.S + e;
+  } else {
+    base = (const char*)(value ? P.ringV : P.ringK);
+    row = (int64_t)slice * P.R + (e - P.S);
+  }
+  return base + row * kHeadDim * kElem;
+}
+
 // ------------------------------------------------------------------------------------------ A
 constexpr int kQcThreads = 256;
 constexpr int kQcBins = kQcThreads * 2;
@@ -38,7 +57,8 @@ constexpr int kQcBins = kQcThreads * 2;
 // grid: (slice * chunks + chunk) * passes + pass.  Lane = two adjacent bins, loop over channels.
 template <bool BF16, int GT>
 __global__ __launch_bounds__(kQcThreads) void attn_qc_kernel(Params P, const void* __restrict__ q,
-                                                            float2* __restrict__ qc, int chunks, int passes) {
+                                                            float2* __restrict__ qc, float* __restrict__ pe,
+                                                            int chunks, int passes) {
   __shared__ float qs[GT][kHeadDim];
   uint32_t bid = blockIdx.x;
   const int pass = bid % passes;
@@ -56,6 +76,30 @@ __global__ __launch_bounds__(kQcThreads) void attn_qc_kernel(Params P, const voi
         (g < P.G) ? load_kv<BF16>(q, ((int64_t)slice * P.G + g) * kHeadDim + (e % kHeadDim)) : 0.f;
   }
   __syncthreads();
+  const int E = P.S + P.R;
+  if (chunk == 0 && E > 0) {  // raw scores q . k_e of the exact tokens, one (token, head) per thread
+    for (int idx = threadIdx.x; idx < E * GT; idx += kQcThreads) {
+      const int e = idx / GT, g = idx % GT;
+      if (g0 + g >= P.G) continue;
+      const void* kr = exact_row<BF16>(P, false, slice, e);
+      float dot = 0.f;
+      for (int c = 0; c < kHeadDim; c += 8) {
+        if constexpr (BF16) {
+          const uint4 w = *(const uint4*)((const uint16_t*)kr + c);
+#pragma unroll
+          for (int j = 0; j < 4; ++j) {
+            const uint32_t u = (&w.x)[j];
+            dot += qs[g][c + 2 * j] * __uint_as_float(u << 16) + qs[g][c + 2 * j + 1] * __uint_as_float(u & 0xffff0000u);
+          }
+        } else {
+          const float4 w0 = *(const float4*)((const float*)kr + c), w1 = *(const float4*)((const float*)kr + c + 4);
+          dot += qs[g][c] * w0.x + qs[g][c + 1] * w0.y + qs[g][c + 2] * w0.z + qs[g][c + 3] * w0.w +
+                 qs[g][c + 4] * w1.x + qs[g][c + 5] * w1.y + qs[g][c + 6] * w1.z + qs[g][c + 7] * w1.w;
+        }
+      }
+      pe[((int64_t)slice * P.G + g0 + g) * E + e] = dot;
+    }
+  }
   const int i0 = chunk * kQcBins + threadIdx.x * 2;
   if (i0 >= L.Bp) return;
   const v4f* row = (const v4f*)(P.FK + L.coef_off + (int64_t)s * kHeadDim * L.Bp + i0);
@@ -120,8 +164,8 @@ __device__ __forceinline__ float wave_reduce_scatter(float (&v)[V], int lane) {
 // 32 x 8 x 2048-bin workload, this kernel +5 us).
 template <bool BF16, int GT>
 __global__ __launch_bounds__(kOutThreads) void attn_out_kernel(Params P, const float2* __restrict__ Pn,
-                                                              void* __restrict__ out, int passes, int per_xcd,
-                                                              int total) {
+                                                              void* __restrict__ out, const float* __restrict__ pe,
+                                                              int passes, int per_xcd, int total) {
   constexpr int V = kOutDC * GT;
   constexpr int VR = V > 64 ? 64 : V;  // values per reduction round
   __shared__ float red[kOutThreads / 64][V];
@@ -176,7 +220,13 @@ __global__ __launch_bounds__(kOutThreads) void attn_out_kernel(Params P, const f
 #pragma unroll
     for (int w = 0; w < kOutThreads / 64; ++w) tot += red[w][v];
     const int dd = v / GT, g = v % GT;
-    if (g0 + g < P.G) store_kv<BF16>(out, ((int64_t)slice * P.G + g0 + g) * kHeadDim + d0 + dd, tot);
+    if (g0 + g < P.G) {
+      const int E = P.S + P.R;
+      const float* w = pe + ((int64_t)slice * P.G + g0 + g) * E;
+      for (int e = 0; e < E; ++e)  // exact tokens: weights already divided by the softmax sum
+        tot += w[e] * load_kv<BF16>(exact_row<BF16>(P, true, slice, e), d0 + dd);
+      store_kv<BF16>(out, ((int64_t)slice * P.G + g0 + g) * kHeadDim + d0 + dd, tot);
+    }
   }
 }
 
@@ -365,6 +415,8 @@ __device__ __forceinline__ float2 block_sum2(float2 v, float2* scratch, int tid)
   return r;
 }
 
+__device__ __forceinline__ int64_t s_global_head(int slice, int G, int g) { return (int64_t)slice * G + g; }
+
 // grid: slice * pairs + pair.  Two query heads share one complex transform: head g0 travels in
 // the real part, head g0+1 in the imaginary part (each head's spectrum is made Hermitian first,
 // so its time-domain signal is real).  Time index a = Pb * a' + b: block b of Q = M / Pb samples
@@ -377,8 +429,8 @@ __device__ __forceinline__ float2 block_sum2(float2 v, float2* scratch, int tid)
 // VGPRs and one workgroup per CU (measured 1.5x faster than spilling at two per CU).
 template <int LOGQ, int NBT, bool MULTI>
 __global__ __launch_bounds__(kFftThreads, (MULTI && NBT > 4) ? 2 : 4) void attn_fft_kernel(Params P, const float2* __restrict__ qc,
-                                                                 float2* __restrict__ Pn, float scale,
-                                                                 int pairs) {
+                                                                 float2* __restrict__ Pn, float* __restrict__ pe,
+                                                                 float scale, int pairs) {
   extern __shared__ float2 smem[];
   __shared__ float2 scratch[kFftThreads / 64];
   const int tid = threadIdx.x;
@@ -414,6 +466,26 @@ __global__ __launch_bounds__(kFftThreads, (MULTI && NBT > 4) ? 2 : 4) void attn_
     kk[j] = (uint32_t)bins[i < L.nb ? i : L.nb - 1];
   }
   float2 mx = make_float2(-INFINITY, -INFINITY), Z = make_float2(0.f, 0.f);
+
+  // Exact tokens open the online softmax: their raw scores q . k_e come from kernel A.
+  const int E = P.S + P.R;
+  float* pe0 = pe + ((int64_t)s_global_head(slice, P.G, g0)) * E;
+  float* pe1 = pe0 + E;
+  const float escale = 1.44269504088896341f * scale;  // scores live in log2 units (exp2 softmax)
+  if (E > 0) {
+    float2 lm = make_float2(-INFINITY, -INFINITY);
+    for (int e = tid; e < E; e += kFftThreads) {
+      lm.x = fmaxf(lm.x, pe0[e] * escale);
+      if (has1) lm.y = fmaxf(lm.y, pe1[e] * escale);
+    }
+    mx = block_max2(lm, scratch, tid);
+    float2 ls = make_float2(0.f, 0.f);
+    for (int e = tid; e < E; e += kFftThreads) {
+      ls.x += __builtin_amdgcn_exp2f(pe0[e] * escale - mx.x);
+      if (has1) ls.y += __builtin_amdgcn_exp2f(pe1[e] * escale - mx.y);
+    }
+    Z = block_sum2(ls, scratch, tid);
+  }
 
   constexpr bool kTight = MULTI && NBT <= 4;  // 128-VGPR multi-block variant: fight hoisting
   for (uint32_t b = 0; b < Pb; ++b) {
@@ -555,6 +627,10 @@ __global__ __launch_bounds__(kFftThreads, (MULTI && NBT > 4) ? 2 : 4) void attn_
       if (has1) o1[i] = r1;
     }
   }
+  for (int e = tid; e < E; e += kFftThreads) {  // raw scores -> weights p_e / Z (same thread, same entry)
+    pe0[e] = __builtin_amdgcn_exp2f(pe0[e] * escale - mx.x) / Z.x;
+    if (has1) pe1[e] = __builtin_amdgcn_exp2f(pe1[e] * escale - mx.y) / Z.y;
+  }
 }
 
 // ---------------------------------------------------------------------------------- B (direct)
@@ -563,8 +639,8 @@ constexpr int kDirStage = 1024;
 
 // grid: slice * G + g.  Evaluates the score and weight sums term by term; O(M |B|) per head.
 __global__ __launch_bounds__(kDirThreads) void attn_direct_kernel(Params P, const float2* __restrict__ qc,
-                                                                 float2* __restrict__ Pn, float scale,
-                                                                 float* __restrict__ scores) {
+                                                                 float2* __restrict__ Pn, float* __restrict__ pe,
+                                                                 float scale, float* __restrict__ scores) {
   __shared__ float2 Ys[kDirStage];
   __shared__ uint32_t ks[kDirStage];
   __shared__ float redf[kDirThreads / 64];
@@ -599,8 +675,11 @@ __global__ __launch_bounds__(kDirThreads) void attn_direct_kernel(Params P, cons
     }
   }
   __syncthreads();
+  const int E = P.S + P.R;
+  float* per = pe + ((int64_t)slice * P.G + g) * E;  // raw q . k_e from kernel A
   float lm = -INFINITY;
   for (uint32_t a = tid; a < P.M; a += kDirThreads) lm = fmaxf(lm, sc[a]);
+  for (int e = tid; e < E; e += kDirThreads) lm = fmaxf(lm, per[e] * scale);
   lm = wave_max(lm);
   if ((tid & 63) == 0) redf[tid >> 6] = lm;
   __syncthreads();
@@ -613,12 +692,14 @@ __global__ __launch_bounds__(kDirThreads) void attn_direct_kernel(Params P, cons
     sc[a] = p;
     lsum += p;
   }
+  for (int e = tid; e < E; e += kDirThreads) lsum += expf(per[e] * scale - mx);
   lsum = wave_sum(lsum);
   if ((tid & 63) == 0) redf[tid >> 6] = lsum;
   __syncthreads();
   float Z = 0.f;
   for (int w = 0; w < kDirThreads / 64; ++w) Z += redf[w];
 
+  for (int e = tid; e < E; e += kDirThreads) per[e] = expf(per[e] * scale - mx) / Z;  // weights p_e / Z
   float2* orow = Pn + L.ws_off + ((int64_t)s * P.G + g) * L.Bp;
   const float inv_M = 1.0f / (float)P.M;
   for (int i = tid; i < L.Bp; i += kDirThreads) {
@@ -645,7 +726,7 @@ __global__ __launch_bounds__(kDirThreads) void attn_direct_kernel(Params P, cons
 // --------------------------------------------------------------------------------------- host
 template <bool BF16>
 static hipError_t launch_attn_t(const Params& P, const void* q, void* out, float scale, float2* qc,
-                                float2* Pn, float* direct_scratch, bool use_fft, hipStream_t st) {
+                                float2* Pn, float* pe, float* direct_scratch, bool use_fft, hipStream_t st) {
   const int GT = P.G >= 8 ? 8 : (P.G > 2 ? 4 : P.G);  // 1, 2, 4 or 8 heads per pass
   const int passes = (P.G + GT - 1) / GT;
   const int chunks = (P.max_Bp + kQcBins - 1) / kQcBins;
@@ -663,7 +744,7 @@ static hipError_t launch_attn_t(const Params& P, const void* q, void* out, float
     default: KERNEL<BF16, 8><<<dim3((uint32_t)(GRID)), dim3(THREADS), 0, st>>>(__VA_ARGS__); break; \
   }
 
-  IWDFT_GT_SWITCH(attn_qc_kernel, gridA, kQcThreads, P, q, qc, chunks, passes)
+  IWDFT_GT_SWITCH(attn_qc_kernel, gridA, kQcThreads, P, q, qc, pe, chunks, passes)
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
 
@@ -677,14 +758,11 @@ static hipError_t launch_attn_t(const Params& P, const void* q, void* out, float
     const int per_thread = (P.max_Bp + kFftThreads - 1) / kFftThreads;  // <= 8 (checked at create)
 #define IWDFT_FFT_CASE(LQ, NBT, MULTI)                                                                   \
   {                                                                                                      \
-    static bool attr_set = false; /* raising the limit is idempotent; a race only repeats it */          \
-    if (!attr_set) {                                                                                     \
-      e = hipFuncSetAttribute((const void*)attn_fft_kernel<LQ, NBT, MULTI>,                              \
-                              hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);                     \
-      if (e != hipSuccess) return e;                                                                     \
-      attr_set = true;                                                                                   \
-    }                                                                                                    \
-    attn_fft_kernel<LQ, NBT, MULTI><<<dim3(gridB), dim3(kFftThreads), lds, st>>>(P, qc, Pn, scale, pairs); \
+    static LdsLimit lim;                                                                                 \
+    e = lim.ensure((const void*)attn_fft_kernel<LQ, NBT, MULTI>, (int)lds);                              \
+    if (e != hipSuccess) return e;                                                                       \
+    attn_fft_kernel<LQ, NBT, MULTI><<<dim3(gridB), dim3(kFftThreads), lds, st>>>(P, qc, Pn, pe, scale,   \
+                                                                                pairs);                  \
   }
 #define IWDFT_FFT_NBT(LQ, MULTI)                                                                         \
   {                                                                                                      \
@@ -704,21 +782,21 @@ static hipError_t launch_attn_t(const Params& P, const void* q, void* out, float
 #undef IWDFT_FFT_NBT
 #undef IWDFT_FFT_CASE
   } else {
-    attn_direct_kernel<<<dim3((uint32_t)gridBd), dim3(kDirThreads), 0, st>>>(P, qc, Pn, scale, direct_scratch);
+    attn_direct_kernel<<<dim3((uint32_t)gridBd), dim3(kDirThreads), 0, st>>>(P, qc, Pn, pe, scale, direct_scratch);
   }
   e = hipGetLastError();
   if (e != hipSuccess) return e;
 
   const int per_xcd = (int)((gridC + 7) / 8);
-  IWDFT_GT_SWITCH(attn_out_kernel, (uint64_t)per_xcd * 8, kOutThreads, P, Pn, out, passes, per_xcd, (int)gridC)
+  IWDFT_GT_SWITCH(attn_out_kernel, (uint64_t)per_xcd * 8, kOutThreads, P, Pn, out, pe, passes, per_xcd, (int)gridC)
 #undef IWDFT_GT_SWITCH
   return hipGetLastError();
 }
 
 hipError_t launch_attn(const Params& P, const void* q, void* out, float scale, float2* qc, float2* Pn,
-                       float* direct_scratch, bool use_fft, hipStream_t st) {
-  return P.kv_dtype == 1 ? launch_attn_t<true>(P, q, out, scale, qc, Pn, direct_scratch, use_fft, st)
-                         : launch_attn_t<false>(P, q, out, scale, qc, Pn, direct_scratch, use_fft, st);
+                       float* pe, float* direct_scratch, bool use_fft, hipStream_t st) {
+  return P.kv_dtype == 1 ? launch_attn_t<true>(P, q, out, scale, qc, Pn, pe, direct_scratch, use_fft, st)
+                         : launch_attn_t<false>(P, q, out, scale, qc, Pn, pe, direct_scratch, use_fft, st);
 }
 
 }  // namespace iwdft

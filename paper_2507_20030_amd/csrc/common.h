@@ -42,6 +42,13 @@ struct Params {
   const uint16_t* fold;  // per kept bin: low byte = round of its direct slot, high byte = round of its mirror slot
   float2* FK;
   float2* FV;
+  // Exact tokens (Sec. 4.2.1): S sink tokens and a ring of R recent tokens per slice, kv_dtype,
+  // [slice][S][128] and [slice][R][128].  Null / 0 when the windows are not used.
+  int32_t S, R;
+  void* sinkK;
+  void* sinkV;
+  void* ringK;
+  void* ringV;
 };
 
 // (a * b) mod M, exact.
@@ -115,13 +122,30 @@ __device__ __forceinline__ void store_kv(void* p, int64_t i, float v) {
 // Host-side launchers (defined next to their kernels).  Each validates nothing: the C ABI
 // layer has already checked every shape.  They return the hipError_t of the launch.
 hipError_t launch_prefill(const Params& P, const void* K, const void* V, hipStream_t st);
+// ring_pos: slot of the recent ring that holds the oldest token (ignored when R == 0).
 hipError_t launch_append(const Params& P, const void* tok_k, const void* tok_v, uint32_t t_shift,
-                         hipStream_t st);
+                         uint32_t ring_pos, hipStream_t st);
 hipError_t launch_export(const Params& P, int layer, float* SK, float* SV, uint32_t t_shift,
                          float inv_T, hipStream_t st);
 hipError_t launch_reconstruct(const Params& P, int layer, uint32_t a0, uint32_t n_slots, void* Kt,
                               void* Vt, uint32_t t_shift, hipStream_t st);
+// pe: [slice][query head][S + R] normalised softmax weights of the exact tokens (workspace).
 hipError_t launch_attn(const Params& P, const void* q, void* out, float scale, float2* qc,
-                       float2* Pn, float* direct_scratch, bool use_fft, hipStream_t st);
+                       float2* Pn, float* pe, float* direct_scratch, bool use_fft, hipStream_t st);
+
+// Raises a kernel's dynamic-LDS limit once per (kernel, device); one static instance per kernel.
+struct LdsLimit {
+  unsigned long long done = 0;  // bit per device; a race only repeats the idempotent call
+  hipError_t ensure(const void* fn, int bytes) {
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    const unsigned long long bit = 1ull << (dev & 63);
+    if (done & bit) return hipSuccess;
+    e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
+    if (e == hipSuccess) done |= bit;
+    return e;
+  }
+};
 
 }  // namespace iwdft

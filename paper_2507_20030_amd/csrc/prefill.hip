@@ -186,7 +186,8 @@ __global__ __launch_bounds__(kPfThreads) void prefill_mfma_kernel(Params P, cons
     acc_im[b] = (floatx16)(0.f);
   }
 
-  const int64_t slice_base = (int64_t)slice * M * kHeadDim;
+  // a slice holds S sink + M transformed + R recent tokens; the transform starts after the sinks
+  const int64_t slice_base = ((int64_t)slice * ((int64_t)P.S + M + P.R) + P.S) * kHeadDim;
   const uint32_t n_tiles = (M + kPfTok - 1) / kPfTok;
   const int a_off = (lane & 31) * kPfRS + 8 * g;  // this lane's row / token group inside a channel block
   TileRegs<BF16> regs;
@@ -284,29 +285,46 @@ __global__ __launch_bounds__(kPfThreads) void prefill_mfma_kernel(Params P, cons
   }
 }
 
+// Copies the exact tokens of a prefill (Sec. 4.2.1: the first S and the last R of every slice are
+// not transformed) into the sink store and the recent ring (ring slot j = j-th oldest).
+// grid: slice ; z: tensor.  One 16-byte chunk per thread and step.
+template <bool BF16>
+__global__ __launch_bounds__(256) void prefill_edges_kernel(Params P, const void* __restrict__ K,
+                                                           const void* __restrict__ V) {
+  constexpr int kElem = BF16 ? 2 : 4;
+  constexpr int kRowChunks = kHeadDim * kElem / 16;  // 16-byte chunks per token row
+  const int slice = blockIdx.x;
+  const int tensor = blockIdx.y;
+  const int64_t N = (int64_t)P.S + P.M + P.R;
+  const uint4* src = (const uint4*)(tensor ? V : K) + (int64_t)slice * N * kRowChunks;
+  uint4* sink = (uint4*)(tensor ? P.sinkV : P.sinkK) + (int64_t)slice * P.S * kRowChunks;
+  uint4* ring = (uint4*)(tensor ? P.ringV : P.ringK) + (int64_t)slice * P.R * kRowChunks;
+  for (int e = threadIdx.x; e < P.S * kRowChunks; e += 256) sink[e] = src[e];
+  const uint4* tail = src + ((int64_t)P.S + P.M) * kRowChunks;
+  for (int e = threadIdx.x; e < P.R * kRowChunks; e += 256) ring[e] = tail[e];
+}
+
 hipError_t launch_prefill(const Params& P, const void* K, const void* V, hipStream_t st) {
+  if (P.S + P.R > 0) {
+    if (P.kv_dtype == 1) prefill_edges_kernel<true><<<dim3((uint32_t)P.n_slices, 2), dim3(256), 0, st>>>(P, K, V);
+    else prefill_edges_kernel<false><<<dim3((uint32_t)P.n_slices, 2), dim3(256), 0, st>>>(P, K, V);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+  }
   const int nt = (P.max_nb + kPfBins - 1) / kPfBins;
   const uint64_t total = (uint64_t)P.n_slices * nt;
   if (total > 0x3fffffffull) return hipErrorInvalidConfiguration;
   const int per_xcd = (int)((total + 7) / 8);
   const bool bf16 = P.kv_dtype == 1;
   const size_t lds = sizeof(_Float16) * 2 * (bf16 ? 1 : 2) * kPfCh * kPfRS;
-  static bool attr_set = false;  // idempotent; a race only repeats the call
-  if (!attr_set) {
+  {
+    static LdsLimit lim[4];
     const int lds16 = (int)(sizeof(_Float16) * 2 * kPfCh * kPfRS), lds32 = 2 * lds16;
-    hipError_t e = hipFuncSetAttribute((const void*)prefill_mfma_kernel<true, true>,
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, lds16);
-    if (e == hipSuccess)
-      e = hipFuncSetAttribute((const void*)prefill_mfma_kernel<true, false>,
-                              hipFuncAttributeMaxDynamicSharedMemorySize, lds16);
-    if (e == hipSuccess)
-      e = hipFuncSetAttribute((const void*)prefill_mfma_kernel<false, true>,
-                              hipFuncAttributeMaxDynamicSharedMemorySize, lds32);
-    if (e == hipSuccess)
-      e = hipFuncSetAttribute((const void*)prefill_mfma_kernel<false, false>,
-                              hipFuncAttributeMaxDynamicSharedMemorySize, lds32);
+    hipError_t e = lim[0].ensure((const void*)prefill_mfma_kernel<true, true>, lds16);
+    if (e == hipSuccess) e = lim[1].ensure((const void*)prefill_mfma_kernel<true, false>, lds16);
+    if (e == hipSuccess) e = lim[2].ensure((const void*)prefill_mfma_kernel<false, true>, lds32);
+    if (e == hipSuccess) e = lim[3].ensure((const void*)prefill_mfma_kernel<false, false>, lds32);
     if (e != hipSuccess) return e;
-    attr_set = true;
   }
   const dim3 grid((uint32_t)(per_xcd * 8)), block(kPfThreads);
   const bool full = (P.M % kPfTok) == 0 && P.Mmask != 0;

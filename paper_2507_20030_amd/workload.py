@@ -22,18 +22,24 @@ class Config:
     n_kv_heads: int
     group: int            # query heads per KV head
     head_dim: int
-    L: int                # prefill tokens = DFT length M
+    L: int                # transformed prefill tokens = DFT length M (prefill holds n_sink + L + n_recent)
     n_bins: int           # kept bins per layer
     steps: int            # decode steps (append + attention)
     dtype: str            # "f32" or "bf16"
     mask: str             # "low" or "mixed" (half the layers low band, half low + mid groups)
     outlier_channels: int = 0
+    n_sink: int = 0       # first tokens kept exact (attention sinks)
+    n_recent: int = 0     # newest tokens kept exact (recent window)
     outlier_scale: float = 20.0
     seed: int = 0
 
     @property
     def n_q_heads(self) -> int:
         return self.n_kv_heads * self.group
+
+    @property
+    def n_prefill(self) -> int:
+        return self.n_sink + self.L + self.n_recent
 
     @property
     def n_slices(self) -> int:
@@ -51,6 +57,8 @@ CONFIGS = {
     "cfg3": Config("cfg3", 32, 8, 8, 4, 128, 32768, 4096, 512, "bf16", "mixed"),
     "cfg4": Config("cfg4", 32, 1, 8, 4, 128, 131072, 4096, 1024, "bf16", "low"),
     "cfg5": Config("cfg5", 80, 16, 8, 8, 128, 16384, 1638, 128, "bf16", "mixed", outlier_channels=4),
+    # cfg2 with the paper's exact windows (Sec. 5.1: 10 sink tokens, 50 recent tokens)
+    "cfg2w": Config("cfg2w", 32, 1, 8, 4, 128, 8192, 2048, 256, "bf16", "low", n_sink=10, n_recent=50),
 }
 
 
@@ -125,9 +133,9 @@ def _k_channel_scale(cfg: Config, layer: int, device) -> torch.Tensor:
 
 
 def prefill_layer(cfg: Config, layer: int, device):
-    """K, V of one layer, [batch, n_kv_heads, L, head_dim] in the storage dtype."""
+    """K, V of one layer, [batch, n_kv_heads, n_sink + L + n_recent, head_dim] in the storage dtype."""
     g = _gen(device, _seed(cfg, 5, layer))
-    shape = (cfg.batch, cfg.n_kv_heads, cfg.L, cfg.head_dim)
+    shape = (cfg.batch, cfg.n_kv_heads, cfg.n_prefill, cfg.head_dim)
     K = torch.randn(shape, generator=g, device=device, dtype=torch.float32)
     K *= k_channel_scale(cfg, layer, device)[None, :, None, :]
     K = K.to(cfg.torch_dtype)
@@ -136,8 +144,8 @@ def prefill_layer(cfg: Config, layer: int, device):
 
 
 def prefill_tensors(cfg: Config, device):
-    """K, V of all layers, [n_layers, batch, n_kv_heads, L, head_dim]."""
-    shape = (cfg.n_layers, cfg.batch, cfg.n_kv_heads, cfg.L, cfg.head_dim)
+    """K, V of all layers, [n_layers, batch, n_kv_heads, n_sink + L + n_recent, head_dim]."""
+    shape = (cfg.n_layers, cfg.batch, cfg.n_kv_heads, cfg.n_prefill, cfg.head_dim)
     K = torch.empty(shape, device=device, dtype=cfg.torch_dtype)
     V = torch.empty(shape, device=device, dtype=cfg.torch_dtype)
     for l in range(cfg.n_layers):

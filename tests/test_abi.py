@@ -51,6 +51,9 @@ def test_query_bytes_accounts_for_padded_rows():
     (dict(M=(1 << 30) + 1), B.IWDFT_ERR_ARG),
     (dict(flags=8), B.IWDFT_ERR_ARG),
     (dict(head_dim=64), B.IWDFT_ERR_UNSUPPORTED),
+    (dict(n_sink=-1), B.IWDFT_ERR_ARG),
+    (dict(n_recent=-3), B.IWDFT_ERR_ARG),
+    (dict(n_sink=1000, n_recent=25), B.IWDFT_ERR_UNSUPPORTED),
     (dict(bins=[np.arange(8), np.array([0, 3, 3, 9])]), B.IWDFT_ERR_BINS),
     (dict(bins=[np.arange(8), np.array([5, 3])]), B.IWDFT_ERR_BINS),
     (dict(bins=[np.arange(8), np.array([0, 64])]), B.IWDFT_ERR_BINS),
@@ -78,3 +81,11 @@ def test_null_pointers_and_null_ctx():
     out = ctypes.c_void_p()
     assert lib.iwdft_create(ctypes.byref(d.c), None, 0, None, 0, ctypes.byref(out)) == B.IWDFT_ERR_ARG
     assert lib.iwdft_create(ctypes.byref(d.c), None, 0, None, 0, None) == B.IWDFT_ERR_ARG
+
+
+def test_query_bytes_grows_with_exact_windows():
+    s0, w0 = B.iwdft_query_bytes(desc())
+    s1, w1 = B.iwdft_query_bytes(desc(n_sink=10, n_recent=50))
+    # 4 slices x (10 + 50) tokens x 128 channels x 2 B (bf16), K and V
+    assert s1 - s0 >= 2 * 4 * 60 * 128 * 2 and s1 - s0 < 2 * 4 * 60 * 128 * 2 + 2048
+    assert w1 > w0

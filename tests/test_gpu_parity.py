@@ -38,33 +38,47 @@ def c128(t):
 
 def make_cache(cfg, bins, weights=None, flags=0):
     return B.Cache(cfg.n_layers, cfg.batch, cfg.n_kv_heads, cfg.n_q_heads, cfg.head_dim, cfg.torch_dtype,
-                   cfg.L, bins, weights, flags, DEV)
+                   cfg.L, bins, weights, flags, DEV, n_sink=cfg.n_sink, n_recent=cfg.n_recent)
 
 
 class SliceOracle:
-    """Float64 state of a few sampled slices, advanced next to the GPU cache."""
+    """Float64 state of a few sampled slices, advanced next to the GPU cache: coefficients of the
+    transformed middle segment plus the exact sink tokens and the recent window (Sec. 4.2)."""
 
     def __init__(self, cfg, bins, weights, K, V, slices):
         self.cfg, self.bins, self.weights, self.slices = cfg, bins, weights, slices
         self.M = cfg.L
         self.T = cfg.L
-        self.S = {}
-        for (l, b, h) in slices:
-            self.S[(l, b, h)] = [orc.prefill(f64(K[l, b, h]), bins[l]), orc.prefill(f64(V[l, b, h]), bins[l])]
+        self.S, self.sink, self.recent = {}, {}, {}
+        s0, s1 = cfg.n_sink, cfg.n_sink + cfg.L
+        for key in slices:
+            l = key[0]
+            k, v = f64(K[key]), f64(V[key])
+            self.S[key] = [orc.prefill(k[s0:s1], bins[l]), orc.prefill(v[s0:s1], bins[l])]
+            self.sink[key] = (k[:s0], v[:s0])
+            self.recent[key] = ([r for r in k[s1:]], [r for r in v[s1:]])
 
     def append(self, tk, tv):
-        for (l, b, h), st in self.S.items():
-            st[0] = orc.append(st[0], f64(tk[l, b, h]), self.T, self.bins[l], self.M)
-            st[1] = orc.append(st[1], f64(tv[l, b, h]), self.T, self.bins[l], self.M)
+        for key, st in self.S.items():
+            l = key[0]
+            rk, rv = self.recent[key]
+            rk.append(f64(tk[key]))
+            rv.append(f64(tv[key]))
+            st[0] = orc.append(st[0], rk.pop(0), self.T, self.bins[l], self.M)
+            st[1] = orc.append(st[1], rv.pop(0), self.T, self.bins[l], self.M)
         self.T += 1
 
     def attend(self, q):
-        G = self.cfg.group
+        G, d = self.cfg.group, self.cfg.head_dim
         out = {}
-        for (l, b, h), st in self.S.items():
+        for key, st in self.S.items():
+            l, b, h = key
             w = None if self.weights is None else self.weights[l]
-            out[(l, b, h)] = orc.decode_attention(f64(q[l, b, h * G:(h + 1) * G]), st[0], st[1], self.T, self.M,
-                                                  self.bins[l], w)
+            rk, rv = self.recent[key]
+            rk = np.stack(rk) if rk else np.zeros((0, d))
+            rv = np.stack(rv) if rv else np.zeros((0, d))
+            out[key] = orc.windowed_attention(f64(q[l, b, h * G:(h + 1) * G]), self.sink[key][0], self.sink[key][1],
+                                              st[0], st[1], self.T, self.M, self.bins[l], rk, rv, w)
         return out
 
     def reconstruct(self, key, which):
@@ -243,6 +257,38 @@ def test_checkpoint_resume_is_bitwise():
     assert torch.equal(cache.state, end)
     assert torch.equal(cache.attend(steps[5][2]), a)
     cache.close()
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("L,S,R,group", [(256, 10, 50, 2), (1024, 3, 1, 3), (96, 4, 7, 1), (512, 0, 5, 4),
+                                         (512, 6, 0, 8)])
+def test_sink_and_recent_windows(dtype, L, S, R, group):
+    # exact sink / recent tokens join the softmax; more appends than R so that the ring wraps and every
+    # original recent token and several appended ones have aged into the coefficients
+    cfg = small_cfg(L=L, group=group, dtype=dtype, n_bins=41, n_sink=S, n_recent=R, steps=max(6, R + 3) if R < 10 else 7)
+    run_stream(cfg, random_bins(cfg, 17), rec=(2, 40), tag=f"windows-{dtype}-L{L}-S{S}-R{R}-G{group}")
+
+
+def test_windows_all_bins_equals_full_attention_over_the_whole_context():
+    # every bin kept, nothing appended beyond the recent hand-over: the assembled cache is the complete
+    # context, so the library must reproduce plain softmax attention over all S + M + R tokens
+    cfg = small_cfg(L=256, n_bins=256, group=2, dtype="f32", n_sink=5, n_recent=9, n_layers=1, batch=1, steps=0)
+    bins = [np.arange(256, dtype=np.int32)]
+    K, V = wl.prefill_tensors(cfg, DEV)
+    cache = make_cache(cfg, bins)
+    cache.prefill(K, V)
+    _, _, q = wl.decode_step(cfg, 0, DEV)
+    out = cache.attend(q)
+    G = cfg.group
+    for h in range(cfg.n_kv_heads):
+        ref = orc.attention(f64(q[0, 0, h * G:(h + 1) * G]), f64(K[0, 0, h]), f64(V[0, 0, h]))
+        assert rel_l2(f64(out[0, 0, h * G:(h + 1) * G]), ref) < 1e-5
+    cache.close()
+
+
+def test_cfg2_with_paper_windows_full_size():
+    cfg = wl.CONFIGS["cfg2w"]
+    run_stream(cfg, wl.layer_bins(cfg), steps=3, tag="cfg2w")
 
 
 def test_cfg2_full_size_sampled_slices():
