@@ -2,13 +2,16 @@
 """Benchmark of the IWDFT hot path on one MI355X.
 
 One *step* is one whole job over the named workload with all inputs already resident in HBM:
-    iwdft_prefill(K, V)  ->  decode_steps x ( iwdft_append(k_i, v_i) ; compressed_decode_attn(q_i) )
-(the reconstruction of Eq. reconstruct-idft happens inside the attention kernels; the materialising
-iwdft_reconstruct call is timed separately and reported under "kernels").
+    iwdft_prefill(K, V)  ->  decode_steps x iwdft_append_attn(k_i, v_i, q_i)
+where iwdft_append_attn is the append followed by the decode attention with the update fused into
+the attention kernels (--split runs the two separate calls instead).  The reconstruction of
+Eq. reconstruct-idft happens inside the attention kernels; the materialising iwdft_reconstruct call
+is timed separately and reported under "kernels", and so are the two separate calls of the metric
+(append tokens/s, decode attention us/step).
 
-Prints ONE JSON line: whole-job appended tokens per second, the per-call timings measured with
-HIP events inside the timed region, the roofline of the dominant kernel (the streaming update)
-and the float64 CPU oracle timed on a bounded sample of the same workload.
+Prints ONE JSON line: whole-job appended tokens per second, the per-call and per-kernel timings
+measured with HIP events inside the timed region, the roofline of the dominant kernel and the
+float64 CPU oracle timed on a bounded sample of the same workload.
 """
 import argparse
 import json
@@ -31,6 +34,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=1)
     ap.add_argument("--config", default="cfg2")
     ap.add_argument("--decode-steps", type=int, default=None, help="override the workload's decode steps")
+    ap.add_argument("--split", action="store_true",
+                    help="decode with the two separate calls (iwdft_append, compressed_decode_attn) instead of "
+                         "the fused iwdft_append_attn")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="only run a plain 1 GiB device copy (reference for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE)")
@@ -66,48 +72,88 @@ def main():
     out = torch.empty_like(pool[0][2])
     stream = torch.cuda.current_stream()
 
-    def job(events=None):
+    fused = not args.split
+
+    def decode(i, marks=None):
+        tk, tv, q = pool[i % n_pool]
+        if fused:
+            if marks is not None:
+                marks[0].record(stream)
+            cache.step(tk, tv, q, out, 0.0, stream)
+            if marks is not None:
+                marks[2].record(stream)
+        else:
+            if marks is not None:
+                marks[0].record(stream)
+            cache.append(tk, tv, stream)
+            if marks is not None:
+                marks[1].record(stream)
+            cache.attend(q, out, 0.0, stream)
+            if marks is not None:
+                marks[2].record(stream)
+
+    # Event records between the kernels cost a few us each, so only a sample of the decode steps of
+    # the timed region carries them: every 8th step has the library's phase marks around its three
+    # attention kernels, another every 8th has events around the call(s); the rest run unmarked.
+    # HIP events are created at their first record, which costs far more than a record: all of them
+    # are recorded once before the timed region.
+    def mk(n):
+        evs = [torch.cuda.Event(enable_timing=True) for _ in range(n)]
+        for e in evs:
+            e.record(stream)
+        return evs
+    ev = [{i: mk(3) for i in range(dsteps) if i % 8 == 4 or dsteps < 8} for _ in range(args.steps)]
+    pre = [mk(2) for _ in range(args.steps)]
+    marked = lambda i: i % 8 == 0
+
+    def run_job(s):
+        if s is not None:
+            pre[s][0].record(stream)
         cache.prefill(K, V, stream)
+        if s is not None:
+            pre[s][1].record(stream)
         for i in range(dsteps):
-            tk, tv, q = pool[i % n_pool]
-            if events is not None:
-                e = events[i]
-                e[0].record(stream)
-                cache.append(tk, tv, stream)
-                e[1].record(stream)
-                cache.attend(q, out, 0.0, stream)
-                e[2].record(stream)
-            else:
-                cache.append(tk, tv, stream)
-                cache.attend(q, out, 0.0, stream)
+            if marked(i):
+                B.iwdft_phase_timing(cache.ctx, True)
+            decode(i, ev[s].get(i) if s is not None else None)
+            if marked(i):
+                B.iwdft_phase_timing(cache.ctx, False)
 
+    for _ in range(args.steps):                 # untimed: creates the library's marks
+        run_job(None)
+    B.iwdft_phase_times(cache.ctx)
     for _ in range(args.warmup):
-        job()
-    torch.cuda.synchronize()
-
-    ev = [[[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(dsteps)]
-          for _ in range(args.steps)]
-    pre = [[torch.cuda.Event(enable_timing=True) for _ in range(2)] for _ in range(args.steps)]
+        run_job(None)
+    B.iwdft_phase_times(cache.ctx)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for s in range(args.steps):
-        pre[s][0].record(stream)
-        cache.prefill(K, V, stream)
-        pre[s][1].record(stream)
-        for i in range(dsteps):
-            tk, tv, q = pool[i % n_pool]
-            e = ev[s][i]
-            e[0].record(stream)
-            cache.append(tk, tv, stream)
-            e[1].record(stream)
-            cache.attend(q, out, 0.0, stream)
-            e[2].record(stream)
+        run_job(s)
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
+    phase_ms, phase_calls = B.iwdft_phase_times(cache.ctx)
+    phase_avg = [m / max(phase_calls, 1) for m in phase_ms]  # kernels A, B, C of the timed region
 
-    app_ms = np.array([[e[0].elapsed_time(e[1]) for e in row] for row in ev])
-    att_ms = np.array([[e[1].elapsed_time(e[2]) for e in row] for row in ev])
     pre_ms = np.array([p[0].elapsed_time(p[1]) for p in pre])
+    step_ms = np.array([[e[0].elapsed_time(e[2]) for e in row.values()] for row in ev])
+
+    # The two calls of the metric on their own (append, then decode attention), same state and inputs.
+    # In a fused run this pass comes after the timed region; in a --split run it is the timed region.
+    if fused:
+        sp = [mk(3) for _ in range(dsteps)]
+        for i in range(dsteps):
+            tk, tv, q = pool[i % n_pool]
+            sp[i][0].record(stream)
+            cache.append(tk, tv, stream)
+            sp[i][1].record(stream)
+            cache.attend(q, out, 0.0, stream)
+            sp[i][2].record(stream)
+        torch.cuda.synchronize()
+        app_ms = np.array([e[0].elapsed_time(e[1]) for e in sp])
+        att_ms = np.array([e[1].elapsed_time(e[2]) for e in sp])
+    else:
+        app_ms = np.array([[e[0].elapsed_time(e[1]) for e in row.values()] for row in ev])
+        att_ms = np.array([[e[1].elapsed_time(e[2]) for e in row.values()] for row in ev])
 
     # materialising reconstruction of one layer, timed on its own (not part of the job)
     r0, r1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
@@ -126,13 +172,27 @@ def main():
     attn_bytes = 2 * coef_bytes                                            # K and V read once
     prefill_useful_flop = 2.0 * 2 * nb_total * cfg.L * cfg.head_dim * 2     # cos+sin rows, K and V
     app_avg, att_avg, pre_avg = float(app_ms.mean()), float(att_ms.mean()), float(pre_ms.mean())
+    step_avg = float(step_ms.mean())
     tokens = args.steps * dsteps * cfg.batch
+    gbps = lambda nbytes, ms: nbytes / (ms * 1e-3) / 1e9
 
-    traffic = None
+    traffic_all = {}
     tpath = os.path.join(ROOT, "profiles", "traffic.json")
     if os.path.exists(tpath):
-        traffic = json.load(open(tpath)).get(f"append_{cfg.name}")
+        traffic_all = json.load(open(tpath))
 
+    if fused:
+        # dominant kernel of the job: phase A of the fused step, a read-modify-write of every K coefficient
+        roof_kernel = "attn_qc_kernel<UPD> (iwdft_append_attn, phase A: K update + scores)"
+        roof_bytes, roof_ms = 2 * coef_bytes, phase_avg[0]
+        traffic = traffic_all.get(f"step_qc_{cfg.name}")
+    else:
+        roof_kernel = "append_kernel (iwdft_append)"
+        roof_bytes, roof_ms = append_bytes, app_avg
+        traffic = traffic_all.get(f"append_{cfg.name}")
+
+    step_def = ("prefill + decode_steps x iwdft_append_attn (append fused into the decode attention)" if fused
+                else "prefill + decode_steps x (iwdft_append, compressed_decode_attn)")
     result = {
         "metric": "IWDFT tokens appended/sec + compressed decode-attn us/step (frac of HBM peak)",
         "value": tokens / elapsed,
@@ -152,32 +212,48 @@ def main():
                         f"{cfg.n_bins} kept bins/layer ({cfg.mask}), {dsteps} x (append + decode attention), "
                         f"{cfg.group} query heads per KV head",
             "decode_steps": dsteps,
-            "step_definition": "prefill + decode_steps x (append, decode attention)",
+            "step_definition": step_def,
         },
         "decode_attn_us_per_step": 1e3 * att_avg,
         "append_tokens_per_s": cfg.batch / (app_avg * 1e-3),
+        "decode_step_us": 1e3 * step_avg,
         "kernels": {
             "iwdft_append": {"avg_ms": app_avg, "min_ms": float(app_ms.min()), "algorithmic_GB": append_bytes / 1e9,
-                             "GBps": append_bytes / (app_avg * 1e-3) / 1e9,
-                             "frac_hbm_peak": append_bytes / (app_avg * 1e-3) / 1e9 / HBM_PEAK_GBS},
+                             "GBps": gbps(append_bytes, app_avg),
+                             "frac_hbm_peak": gbps(append_bytes, app_avg) / HBM_PEAK_GBS},
             "compressed_decode_attn": {"avg_ms": att_avg, "min_ms": float(att_ms.min()),
                                        "algorithmic_GB": attn_bytes / 1e9,
-                                       "GBps": attn_bytes / (att_avg * 1e-3) / 1e9,
-                                       "frac_hbm_peak": attn_bytes / (att_avg * 1e-3) / 1e9 / HBM_PEAK_GBS},
+                                       "GBps": gbps(attn_bytes, att_avg),
+                                       "frac_hbm_peak": gbps(attn_bytes, att_avg) / HBM_PEAK_GBS},
             "iwdft_prefill": {"avg_ms": pre_avg, "useful_TFLOP": prefill_useful_flop / 1e12,
                               "useful_TFLOPps": prefill_useful_flop / (pre_avg * 1e-3) / 1e12},
             "iwdft_reconstruct_one_layer": {"ms": rec_ms},
         },
         "roofline": {
-            "kernel": "append_kernel (iwdft_append)",
+            "kernel": roof_kernel,
             "bound": "hbm",
-            "achieved": append_bytes / (app_avg * 1e-3) / 1e9,
+            "achieved": gbps(roof_bytes, roof_ms),
             "peak": HBM_PEAK_GBS,
             "unit": "GB/s",
-            "frac": append_bytes / (app_avg * 1e-3) / 1e9 / HBM_PEAK_GBS,
+            "frac": gbps(roof_bytes, roof_ms) / HBM_PEAK_GBS,
             "traffic": traffic,
         },
     }
+    if fused:
+        # every coefficient read once and written once per step: the same bytes as one append
+        result["kernels"]["iwdft_append_attn"] = {
+            "avg_ms": step_avg, "min_ms": float(step_ms.min()), "algorithmic_GB": append_bytes / 1e9,
+            "GBps": gbps(append_bytes, step_avg), "frac_hbm_peak": gbps(append_bytes, step_avg) / HBM_PEAK_GBS,
+            "phase_A_K_update_scores_ms": phase_avg[0], "phase_B_softmax_transforms_ms": phase_avg[1],
+            "phase_C_V_update_output_ms": phase_avg[2],
+            "phase_A_frac_hbm_peak": gbps(2 * coef_bytes, phase_avg[0]) / HBM_PEAK_GBS,
+            "phase_C_frac_hbm_peak": gbps(2 * coef_bytes, phase_avg[2]) / HBM_PEAK_GBS,
+        }
+        result["kernels"]["iwdft_append"]["measured"] = "separate calls after the timed region"
+        result["kernels"]["compressed_decode_attn"]["measured"] = "separate calls after the timed region"
+    else:
+        result["kernels"]["compressed_decode_attn"].update(
+            {"phase_A_ms": phase_avg[0], "phase_B_ms": phase_avg[1], "phase_C_ms": phase_avg[2]})
 
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(cfg, bins, K, V, pool, np, torch)
@@ -195,8 +271,8 @@ def cpu_baseline(cfg, bins, K, V, pool, np, torch):
     except Exception:  # pragma: no cover
         limiter = None
     from paper_2507_20030_amd import workload as wl
-    slices = wl.sample_slices(cfg, 4)
-    steps = min(4, len(pool))
+    slices = wl.sample_slices(cfg, 32)
+    steps = min(12, len(pool))
     f64 = lambda t: t.detach().cpu().to(torch.float64).numpy()
     host = [(f64(K[l, b, h]), f64(V[l, b, h])) for (l, b, h) in slices]
     host_steps = [[(f64(tk[l, b, h]), f64(tv[l, b, h]), f64(q[l, b, h * cfg.group:(h + 1) * cfg.group]))

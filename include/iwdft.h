@@ -132,6 +132,27 @@ int iwdft_reconstruct(iwdft_ctx* ctx, int32_t layer, int64_t a0, int64_t n_slots
 int compressed_decode_attn(iwdft_ctx* ctx, const void* d_q, void* d_out, float scale,
                            void* hip_stream);
 
+/* One decode step: iwdft_append(tok) followed by compressed_decode_attn(q) (the three operations
+ * of the decoding stage, Sec. 4.2.2), fused: each K coefficient is updated (Eq. infi-dft) on its
+ * way into the scores and each V coefficient on its way into the output, so every coefficient is
+ * read once and written once per step instead of read twice and written once.  Same arguments,
+ * same result (up to rounding order) and same errors as the two calls in sequence.  T -> T+1. */
+int iwdft_append_attn(iwdft_ctx* ctx, const void* d_tok_k, const void* d_tok_v, const void* d_q,
+                      void* d_out, float scale, void* hip_stream);
+
+/* Profiling aid (no paper operation).  While enabled, every compressed_decode_attn and fused
+ * iwdft_append_attn call records HIP events around its three phases -- A: the query against the K
+ * coefficients (Eq. kv-attn scores in the frequency domain; with the K update in the fused step),
+ * B: inverse transform + softmax + forward transform, C: the output from the V coefficients (with
+ * the V update in the fused step) -- on the call's stream.  Events are host objects the context
+ * owns; no device memory is allocated.  A fused call that falls back to append + attention marks
+ * its attention part only. */
+int iwdft_phase_timing(iwdft_ctx* ctx, int enable);
+
+/* Waits for the marked calls made since the last read-out, then returns the summed duration of each
+ * phase in milliseconds (ms[0..2] = A, B, C; HOST) and the number of calls, and clears the list. */
+int iwdft_phase_times(iwdft_ctx* ctx, double* ms, int64_t* n_calls);
+
 /* The paper-convention coefficients S_T of one layer, for inspection and parity:
  * d_SK, d_SV: [batch][n_kv_heads][|B_layer|][head_dim][2] (re, im) fp32; either may be NULL. */
 int iwdft_export_coeffs(iwdft_ctx* ctx, int32_t layer, float* d_SK, float* d_SV,

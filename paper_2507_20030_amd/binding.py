@@ -21,8 +21,8 @@ IWDFT_FLAG_DIRECT_SYNTHESIS = 1
 
 EXPORTED = [
     "iwdft_query_bytes", "iwdft_create", "iwdft_destroy", "iwdft_prefill", "iwdft_append",
-    "iwdft_reconstruct", "compressed_decode_attn", "iwdft_export_coeffs", "iwdft_export_bins",
-    "iwdft_num_tokens", "iwdft_set_num_tokens", "iwdft_last_error",
+    "iwdft_reconstruct", "compressed_decode_attn", "iwdft_append_attn", "iwdft_export_coeffs", "iwdft_export_bins",
+    "iwdft_num_tokens", "iwdft_set_num_tokens", "iwdft_last_error", "iwdft_phase_timing", "iwdft_phase_times",
 ]
 
 LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libiwdft.so")
@@ -69,6 +69,9 @@ def load_library() -> ctypes.CDLL:
     lib.iwdft_append.argtypes = [vp, vp, vp, vp]
     lib.iwdft_reconstruct.argtypes = [vp, i32, i64, i64, vp, vp, vp]
     lib.compressed_decode_attn.argtypes = [vp, vp, vp, f32, vp]
+    lib.iwdft_append_attn.argtypes = [vp, vp, vp, vp, vp, f32, vp]
+    lib.iwdft_phase_timing.argtypes = [vp, i32]
+    lib.iwdft_phase_times.argtypes = [vp, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_int64)]
     lib.iwdft_export_coeffs.argtypes = [vp, i32, vp, vp, vp]
     lib.iwdft_export_bins.argtypes = [vp, i32, vp, vp]
     lib.iwdft_num_tokens.argtypes = [vp]
@@ -162,6 +165,23 @@ def compressed_decode_attn(ctx, q: torch.Tensor, out: torch.Tensor, scale: float
     _check(load_library().compressed_decode_attn(ctx, _ptr(q), _ptr(out), scale, _stream(stream)))
 
 
+def iwdft_append_attn(ctx, tok_k, tok_v, q, out, scale: float = 0.0, stream=None) -> None:
+    _check(load_library().iwdft_append_attn(ctx, _ptr(tok_k), _ptr(tok_v), _ptr(q), _ptr(out), scale,
+                                            _stream(stream)))
+
+
+def iwdft_phase_timing(ctx, enable: bool) -> None:
+    _check(load_library().iwdft_phase_timing(ctx, 1 if enable else 0))
+
+
+def iwdft_phase_times(ctx):
+    """(ms of phases A, B, C summed over the marked calls since the last read-out, number of calls)."""
+    ms = (ctypes.c_double * 3)()
+    n = ctypes.c_int64(0)
+    _check(load_library().iwdft_phase_times(ctx, ms, ctypes.byref(n)))
+    return [ms[0], ms[1], ms[2]], n.value
+
+
 def iwdft_export_coeffs(ctx, layer: int, SK, SV, stream=None) -> None:
     _check(load_library().iwdft_export_coeffs(ctx, layer, _ptr(SK), _ptr(SV), _stream(stream)))
 
@@ -221,6 +241,13 @@ class Cache:
         if out is None:
             out = torch.empty_like(q)
         compressed_decode_attn(self.ctx, q, out, scale, stream)
+        return out
+
+    def step(self, tok_k, tok_v, q, out=None, scale=0.0, stream=None):
+        """Fused decode step: append (tok_k, tok_v), then attend with q."""
+        if out is None:
+            out = torch.empty_like(q)
+        iwdft_append_attn(self.ctx, tok_k, tok_v, q, out, scale, stream)
         return out
 
     def reconstruct(self, layer, a0, n_slots, want_k=True, want_v=True, stream=None):

@@ -37,7 +37,7 @@ struct Plan {  // byte offsets inside the two caller buffers, derived from a des
   bool use_fft = false;
   size_t off_layers = 0, off_bins = 0, off_weights = 0, off_fold = 0, off_FK = 0, off_FV = 0, state_bytes = 0;
   size_t off_sinkK = 0, off_sinkV = 0, off_ringK = 0, off_ringV = 0;
-  size_t off_qc = 0, off_Pn = 0, off_pe = 0, off_direct = 0, ws_bytes = 0;
+  size_t off_qc = 0, off_Pn = 0, off_pe = 0, off_stageK = 0, off_stageV = 0, off_direct = 0, ws_bytes = 0;
 };
 
 // Largest problem the FFT attention kernel keeps in registers / LDS.
@@ -159,6 +159,8 @@ int make_plan(const iwdft_desc* d, Plan* pl) {
   pl->off_qc = o; o = align256(o + sizeof(float2) * (size_t)ws);
   pl->off_Pn = o; o = align256(o + sizeof(float2) * (size_t)ws);
   pl->off_pe = o; o = align256(o + sizeof(float) * n_sl * (size_t)pl->G * (size_t)(d->n_sink + d->n_recent));
+  pl->off_stageK = o; o = align256(o + (d->n_recent ? esz * n_sl * kHeadDim : 0));
+  pl->off_stageV = o; o = align256(o + (d->n_recent ? esz * n_sl * kHeadDim : 0));
   pl->off_direct = o;
   if (!pl->use_fft)
     o = align256(o + sizeof(float) * (size_t)d->n_layers * (size_t)slices_per_layer *
@@ -177,6 +179,10 @@ struct iwdft_ctx {
   int64_t T = 0;
   char* state = nullptr;
   char* ws = nullptr;
+  // phase timing (iwdft_phase_timing): events of the calls since the last read-out
+  bool timing = false;
+  std::vector<iwdft::PhaseEvents> marks;  // pool, reused after every read-out
+  size_t marks_used = 0;
 };
 
 namespace {
@@ -193,6 +199,25 @@ int check_ctx(const iwdft_ctx* c) {
 
 int launched(hipError_t e, const char* what) {
   if (e != hipSuccess) return fail(IWDFT_ERR_HIP, "%s: %s", what, hipGetErrorString(e));
+  return IWDFT_OK;
+}
+
+// Next set of phase events of a timed call (created on demand), or null when timing is off.
+int next_marks(iwdft_ctx* c, const PhaseEvents** out) {
+  *out = nullptr;
+  if (!c->timing) return IWDFT_OK;
+  if (c->marks_used == c->marks.size()) {
+    PhaseEvents m;
+    for (int i = 0; i < 4; ++i) {
+      hipError_t e = hipEventCreate(&m.ev[i]);
+      if (e != hipSuccess) {
+        for (int j = 0; j < i; ++j) (void)hipEventDestroy(m.ev[j]);
+        return fail(IWDFT_ERR_HIP, "hipEventCreate: %s", hipGetErrorString(e));
+      }
+    }
+    c->marks.push_back(m);
+  }
+  *out = &c->marks[c->marks_used++];
   return IWDFT_OK;
 }
 
@@ -297,7 +322,41 @@ int iwdft_create(const iwdft_desc* desc, void* d_state, size_t state_bytes, void
 }
 
 int iwdft_destroy(iwdft_ctx* ctx) {
+  if (ctx)
+    for (auto& m : ctx->marks)
+      for (int i = 0; i < 4; ++i) (void)hipEventDestroy(m.ev[i]);
   delete ctx;
+  return IWDFT_OK;
+}
+
+int iwdft_phase_timing(iwdft_ctx* ctx, int enable) {
+  int rc = check_ctx(ctx);
+  if (rc != IWDFT_OK) return rc;
+  ctx->timing = enable != 0;
+  return IWDFT_OK;
+}
+
+int iwdft_phase_times(iwdft_ctx* ctx, double* ms, int64_t* n_calls) {
+  int rc = check_ctx(ctx);
+  if (rc != IWDFT_OK) return rc;
+  if (!ms || !n_calls) return fail(IWDFT_ERR_ARG, "ms / n_calls is NULL");
+  ms[0] = ms[1] = ms[2] = 0.0;
+  *n_calls = 0;
+  for (size_t i = 0; i < ctx->marks_used; ++i) {
+    const PhaseEvents& m = ctx->marks[i];
+    hipError_t e = hipEventSynchronize(m.ev[3]);
+    for (int p = 0; p < 3 && e == hipSuccess; ++p) {
+      float t = 0.f;
+      e = hipEventElapsedTime(&t, m.ev[p], m.ev[p + 1]);
+      ms[p] += t;
+    }
+    if (e != hipSuccess) {
+      ctx->marks_used = 0;
+      return fail(IWDFT_ERR_HIP, "reading phase events: %s", hipGetErrorString(e));
+    }
+  }
+  *n_calls = (int64_t)ctx->marks_used;
+  ctx->marks_used = 0;
   return IWDFT_OK;
 }
 
@@ -379,11 +438,40 @@ int compressed_decode_attn(iwdft_ctx* ctx, const void* d_q, void* d_out, float s
   if (!std::isfinite(scale)) return fail(IWDFT_ERR_ARG, "scale is not finite");
   if (scale <= 0.0f) scale = 1.0f / std::sqrt((float)ctx->desc.head_dim);
   const Plan& pl = ctx->plan;
+  const PhaseEvents* marks = nullptr;
+  if ((rc = next_marks(ctx, &marks)) != IWDFT_OK) return rc;
   return launched(launch_attn(ctx->P, d_q, d_out, scale, (float2*)(ctx->ws + pl.off_qc),
                               (float2*)(ctx->ws + pl.off_Pn), (float*)(ctx->ws + pl.off_pe),
                               (float*)(ctx->ws + pl.off_direct),
-                              pl.use_fft, (hipStream_t)hip_stream),
+                              pl.use_fft, marks, (hipStream_t)hip_stream),
                   "decode attention launch");
+}
+
+int iwdft_append_attn(iwdft_ctx* ctx, const void* d_tok_k, const void* d_tok_v, const void* d_q, void* d_out,
+                      float scale, void* hip_stream) {
+  int rc = check_ctx(ctx);
+  if (rc != IWDFT_OK) return rc;
+  if (!d_tok_k || !d_tok_v || !d_q || !d_out) return fail(IWDFT_ERR_ARG, "a token / query / output pointer is NULL");
+  if (ctx->T < ctx->desc.M) return fail(IWDFT_ERR_STATE, "iwdft_append_attn before iwdft_prefill");
+  if (!std::isfinite(scale)) return fail(IWDFT_ERR_ARG, "scale is not finite");
+  if (scale <= 0.0f) scale = 1.0f / std::sqrt((float)ctx->desc.head_dim);
+  if (!step_can_fuse(ctx->P)) {  // more query heads per KV head than one pass holds: plain sequence
+    rc = iwdft_append(ctx, d_tok_k, d_tok_v, hip_stream);
+    if (rc != IWDFT_OK) return rc;
+    return compressed_decode_attn(ctx, d_q, d_out, scale, hip_stream);
+  }
+  const Plan& pl = ctx->plan;
+  const uint32_t ring_pos = ctx->P.R ? (uint32_t)((ctx->T - ctx->desc.M) % ctx->P.R) : 0u;
+  const PhaseEvents* marks = nullptr;
+  if ((rc = next_marks(ctx, &marks)) != IWDFT_OK) return rc;
+  rc = launched(launch_step(ctx->P, d_tok_k, d_tok_v, d_q, d_out, scale, (float2*)(ctx->ws + pl.off_qc),
+                            (float2*)(ctx->ws + pl.off_Pn), (float*)(ctx->ws + pl.off_pe),
+                            ctx->ws + pl.off_stageK, ctx->ws + pl.off_stageV, (float*)(ctx->ws + pl.off_direct),
+                            pl.use_fft, t_shift(ctx), ring_pos, marks, (hipStream_t)hip_stream),
+                "fused decode step launch");
+  if (rc != IWDFT_OK) return rc;
+  ctx->T += 1;
+  return IWDFT_OK;
 }
 
 }  // extern "C"

@@ -51,14 +51,29 @@ __device__ __forceinline__ const void* exact_row(const Params& P, bool value, in
 }
 
 // ------------------------------------------------------------------------------------------ A
-constexpr int kQcThreads = 256;
-constexpr int kQcBins = kQcThreads * 2;
+// Block size of kernel A: the read-only form streams best with 256 threads; the read-modify-write
+// form of the fused step measured ~10 % faster with 512 (206 -> 186 us on 32 x 8 x 2048 bins).
+constexpr int qc_threads(bool upd) { return upd ? 512 : 256; }
+constexpr int qc_bins(bool upd) { return qc_threads(upd) * 2; }
+
+// Token to absorb in the fused decode step (see launch_step): x[slice * stride + channel], and the
+// slot shift (T - M) mod M of the step.
+struct StepUpdate {
+  const void* xk;
+  const void* xv;
+  int64_t stride;
+  uint32_t tsh;
+};
 
 // grid: (slice * chunks + chunk) * passes + pass.  Lane = two adjacent bins, loop over channels.
-template <bool BF16, int GT>
-__global__ __launch_bounds__(kQcThreads) void attn_qc_kernel(Params P, const void* __restrict__ q,
+// UPD: fused decode step -- every K coefficient first absorbs the token (the streaming update,
+// Eq. infi-dft in the fixed frame: F += x e^{+j 2 pi k (T-M)/M}), is written back, and the updated
+// value feeds qc, so that K coefficients are read once per step instead of twice (needs passes == 1).
+template <bool BF16, int GT, bool UPD>
+__global__ __launch_bounds__(qc_threads(UPD)) void attn_qc_kernel(Params P, const void* __restrict__ q,
                                                             float2* __restrict__ qc, float* __restrict__ pe,
-                                                            int chunks, int passes) {
+                                                            int chunks, int passes, StepUpdate up) {
+  constexpr int kQcThreads = qc_threads(UPD), kQcBins = qc_bins(UPD);
   __shared__ float qs[GT][kHeadDim];
   uint32_t bid = blockIdx.x;
   const int pass = bid % passes;
@@ -102,8 +117,20 @@ __global__ __launch_bounds__(kQcThreads) void attn_qc_kernel(Params P, const voi
   }
   const int i0 = chunk * kQcBins + threadIdx.x * 2;
   if (i0 >= L.Bp) return;
-  const v4f* row = (const v4f*)(P.FK + L.coef_off + (int64_t)s * kHeadDim * L.Bp + i0);
+  v4f* row = (v4f*)(P.FK + L.coef_off + (int64_t)s * kHeadDim * L.Bp + i0);
   const int64_t stride = L.Bp / 2;
+  v4f tw = (v4f)(0.f);  // twiddles of this lane's two bins; padding entries keep 0 and are not written
+  const bool live = i0 < L.nb;
+  if (UPD && live) {
+    const float2 w0 = cis(mulmod((uint32_t)P.bins[L.bin_off + i0], up.tsh, P.M, P.Mmask), P.M);
+    tw.x = w0.x;
+    tw.y = w0.y;
+    if (i0 + 1 < L.nb) {
+      const float2 w1 = cis(mulmod((uint32_t)P.bins[L.bin_off + i0 + 1], up.tsh, P.M, P.Mmask), P.M);
+      tw.z = w1.x;
+      tw.w = w1.y;
+    }
+  }
   v4f acc[GT];
 #pragma unroll
   for (int g = 0; g < GT; ++g) acc[g] = (v4f)(0.f);
@@ -113,6 +140,16 @@ __global__ __launch_bounds__(kQcThreads) void attn_qc_kernel(Params P, const voi
     v4f f[U];
 #pragma unroll
     for (int u = 0; u < U; ++u) f[u] = __builtin_nontemporal_load(row + (d + u) * stride);
+    if constexpr (UPD) {
+      float x[U];
+#pragma unroll
+      for (int u = 0; u < U; ++u) x[u] = load_kv<BF16>(up.xk, (int64_t)slice * up.stride + d + u);
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        f[u] += x[u] * tw;
+        if (live) __builtin_nontemporal_store(f[u], row + (d + u) * stride);
+      }
+    }
 #pragma unroll
     for (int u = 0; u < U; ++u)
 #pragma unroll
@@ -162,10 +199,14 @@ __device__ __forceinline__ float wave_reduce_scatter(float (&v)[V], int lane) {
 // The coefficient loads are ordinary (cacheable) loads on purpose: what they leave in the
 // memory-side cache is V state the next append reads first (measured: append 357 -> 326 us on the
 // 32 x 8 x 2048-bin workload, this kernel +5 us).
-template <bool BF16, int GT>
+// UPD: fused decode step -- every V coefficient absorbs the token on its way through (written back,
+// the updated value is what attention uses), so V coefficients are read once per step too.  There
+// the state is touched once per step and nothing gains from caching it: streaming (non-temporal)
+// loads and stores measured 195 -> 177 us.
+template <bool BF16, int GT, bool UPD>
 __global__ __launch_bounds__(kOutThreads) void attn_out_kernel(Params P, const float2* __restrict__ Pn,
                                                               void* __restrict__ out, const float* __restrict__ pe,
-                                                              int passes, int per_xcd, int total) {
+                                                              int passes, int per_xcd, int total, StepUpdate up) {
   constexpr int V = kOutDC * GT;
   constexpr int VR = V > 64 ? 64 : V;  // values per reduction round
   __shared__ float red[kOutThreads / 64][V];
@@ -182,12 +223,17 @@ __global__ __launch_bounds__(kOutThreads) void attn_out_kernel(Params P, const f
   const int g0 = pass * GT;
   const int d0 = dc * kOutDC;
   const int64_t stride = L.Bp / 2;
-  const v4f* Fv = (const v4f*)(P.FV + L.coef_off + ((int64_t)s * kHeadDim + d0) * L.Bp);
+  v4f* Fv = (v4f*)(P.FV + L.coef_off + ((int64_t)s * kHeadDim + d0) * L.Bp);
   const float2* Prow = Pn + L.ws_off + ((int64_t)s * P.G + g0) * L.Bp;
 
   float acc[V];
 #pragma unroll
   for (int v = 0; v < V; ++v) acc[v] = 0.f;
+  float xr[UPD ? kOutDC : 1];
+  if constexpr (UPD) {
+#pragma unroll
+    for (int dd = 0; dd < kOutDC; ++dd) xr[dd] = load_kv<BF16>(up.xv, (int64_t)slice * up.stride + d0 + dd);
+  }
 
   for (int i0 = threadIdx.x * 2; i0 < L.Bp; i0 += kOutThreads * 2) {
     v4f p[GT];
@@ -196,7 +242,26 @@ __global__ __launch_bounds__(kOutThreads) void attn_out_kernel(Params P, const f
       p[g] = (g0 + g < P.G) ? *(const v4f*)(Prow + (int64_t)g * L.Bp + i0) : (v4f)(0.f);
     v4f f[kOutDC];
 #pragma unroll
-    for (int dd = 0; dd < kOutDC; ++dd) f[dd] = Fv[dd * stride + i0 / 2];
+    for (int dd = 0; dd < kOutDC; ++dd)
+      f[dd] = UPD ? __builtin_nontemporal_load(Fv + dd * stride + i0 / 2) : Fv[dd * stride + i0 / 2];
+    if constexpr (UPD) {
+      if (i0 < L.nb) {  // padding entries are never written
+        v4f tw = (v4f)(0.f);
+        const float2 w0 = cis_poly(mulmod((uint32_t)P.bins[L.bin_off + i0], up.tsh, P.M, P.Mmask), P.M);
+        tw.x = w0.x;
+        tw.y = w0.y;
+        if (i0 + 1 < L.nb) {
+          const float2 w1 = cis_poly(mulmod((uint32_t)P.bins[L.bin_off + i0 + 1], up.tsh, P.M, P.Mmask), P.M);
+          tw.z = w1.x;
+          tw.w = w1.y;
+        }
+#pragma unroll
+        for (int dd = 0; dd < kOutDC; ++dd) {
+          f[dd] += xr[dd] * tw;
+          __builtin_nontemporal_store(f[dd], Fv + dd * stride + i0 / 2);
+        }
+      }
+    }
 #pragma unroll
     for (int dd = 0; dd < kOutDC; ++dd)
 #pragma unroll
@@ -724,11 +789,17 @@ __global__ __launch_bounds__(kDirThreads) void attn_direct_kernel(Params P, cons
 }
 
 // --------------------------------------------------------------------------------------- host
+static int heads_per_pass(int G) { return G >= 8 ? 8 : (G > 2 ? 4 : G); }  // 1, 2, 4 or 8
+
+// up != nullptr: fused decode step (the token is absorbed inside kernels A and C).
 template <bool BF16>
 static hipError_t launch_attn_t(const Params& P, const void* q, void* out, float scale, float2* qc,
-                                float2* Pn, float* pe, float* direct_scratch, bool use_fft, hipStream_t st) {
-  const int GT = P.G >= 8 ? 8 : (P.G > 2 ? 4 : P.G);  // 1, 2, 4 or 8 heads per pass
+                                float2* Pn, float* pe, float* direct_scratch, bool use_fft,
+                                const StepUpdate* up, const PhaseEvents* marks, hipStream_t st) {
+  const int GT = heads_per_pass(P.G);
   const int passes = (P.G + GT - 1) / GT;
+  const StepUpdate u = up ? *up : StepUpdate{nullptr, nullptr, 0, 0};
+  const int kQcThreads = qc_threads(up != nullptr), kQcBins = qc_bins(up != nullptr);
   const int chunks = (P.max_Bp + kQcBins - 1) / kQcBins;
   const uint64_t gridA = (uint64_t)P.n_slices * chunks * passes;
   const uint64_t gridC = (uint64_t)P.n_slices * (kHeadDim / kOutDC) * passes;
@@ -736,17 +807,26 @@ static hipError_t launch_attn_t(const Params& P, const void* q, void* out, float
   if (gridA > 0x7fffffffull || gridC > 0x7fffffffull || gridBd > 0x7fffffffull)
     return hipErrorInvalidConfiguration;
 
-#define IWDFT_GT_SWITCH(KERNEL, GRID, THREADS, ...)                                                 \
-  switch (GT) {                                                                                     \
-    case 1: KERNEL<BF16, 1><<<dim3((uint32_t)(GRID)), dim3(THREADS), 0, st>>>(__VA_ARGS__); break;  \
-    case 2: KERNEL<BF16, 2><<<dim3((uint32_t)(GRID)), dim3(THREADS), 0, st>>>(__VA_ARGS__); break;  \
-    case 4: KERNEL<BF16, 4><<<dim3((uint32_t)(GRID)), dim3(THREADS), 0, st>>>(__VA_ARGS__); break;  \
-    default: KERNEL<BF16, 8><<<dim3((uint32_t)(GRID)), dim3(THREADS), 0, st>>>(__VA_ARGS__); break; \
+#define IWDFT_GT_SWITCH1(KERNEL, UPD, GRID, THREADS, ...)                                                \
+  switch (GT) {                                                                                          \
+    case 1: KERNEL<BF16, 1, UPD><<<dim3((uint32_t)(GRID)), dim3(THREADS), 0, st>>>(__VA_ARGS__); break;  \
+    case 2: KERNEL<BF16, 2, UPD><<<dim3((uint32_t)(GRID)), dim3(THREADS), 0, st>>>(__VA_ARGS__); break;  \
+    case 4: KERNEL<BF16, 4, UPD><<<dim3((uint32_t)(GRID)), dim3(THREADS), 0, st>>>(__VA_ARGS__); break;  \
+    default: KERNEL<BF16, 8, UPD><<<dim3((uint32_t)(GRID)), dim3(THREADS), 0, st>>>(__VA_ARGS__); break; \
   }
+#define IWDFT_GT_SWITCH(KERNEL, GRID, THREADS, ...)                         \
+  if (up) { IWDFT_GT_SWITCH1(KERNEL, true, GRID, THREADS, __VA_ARGS__) }    \
+  else { IWDFT_GT_SWITCH1(KERNEL, false, GRID, THREADS, __VA_ARGS__) }
 
-  IWDFT_GT_SWITCH(attn_qc_kernel, gridA, kQcThreads, P, q, qc, pe, chunks, passes)
-  hipError_t e = hipGetLastError();
+  if (up && passes != 1) return hipErrorInvalidValue;  // the fused step needs all heads in one pass
+  hipError_t e = hipSuccess;
+#define IWDFT_MARK(I)                                            \
+  if (marks && (e = hipEventRecord(marks->ev[I], st)) != hipSuccess) return e;
+  IWDFT_MARK(0)
+  IWDFT_GT_SWITCH(attn_qc_kernel, gridA, kQcThreads, P, q, qc, pe, chunks, passes, u)
+  e = hipGetLastError();
   if (e != hipSuccess) return e;
+  IWDFT_MARK(1)
 
   if (use_fft) {
     int logM = 0;
@@ -786,17 +866,69 @@ static hipError_t launch_attn_t(const Params& P, const void* q, void* out, float
   }
   e = hipGetLastError();
   if (e != hipSuccess) return e;
+  IWDFT_MARK(2)
 
   const int per_xcd = (int)((gridC + 7) / 8);
-  IWDFT_GT_SWITCH(attn_out_kernel, (uint64_t)per_xcd * 8, kOutThreads, P, Pn, out, pe, passes, per_xcd, (int)gridC)
+  IWDFT_GT_SWITCH(attn_out_kernel, (uint64_t)per_xcd * 8, kOutThreads, P, Pn, out, pe, passes, per_xcd, (int)gridC, u)
 #undef IWDFT_GT_SWITCH
-  return hipGetLastError();
+#undef IWDFT_GT_SWITCH1
+  e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  IWDFT_MARK(3)
+#undef IWDFT_MARK
+  return hipSuccess;
 }
 
 hipError_t launch_attn(const Params& P, const void* q, void* out, float scale, float2* qc, float2* Pn,
-                       float* pe, float* direct_scratch, bool use_fft, hipStream_t st) {
-  return P.kv_dtype == 1 ? launch_attn_t<true>(P, q, out, scale, qc, Pn, pe, direct_scratch, use_fft, st)
-                         : launch_attn_t<false>(P, q, out, scale, qc, Pn, pe, direct_scratch, use_fft, st);
+                       float* pe, float* direct_scratch, bool use_fft, const PhaseEvents* marks,
+                       hipStream_t st) {
+  return P.kv_dtype == 1
+             ? launch_attn_t<true>(P, q, out, scale, qc, Pn, pe, direct_scratch, use_fft, nullptr, marks, st)
+             : launch_attn_t<false>(P, q, out, scale, qc, Pn, pe, direct_scratch, use_fft, nullptr, marks, st);
+}
+
+// Recent window, fused step: the oldest ring token moves to the staging row (it is what the
+// coefficients absorb in this step) and the new token takes its slot, so that the attention
+// kernels already see the updated window.  grid: slice ; y: tensor; 128 threads = channels.
+template <bool BF16>
+__global__ __launch_bounds__(kHeadDim) void ring_swap_kernel(Params P, const void* __restrict__ tok_k,
+                                                            const void* __restrict__ tok_v, void* stage_k,
+                                                            void* stage_v, uint32_t pos) {
+  const int slice = blockIdx.x;
+  const void* tok = blockIdx.y ? tok_v : tok_k;
+  void* ring = blockIdx.y ? P.ringV : P.ringK;
+  void* stage = blockIdx.y ? stage_v : stage_k;
+  const int64_t src = (int64_t)slice * kHeadDim + threadIdx.x;
+  const int64_t slot = ((int64_t)slice * P.R + pos) * kHeadDim + threadIdx.x;
+  if constexpr (BF16) {
+    ((uint16_t*)stage)[src] = ((uint16_t*)ring)[slot];
+    ((uint16_t*)ring)[slot] = ((const uint16_t*)tok)[src];
+  } else {
+    ((float*)stage)[src] = ((float*)ring)[slot];
+    ((float*)ring)[slot] = ((const float*)tok)[src];
+  }
+}
+
+bool step_can_fuse(const Params& P) { return (P.G + heads_per_pass(P.G) - 1) / heads_per_pass(P.G) == 1; }
+
+hipError_t launch_step(const Params& P, const void* tok_k, const void* tok_v, const void* q, void* out,
+                       float scale, float2* qc, float2* Pn, float* pe, void* stage_k, void* stage_v,
+                       float* direct_scratch, bool use_fft, uint32_t tsh, uint32_t ring_pos,
+                       const PhaseEvents* marks, hipStream_t st) {
+  StepUpdate up{tok_k, tok_v, kHeadDim, tsh};
+  if (P.R > 0) {
+    if (P.kv_dtype == 1)
+      ring_swap_kernel<true><<<dim3((uint32_t)P.n_slices, 2), dim3(kHeadDim), 0, st>>>(P, tok_k, tok_v, stage_k, stage_v, ring_pos);
+    else
+      ring_swap_kernel<false><<<dim3((uint32_t)P.n_slices, 2), dim3(kHeadDim), 0, st>>>(P, tok_k, tok_v, stage_k, stage_v, ring_pos);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    up.xk = stage_k;
+    up.xv = stage_v;
+  }
+  return P.kv_dtype == 1
+             ? launch_attn_t<true>(P, q, out, scale, qc, Pn, pe, direct_scratch, use_fft, &up, marks, st)
+             : launch_attn_t<false>(P, q, out, scale, qc, Pn, pe, direct_scratch, use_fft, &up, marks, st);
 }
 
 }  // namespace iwdft

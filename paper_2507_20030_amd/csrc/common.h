@@ -129,9 +129,26 @@ hipError_t launch_export(const Params& P, int layer, float* SK, float* SV, uint3
                          float inv_T, hipStream_t st);
 hipError_t launch_reconstruct(const Params& P, int layer, uint32_t a0, uint32_t n_slots, void* Kt,
                               void* Vt, uint32_t t_shift, hipStream_t st);
+// Optional timing marks of the three attention phases: ev[0] before A, ev[1] after A (q against
+// the K coefficients), ev[2] after B (softmax through the transforms), ev[3] after C (output from
+// the V coefficients).
+struct PhaseEvents {
+  hipEvent_t ev[4];
+};
 // pe: [slice][query head][S + R] normalised softmax weights of the exact tokens (workspace).
+// marks may be null.
 hipError_t launch_attn(const Params& P, const void* q, void* out, float scale, float2* qc,
-                       float2* Pn, float* pe, float* direct_scratch, bool use_fft, hipStream_t st);
+                       float2* Pn, float* pe, float* direct_scratch, bool use_fft,
+                       const PhaseEvents* marks, hipStream_t st);
+
+// One decode step = append + attention with the update fused into the attention kernels (each
+// coefficient read once and written once).  stage_k / stage_v: [slice][128] kv_dtype rows for the
+// token leaving the recent window (used when R > 0).  step_can_fuse: all query heads fit one pass.
+bool step_can_fuse(const Params& P);
+hipError_t launch_step(const Params& P, const void* tok_k, const void* tok_v, const void* q, void* out,
+                       float scale, float2* qc, float2* Pn, float* pe, void* stage_k, void* stage_v,
+                       float* direct_scratch, bool use_fft, uint32_t t_shift, uint32_t ring_pos,
+                       const PhaseEvents* marks, hipStream_t st);
 
 // Raises a kernel's dynamic-LDS limit once per (kernel, device); one static instance per kernel.
 struct LdsLimit {

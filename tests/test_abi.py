@@ -77,6 +77,9 @@ def test_null_pointers_and_null_ctx():
     assert lib.iwdft_num_tokens(None) == -1
     assert lib.iwdft_destroy(None) == B.IWDFT_OK
     assert lib.iwdft_set_num_tokens(None, 5) == B.IWDFT_ERR_ARG
+    assert lib.iwdft_phase_timing(None, 1) == B.IWDFT_ERR_ARG
+    ms, n = (ctypes.c_double * 3)(), ctypes.c_int64()
+    assert lib.iwdft_phase_times(None, ms, ctypes.byref(n)) == B.IWDFT_ERR_ARG
     d = desc()
     out = ctypes.c_void_p()
     assert lib.iwdft_create(ctypes.byref(d.c), None, 0, None, 0, ctypes.byref(out)) == B.IWDFT_ERR_ARG

@@ -130,7 +130,7 @@ def check_masks(cache, bins):
         assert got.dtype == np.int32 and np.array_equal(got, np.asarray(b, np.int32)), f"mask of layer {l}"
 
 
-def run_stream(cfg, bins, weights=None, flags=0, steps=None, slices=None, rec=(0, 64), tag=""):
+def run_stream(cfg, bins, weights=None, flags=0, steps=None, slices=None, rec=(0, 64), tag="", fused=False):
     steps = cfg.steps if steps is None else steps
     slices = wl.sample_slices(cfg) if slices is None else slices
     K, V = wl.prefill_tensors(cfg, DEV)
@@ -145,9 +145,17 @@ def run_stream(cfg, bins, weights=None, flags=0, steps=None, slices=None, rec=(0
     worst_attn = 0.0
     for i in range(steps):
         tk, tv, q = wl.decode_step(cfg, i, DEV)
-        cache.append(tk, tv)
         ora.append(tk, tv)
-        worst_attn = max(worst_attn, check_attn(cfg, cache, ora, q, f"{tag} step {i}"))
+        if fused:  # one call: append, then attend
+            out = cache.step(tk, tv, q)
+            ref = ora.attend(q)
+            G = cfg.group
+            w = max(rel_l2(f64(out[l, b, h * G:(h + 1) * G]), r) for (l, b, h), r in ref.items())
+            assert w < TOL_ATTN[cfg.torch_dtype], f"{tag} fused step {i}: attention rel-L2 {w:.3e}"
+            worst_attn = max(worst_attn, w)
+        else:
+            cache.append(tk, tv)
+            worst_attn = max(worst_attn, check_attn(cfg, cache, ora, q, f"{tag} step {i}"))
     assert cache.T == cfg.L + steps
     stats["attn"] = worst_attn
     stats["coefN"] = check_coeffs(cache, ora, tag + " after appends")
@@ -289,6 +297,73 @@ def test_windows_all_bins_equals_full_attention_over_the_whole_context():
 def test_cfg2_with_paper_windows_full_size():
     cfg = wl.CONFIGS["cfg2w"]
     run_stream(cfg, wl.layer_bins(cfg), steps=3, tag="cfg2w")
+
+
+def test_fused_step_cfg1():
+    cfg = wl.CONFIGS["cfg1"]
+    run_stream(cfg, wl.layer_bins(cfg), fused=True, tag="cfg1-fused")
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("L,S,R,group", [(256, 0, 0, 2), (1024, 3, 5, 3), (96, 4, 7, 1), (2048, 0, 0, 8),
+                                         (512, 2, 3, 16)])
+def test_fused_step_ragged_and_windows(dtype, L, S, R, group):
+    # the fused call must give what append + attend give; group 16 needs two head passes and takes the
+    # unfused sequence inside the library
+    cfg = small_cfg(L=L, group=group, dtype=dtype, n_bins=min(77, L // 2 + 5), n_sink=S, n_recent=R, steps=9)
+    run_stream(cfg, random_bins(cfg, 23), rec=(3, 50), fused=True, tag=f"fused-{dtype}-L{L}-S{S}-R{R}-G{group}")
+
+
+def test_fused_step_leaves_the_same_state_as_append():
+    cfg = small_cfg(L=512, n_bins=100, group=4, dtype="bf16", n_sink=3, n_recent=4, steps=6)
+    bins = random_bins(cfg, 29)
+    K, V = wl.prefill_tensors(cfg, DEV)
+    a, b = make_cache(cfg, bins), make_cache(cfg, bins)
+    a.prefill(K, V)
+    b.prefill(K, V)
+    for i in range(cfg.steps):
+        tk, tv, q = wl.decode_step(cfg, i, DEV)
+        a.append(tk, tv)
+        oa = a.attend(q)
+        ob = b.step(tk, tv, q)
+        assert rel_l2(f64(ob), f64(oa)) < 5e-3
+    assert a.T == b.T
+    for l in range(cfg.n_layers):
+        (ka, va), (kb, vb) = a.export_coeffs(l), b.export_coeffs(l)
+        assert rel_l2(c128(kb), c128(ka)) < 1e-6 and rel_l2(c128(vb), c128(va)) < 1e-6
+    a.close()
+    b.close()
+
+
+def test_phase_timing_marks_calls_without_changing_results():
+    cfg = small_cfg(L=1024, n_bins=200, group=4, dtype="bf16", n_sink=2, n_recent=3, steps=4)
+    bins = random_bins(cfg, 31)
+    K, V = wl.prefill_tensors(cfg, DEV)
+    a, b = make_cache(cfg, bins), make_cache(cfg, bins)
+    a.prefill(K, V)
+    b.prefill(K, V)
+    B.iwdft_phase_timing(b.ctx, True)
+    for i in range(cfg.steps):
+        tk, tv, q = wl.decode_step(cfg, i, DEV)
+        oa = a.step(tk, tv, q)
+        ob = b.step(tk, tv, q)
+        assert torch.equal(oa, ob)
+        assert torch.equal(a.attend(q), b.attend(q))
+    ms, n = B.iwdft_phase_times(b.ctx)
+    assert n == 2 * cfg.steps and all(0.0 < m < 1e3 for m in ms)
+    ms, n = B.iwdft_phase_times(b.ctx)       # the read-out cleared the list
+    assert n == 0 and ms == [0.0, 0.0, 0.0]
+    B.iwdft_phase_timing(b.ctx, False)
+    tk, tv, q = wl.decode_step(cfg, 0, DEV)
+    b.step(tk, tv, q)
+    assert B.iwdft_phase_times(b.ctx)[1] == 0
+    a.close()
+    b.close()
+
+
+def test_fused_step_cfg2_windows_full_size():
+    cfg = wl.CONFIGS["cfg2w"]
+    run_stream(cfg, wl.layer_bins(cfg), steps=3, fused=True, tag="cfg2w-fused")
 
 
 def test_cfg2_full_size_sampled_slices():
