@@ -166,11 +166,31 @@ def main():
     torch.cuda.synchronize()
     rec_ms = r0.elapsed_time(r1)
 
+    # the dense (matrix-core) prefill on its own, whatever the job used
+    pre_kind = B.iwdft_prefill_kind(cache.ctx)
+    if pre_kind == "dense":
+        dense_ms = float(pre_ms.mean())
+    else:
+        dcache = B.Cache(cfg.n_layers, cfg.batch, cfg.n_kv_heads, cfg.n_q_heads, cfg.head_dim, cfg.torch_dtype,
+                         cfg.L, bins, flags=B.IWDFT_FLAG_DENSE_PREFILL, device=dev)
+        dcache.prefill(K, V, stream)
+        de = mk(2 * 3)
+        for i in range(3):
+            de[2 * i].record(stream)
+            dcache.prefill(K, V, stream)
+            de[2 * i + 1].record(stream)
+        torch.cuda.synchronize()
+        dense_ms = float(np.mean([de[2 * i].elapsed_time(de[2 * i + 1]) for i in range(3)]))
+        dcache.close()
+        del dcache
+
     nb_total = sum(len(b) for b in bins) * cfg.batch * cfg.n_kv_heads      # kept bins x slices
     coef_bytes = nb_total * cfg.head_dim * 8                               # one tensor, complex fp32
     append_bytes = 2 * coef_bytes * 2                                      # K and V, read + write
     attn_bytes = 2 * coef_bytes                                            # K and V read once
     prefill_useful_flop = 2.0 * 2 * nb_total * cfg.L * cfg.head_dim * 2     # cos+sin rows, K and V
+    mfma_split = 2 if cfg.dtype == "bf16" else 3                           # fp16 hi/lo basis (x fp32 input split)
+    kv_in_bytes = 2 * cfg.n_slices * cfg.L * cfg.head_dim * (2 if cfg.dtype == "bf16" else 4)
     app_avg, att_avg, pre_avg = float(app_ms.mean()), float(att_ms.mean()), float(pre_ms.mean())
     step_avg = float(step_ms.mean())
     tokens = args.steps * dsteps * cfg.batch
@@ -225,8 +245,15 @@ def main():
                                        "algorithmic_GB": attn_bytes / 1e9,
                                        "GBps": gbps(attn_bytes, att_avg),
                                        "frac_hbm_peak": gbps(attn_bytes, att_avg) / HBM_PEAK_GBS},
-            "iwdft_prefill": {"avg_ms": pre_avg, "useful_TFLOP": prefill_useful_flop / 1e12,
-                              "useful_TFLOPps": prefill_useful_flop / (pre_avg * 1e-3) / 1e12},
+            "iwdft_prefill": {"kind": pre_kind, "avg_ms": pre_avg,
+                              "algorithmic_GB": (kv_in_bytes + 2 * coef_bytes) / 1e9,
+                              "GBps": gbps(kv_in_bytes + 2 * coef_bytes, pre_avg),
+                              "dense_equivalent_TFLOPps": prefill_useful_flop / (pre_avg * 1e-3) / 1e12},
+            "iwdft_prefill_dense": {"avg_ms": dense_ms, "useful_TFLOP": prefill_useful_flop / 1e12,
+                                    "useful_TFLOPps": prefill_useful_flop / (dense_ms * 1e-3) / 1e12,
+                                    "executed_TFLOPps": mfma_split * prefill_useful_flop / (dense_ms * 1e-3) / 1e12,
+                                    "frac_mfma_f16_peak": mfma_split * prefill_useful_flop / (dense_ms * 1e-3) / 1e12
+                                                          / MFMA_F16_PEAK_TFLOPS},
             "iwdft_reconstruct_one_layer": {"ms": rec_ms},
         },
         "roofline": {

@@ -61,9 +61,16 @@ enum { IWDFT_F32 = 0, IWDFT_BF16 = 1 };
 
 /* desc.flags */
 enum {
-  IWDFT_FLAG_DIRECT_SYNTHESIS = 1u /* decode attention evaluates the O(M*|B|) sums
-                                      directly instead of through FFTs (always used
-                                      when M is not a power of two)               */
+  IWDFT_FLAG_DIRECT_SYNTHESIS = 1u, /* decode attention evaluates the O(M*|B|) sums
+                                       directly instead of through FFTs (always used
+                                       when M is not a power of two)               */
+  IWDFT_FLAG_DENSE_PREFILL = 2u,    /* iwdft_prefill always runs the dense contraction
+                                       at the kept bins (matrix cores)             */
+  IWDFT_FLAG_FFT_PREFILL = 4u       /* iwdft_prefill always runs FFTs + pruning; needs
+                                       M = 2^m >= 256 and <= 4096 kept bins per layer,
+                                       else IWDFT_ERR_UNSUPPORTED.  With neither flag
+                                       the library picks: FFT when it applies and some
+                                       layer keeps >= 256 bins                     */
 };
 
 typedef struct {
@@ -102,12 +109,17 @@ int iwdft_create(const iwdft_desc* desc, void* d_state, size_t state_bytes, void
 
 int iwdft_destroy(iwdft_ctx* ctx); /* frees host memory only; NULL is accepted */
 
-/* Prefill transform (Eq. dft-full at the kept bins, Eq. prefill-dft, Eq. freq-zero).
+/* Prefill transform (Eq. dft-full at the kept bins, Eq. prefill-dft, Eq. freq-zero), either as a
+ * dense contraction with an on-chip basis or as FFTs followed by pruning (see desc.flags).
  * d_K, d_V: [n_layers][batch][n_kv_heads][S + M + R][head_dim] contiguous, kv_dtype.
  * Per slice the first S tokens are copied to the sink store, the last R to the recent
  * window, and the middle M tokens are transformed (Sec. 4.2.1).  Overwrites the state;
  * T becomes M. */
 int iwdft_prefill(iwdft_ctx* ctx, const void* d_K, const void* d_V, void* hip_stream);
+
+/* Which transform iwdft_prefill runs for this context: 0 = dense contraction, 1 = FFTs + pruning;
+ * -1 if ctx is NULL. */
+int iwdft_prefill_kind(const iwdft_ctx* ctx);
 
 /* Streaming update with one new token per sequence (Eq. infi-dft, Eq. update-iwdft).
  * d_tok_k, d_tok_v: [n_layers][batch][n_kv_heads][head_dim], kv_dtype.  T -> T+1.

@@ -18,11 +18,13 @@ IWDFT_ERR_ARG, IWDFT_ERR_BINS, IWDFT_ERR_SIZE = -1, -2, -3
 IWDFT_ERR_STATE, IWDFT_ERR_HIP, IWDFT_ERR_UNSUPPORTED = -4, -5, -6
 IWDFT_F32, IWDFT_BF16 = 0, 1
 IWDFT_FLAG_DIRECT_SYNTHESIS = 1
+IWDFT_FLAG_DENSE_PREFILL = 2
+IWDFT_FLAG_FFT_PREFILL = 4
 
 EXPORTED = [
     "iwdft_query_bytes", "iwdft_create", "iwdft_destroy", "iwdft_prefill", "iwdft_append",
     "iwdft_reconstruct", "compressed_decode_attn", "iwdft_append_attn", "iwdft_export_coeffs", "iwdft_export_bins",
-    "iwdft_num_tokens", "iwdft_set_num_tokens", "iwdft_last_error", "iwdft_phase_timing", "iwdft_phase_times",
+    "iwdft_num_tokens", "iwdft_set_num_tokens", "iwdft_last_error", "iwdft_phase_timing", "iwdft_phase_times", "iwdft_prefill_kind",
 ]
 
 LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libiwdft.so")
@@ -70,6 +72,7 @@ def load_library() -> ctypes.CDLL:
     lib.iwdft_reconstruct.argtypes = [vp, i32, i64, i64, vp, vp, vp]
     lib.compressed_decode_attn.argtypes = [vp, vp, vp, f32, vp]
     lib.iwdft_append_attn.argtypes = [vp, vp, vp, vp, vp, f32, vp]
+    lib.iwdft_prefill_kind.argtypes = [vp]
     lib.iwdft_phase_timing.argtypes = [vp, i32]
     lib.iwdft_phase_times.argtypes = [vp, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_int64)]
     lib.iwdft_export_coeffs.argtypes = [vp, i32, vp, vp, vp]
@@ -168,6 +171,10 @@ def compressed_decode_attn(ctx, q: torch.Tensor, out: torch.Tensor, scale: float
 def iwdft_append_attn(ctx, tok_k, tok_v, q, out, scale: float = 0.0, stream=None) -> None:
     _check(load_library().iwdft_append_attn(ctx, _ptr(tok_k), _ptr(tok_v), _ptr(q), _ptr(out), scale,
                                             _stream(stream)))
+
+
+def iwdft_prefill_kind(ctx) -> str:
+    return {0: "dense", 1: "fft"}[load_library().iwdft_prefill_kind(ctx)]
 
 
 def iwdft_phase_timing(ctx, enable: bool) -> None:

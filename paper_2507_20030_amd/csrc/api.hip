@@ -34,7 +34,8 @@ struct Plan {  // byte offsets inside the two caller buffers, derived from a des
   int64_t coef_total = 0;  // float2 per tensor
   int64_t ws_total = 0;    // float2 per workspace array
   int32_t G = 1, max_nb = 0, max_Bp = 0;
-  bool use_fft = false;
+  bool use_fft = false;          // decode attention through FFTs
+  bool use_fft_prefill = false;  // prefill through FFTs (else the dense MFMA contraction)
   size_t off_layers = 0, off_bins = 0, off_weights = 0, off_fold = 0, off_FK = 0, off_FV = 0, state_bytes = 0;
   size_t off_sinkK = 0, off_sinkV = 0, off_ringK = 0, off_ringV = 0;
   size_t off_qc = 0, off_Pn = 0, off_pe = 0, off_stageK = 0, off_stageV = 0, off_direct = 0, ws_bytes = 0;
@@ -42,6 +43,7 @@ struct Plan {  // byte offsets inside the two caller buffers, derived from a des
 
 // Largest problem the FFT attention kernel keeps in registers / LDS.
 constexpr int kFftMaxBins = 4096;
+constexpr int kFftPrefillMinBins = 256;  // fewer kept bins per layer: the dense contraction is faster
 constexpr int kMaxExact = 1024;  // most sink + recent tokens (their scores sit in LDS)
 constexpr uint32_t kFftMinM = 256;
 constexpr int64_t kFftMaxQ = 8192;  // longest transform the FFT attention kernel holds in LDS
@@ -56,8 +58,10 @@ int make_plan(const iwdft_desc* d, Plan* pl) {
   if (d->kv_dtype != IWDFT_F32 && d->kv_dtype != IWDFT_BF16)
     return fail(IWDFT_ERR_ARG, "kv_dtype %d is neither IWDFT_F32 nor IWDFT_BF16", d->kv_dtype);
   if (d->reserved != 0) return fail(IWDFT_ERR_ARG, "reserved must be 0");
-  if (d->flags & ~(uint32_t)IWDFT_FLAG_DIRECT_SYNTHESIS)
+  if (d->flags & ~(uint32_t)(IWDFT_FLAG_DIRECT_SYNTHESIS | IWDFT_FLAG_DENSE_PREFILL | IWDFT_FLAG_FFT_PREFILL))
     return fail(IWDFT_ERR_ARG, "unknown bits in flags: 0x%x", d->flags);
+  if ((d->flags & IWDFT_FLAG_DENSE_PREFILL) && (d->flags & IWDFT_FLAG_FFT_PREFILL))
+    return fail(IWDFT_ERR_ARG, "flags ask for both the dense and the FFT prefill");
   if (d->M < 1 || d->M > ((int64_t)1 << 30))
     return fail(IWDFT_ERR_ARG, "M = %lld outside [1, 2^30]", (long long)d->M);
   if (d->n_sink < 0 || d->n_recent < 0) return fail(IWDFT_ERR_ARG, "n_sink / n_recent is negative");
@@ -114,6 +118,17 @@ int make_plan(const iwdft_desc* d, Plan* pl) {
   const bool pow2 = (d->M & (d->M - 1)) == 0;
   pl->use_fft = pow2 && (uint64_t)d->M >= kFftMinM && pl->max_nb <= kFftMaxBins &&
                 !(d->flags & IWDFT_FLAG_DIRECT_SYNTHESIS);
+  // Prefill: the FFT costs the same whatever the number of kept bins, the dense contraction grows
+  // with it; measured break-even on MI355X is near 256 kept bins per layer.
+  const bool fft_pf_ok = pow2 && (uint64_t)d->M >= kFftMinM && pl->max_nb <= kFftMaxBins;
+  if (d->flags & IWDFT_FLAG_FFT_PREFILL) {
+    if (!fft_pf_ok)
+      return fail(IWDFT_ERR_UNSUPPORTED, "FFT prefill needs M = 2^m >= %d and at most %d kept bins per layer",
+                  (int)kFftMinM, kFftMaxBins);
+    pl->use_fft_prefill = true;
+  } else {
+    pl->use_fft_prefill = fft_pf_ok && !(d->flags & IWDFT_FLAG_DENSE_PREFILL) && pl->max_nb >= kFftPrefillMinBins;
+  }
   pl->fold.assign((size_t)pl->n_bins_total, 0);
   if (pl->use_fft) {
     // The FFT attention kernel folds the sparse spectrum (each bin k and its mirror -k) modulo the
@@ -362,6 +377,8 @@ int iwdft_phase_times(iwdft_ctx* ctx, double* ms, int64_t* n_calls) {
 
 int64_t iwdft_num_tokens(const iwdft_ctx* ctx) { return ctx ? ctx->T : -1; }
 
+int iwdft_prefill_kind(const iwdft_ctx* ctx) { return ctx ? (ctx->plan.use_fft_prefill ? 1 : 0) : -1; }
+
 int iwdft_set_num_tokens(iwdft_ctx* ctx, int64_t T) {
   if (!ctx) return fail(IWDFT_ERR_ARG, "ctx is NULL");
   if (T < ctx->desc.M) return fail(IWDFT_ERR_ARG, "T = %lld is below M", (long long)T);
@@ -373,7 +390,9 @@ int iwdft_prefill(iwdft_ctx* ctx, const void* d_K, const void* d_V, void* hip_st
   int rc = check_ctx(ctx);
   if (rc != IWDFT_OK) return rc;
   if (!d_K || !d_V) return fail(IWDFT_ERR_ARG, "d_K / d_V is NULL");
-  rc = launched(launch_prefill(ctx->P, d_K, d_V, (hipStream_t)hip_stream), "prefill launch");
+  rc = launched(ctx->plan.use_fft_prefill ? launch_prefill_fft(ctx->P, d_K, d_V, (hipStream_t)hip_stream)
+                                          : launch_prefill(ctx->P, d_K, d_V, (hipStream_t)hip_stream),
+                "prefill launch");
   if (rc != IWDFT_OK) return rc;
   ctx->T = ctx->desc.M;
   return IWDFT_OK;

@@ -122,6 +122,11 @@ __device__ __forceinline__ void store_kv(void* p, int64_t i, float v) {
 // Host-side launchers (defined next to their kernels).  Each validates nothing: the C ABI
 // layer has already checked every shape.  They return the hipError_t of the launch.
 hipError_t launch_prefill(const Params& P, const void* K, const void* V, hipStream_t st);
+// The same transform through in-LDS FFTs; prefill_fft_ok: M is a power of two >= 256 and no layer
+// keeps more than 4096 bins.  launch_prefill_edges copies the sink / recent tokens (both prefills).
+bool prefill_fft_ok(const Params& P);
+hipError_t launch_prefill_fft(const Params& P, const void* K, const void* V, hipStream_t st);
+hipError_t launch_prefill_edges(const Params& P, const void* K, const void* V, hipStream_t st);
 // ring_pos: slot of the recent ring that holds the oldest token (ignored when R == 0).
 hipError_t launch_append(const Params& P, const void* tok_k, const void* tok_v, uint32_t t_shift,
                          uint32_t ring_pos, hipStream_t st);

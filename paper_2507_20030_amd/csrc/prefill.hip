@@ -304,11 +304,16 @@ __global__ __launch_bounds__(256) void prefill_edges_kernel(Params P, const void
   for (int e = threadIdx.x; e < P.R * kRowChunks; e += 256) ring[e] = tail[e];
 }
 
+hipError_t launch_prefill_edges(const Params& P, const void* K, const void* V, hipStream_t st) {
+  if (P.S + P.R == 0) return hipSuccess;
+  if (P.kv_dtype == 1) prefill_edges_kernel<true><<<dim3((uint32_t)P.n_slices, 2), dim3(256), 0, st>>>(P, K, V);
+  else prefill_edges_kernel<false><<<dim3((uint32_t)P.n_slices, 2), dim3(256), 0, st>>>(P, K, V);
+  return hipGetLastError();
+}
+
 hipError_t launch_prefill(const Params& P, const void* K, const void* V, hipStream_t st) {
-  if (P.S + P.R > 0) {
-    if (P.kv_dtype == 1) prefill_edges_kernel<true><<<dim3((uint32_t)P.n_slices, 2), dim3(256), 0, st>>>(P, K, V);
-    else prefill_edges_kernel<false><<<dim3((uint32_t)P.n_slices, 2), dim3(256), 0, st>>>(P, K, V);
-    hipError_t e = hipGetLastError();
+  {
+    hipError_t e = launch_prefill_edges(P, K, V, st);
     if (e != hipSuccess) return e;
   }
   const int nt = (P.max_nb + kPfBins - 1) / kPfBins;

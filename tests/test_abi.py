@@ -50,6 +50,9 @@ def test_query_bytes_accounts_for_padded_rows():
     (dict(M=0), B.IWDFT_ERR_ARG),
     (dict(M=(1 << 30) + 1), B.IWDFT_ERR_ARG),
     (dict(flags=8), B.IWDFT_ERR_ARG),
+    (dict(flags=B.IWDFT_FLAG_DENSE_PREFILL | B.IWDFT_FLAG_FFT_PREFILL), B.IWDFT_ERR_ARG),
+    (dict(flags=B.IWDFT_FLAG_FFT_PREFILL), B.IWDFT_ERR_UNSUPPORTED),   # M = 64: below the FFT's smallest length
+    (dict(flags=B.IWDFT_FLAG_FFT_PREFILL, M=768), B.IWDFT_ERR_UNSUPPORTED),  # not a power of two
     (dict(head_dim=64), B.IWDFT_ERR_UNSUPPORTED),
     (dict(n_sink=-1), B.IWDFT_ERR_ARG),
     (dict(n_recent=-3), B.IWDFT_ERR_ARG),
@@ -77,6 +80,7 @@ def test_null_pointers_and_null_ctx():
     assert lib.iwdft_num_tokens(None) == -1
     assert lib.iwdft_destroy(None) == B.IWDFT_OK
     assert lib.iwdft_set_num_tokens(None, 5) == B.IWDFT_ERR_ARG
+    assert lib.iwdft_prefill_kind(None) == -1
     assert lib.iwdft_phase_timing(None, 1) == B.IWDFT_ERR_ARG
     ms, n = (ctypes.c_double * 3)(), ctypes.c_int64()
     assert lib.iwdft_phase_times(None, ms, ctypes.byref(n)) == B.IWDFT_ERR_ARG

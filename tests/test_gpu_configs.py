@@ -12,11 +12,14 @@ from test_gpu_parity import (DEV, SliceOracle, check_attn, check_coeffs, check_m
 pytestmark = pytest.mark.gpu
 
 
-def test_cfg3_batch8_mixed_masks():
+@pytest.mark.parametrize("prefill", ["fft", "dense"])
+def test_cfg3_batch8_mixed_masks(prefill):
+    from paper_2507_20030_amd import binding as B
     cfg = wl.CONFIGS["cfg3"]
     bins = wl.layer_bins(cfg)
     assert any(b[-1] >= cfg.n_bins for b in bins) and any(b[-1] == cfg.n_bins - 1 for b in bins)
-    run_stream(cfg, bins, steps=3, tag="cfg3")
+    flags = B.IWDFT_FLAG_FFT_PREFILL if prefill == "fft" else B.IWDFT_FLAG_DENSE_PREFILL
+    run_stream(cfg, bins, flags=flags, steps=3, tag=f"cfg3-{prefill}")
 
 
 def test_cfg5_wide_outlier_channels():

@@ -366,6 +366,43 @@ def test_fused_step_cfg2_windows_full_size():
     run_stream(cfg, wl.layer_bins(cfg), steps=3, fused=True, tag="cfg2w-fused")
 
 
-def test_cfg2_full_size_sampled_slices():
+@pytest.mark.parametrize("prefill", ["fft", "dense"])
+def test_cfg2_full_size_sampled_slices(prefill):
     cfg = wl.CONFIGS["cfg2"]
-    run_stream(cfg, wl.layer_bins(cfg), steps=3, tag="cfg2")
+    flags = B.IWDFT_FLAG_FFT_PREFILL if prefill == "fft" else B.IWDFT_FLAG_DENSE_PREFILL
+    run_stream(cfg, wl.layer_bins(cfg), flags=flags, steps=3, tag=f"cfg2-{prefill}")
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("L,S,R,n_bins", [(256, 0, 0, 129), (512, 2, 3, 77), (1024, 0, 0, 300), (2048, 0, 5, 77),
+                                          (4096, 0, 0, 1500), (8192, 4, 0, 600), (16384, 0, 0, 900),
+                                          (32768, 3, 2, 2100)])
+def test_fft_prefill_all_transform_lengths(dtype, L, S, R, n_bins):
+    # every transform length of the in-LDS FFT (2^8 .. 2^13) and the decimated form beyond it, ragged
+    # scattered bins (both halves of the spectrum, so k and M - k both occur), with and without windows
+    big = L > 8192
+    cfg = small_cfg(L=L, dtype=dtype, n_bins=n_bins, n_sink=S, n_recent=R, steps=2,
+                    n_layers=1 if big else 2, batch=1 if big else 2)
+    bins = random_bins(cfg, 37)
+    st = run_stream(cfg, bins, flags=B.IWDFT_FLAG_FFT_PREFILL, rec=(3, 50), tag=f"fftpf-{dtype}-L{L}")
+    assert st["coef0"] < 2e-5
+
+
+def test_fft_and_dense_prefill_give_the_same_state():
+    cfg = small_cfg(L=4096, dtype="bf16", n_bins=500, n_sink=2, n_recent=3)
+    bins = random_bins(cfg, 41)
+    K, V = wl.prefill_tensors(cfg, DEV)
+    a, b = make_cache(cfg, bins, flags=B.IWDFT_FLAG_FFT_PREFILL), make_cache(cfg, bins, flags=B.IWDFT_FLAG_DENSE_PREFILL)
+    assert B.iwdft_prefill_kind(a.ctx) == "fft" and B.iwdft_prefill_kind(b.ctx) == "dense"
+    c = make_cache(cfg, bins)                      # no flag: 500 kept bins -> FFT
+    d = make_cache(small_cfg(L=4096, n_bins=100), [np.arange(100, dtype=np.int32)] * 2)   # few bins -> dense
+    assert B.iwdft_prefill_kind(c.ctx) == "fft" and B.iwdft_prefill_kind(d.ctx) == "dense"
+    c.close()
+    d.close()
+    a.prefill(K, V)
+    b.prefill(K, V)
+    for l in range(cfg.n_layers):
+        (ka, va), (kb, vb) = a.export_coeffs(l), b.export_coeffs(l)
+        assert rel_l2(c128(ka), c128(kb)) < 1e-5 and rel_l2(c128(va), c128(vb)) < 1e-5
+    a.close()
+    b.close()
