@@ -24,6 +24,10 @@ Readings of the paper this oracle fixes (the paper leaves them open):
   * reconstruction takes the real part of the masked inverse DFT of the
     UN-normalised spectrum U_T (gain T/M on S_T), output length M.
   * tokens beyond M alias onto the M slots (W_k^M = 1).
+  * frequency chunks (Sec. 3.2): chunk c of C holds the bins
+    floor(c M / C) .. floor((c+1) M / C) - 1 (M need not divide by C); "the top
+    r*C chunks" means n_c = clamp(floor(r C + 1/2), 1, C) chunks, largest
+    Delta first, equal Delta -> lower chunk index first.
 Parity unpinned: the choice among those readings (slot map, real part, gain)
 is not fixed by anything the paper prints; every function below is pinned by
 identities in tests/test_oracle_pins.py.
@@ -36,6 +40,7 @@ __all__ = [
     "W", "prefill", "append", "append_many", "slot", "fold_to_slots",
     "closed_form", "reconstruct", "attention", "decode_attention",
     "stream_decode", "windowed_attention", "windowed_stream_decode",
+    "chunk_bounds", "ablate_chunk", "select_bins",
 ]
 
 
@@ -206,3 +211,39 @@ def windowed_stream_decode(K0, V0, S, R, bins, k_new, v_new, q_new, weights=None
     rk = np.stack(recK) if recK else np.zeros((0, K0.shape[1]))
     rv = np.stack(recV) if recV else np.zeros((0, K0.shape[1]))
     return (np.stack(outs) if outs else np.zeros((0,) + np.shape(q_new)[1:])), SK, SV, T, rk, rv
+
+
+def chunk_bounds(M, C):
+    """Edges of the C contiguous frequency chunks of an M-bin spectrum (Sec. 3.2):
+    chunk c = bins [edges[c], edges[c+1])."""
+    return np.array([(c * int(M)) // int(C) for c in range(int(C) + 1)], dtype=np.int64)
+
+
+def ablate_chunk(x, C, c):
+    """Frequency ablation of one chunk (Sec. 3.2, Eq. freq-zero): DFT of x along the
+    token axis, the coefficients of chunk c set to zero, inverse DFT, real part.
+    x: [M, d] float64.  Returns [M, d] float64."""
+    x = np.asarray(x, dtype=np.float64)
+    M = x.shape[0]
+    e = chunk_bounds(M, C)
+    X = np.fft.fft(x, axis=0)
+    X[e[c]:e[c + 1]] = 0.0
+    return np.fft.ifft(X, axis=0).real
+
+
+def select_bins(delta, M, r):
+    """Greedy mask of Sec. 3.2: per layer keep the n_c chunks with the largest
+    Delta (Eq. delta-ppl) and return their bins, sorted.
+    delta: [layers, C].  n_c = clamp(floor(r C + 1/2), 1, C) in float64;
+    equal Delta: the lower chunk index wins.  Returns a list of int32 arrays."""
+    delta = np.asarray(delta)
+    n_layers, C = delta.shape
+    n_c = int(min(max(np.floor(np.float64(r) * np.float64(C) + np.float64(0.5)), 1), C))
+    e = chunk_bounds(M, C)
+    out = []
+    for l in range(n_layers):
+        order = sorted(range(C), key=lambda c: (-float(delta[l, c]), c))
+        keep = sorted(order[:n_c])
+        b = [np.arange(e[c], e[c + 1], dtype=np.int64) for c in keep]
+        out.append(np.concatenate(b).astype(np.int32) if b else np.zeros(0, np.int32))
+    return out

@@ -337,3 +337,106 @@ def test_windowed_attention_weights_split_between_parts():
     o = orc.windowed_attention(q, K0[:S], V0[:S], orc.prefill(K0[S:S + M], bins), orc.prefill(V0[S:S + M], bins),
                                M, M, bins, K0[S + M:], V0[S + M:])
     np.testing.assert_allclose(o[0], V0[1], atol=1e-9)
+
+
+# ------------------------------------------------------------ frequency chunks (Sec. 3.2)
+def test_chunk_bounds_partition_the_spectrum():
+    for M, C in [(8192, 22), (1024, 22), (22, 22), (100, 7), (16, 1), (5, 8)]:
+        e = orc.chunk_bounds(M, C)
+        assert e[0] == 0 and e[-1] == M and len(e) == C + 1 and np.all(np.diff(e) >= 0)
+        # every bin lies in exactly one chunk, chunk sizes differ by at most one
+        sizes = np.diff(e)
+        assert sizes.sum() == M and sizes.max() - sizes.min() <= 1
+        for k in range(M):
+            assert sum(e[c] <= k < e[c + 1] for c in range(C)) == 1
+
+
+def test_ablate_chunk_brute_force_tiny():
+    M, d, C = 12, 2, 5
+    x = rng(50).normal(size=(M, d))
+    e = [(c * M) // C for c in range(C + 1)]
+    for c in range(C):
+        ref = np.zeros((M, d))
+        for ch in range(d):
+            X = [sum(x[n, ch] * cmath.exp(-2j * math.pi * k * n / M) for n in range(M)) for k in range(M)]
+            for k in range(e[c], e[c + 1]):
+                X[k] = 0.0
+            for n in range(M):
+                ref[n, ch] = (sum(X[k] * cmath.exp(2j * math.pi * k * n / M) for k in range(M)) / M).real
+        np.testing.assert_allclose(orc.ablate_chunk(x, C, c), ref, atol=1e-12)
+
+
+def test_ablate_chunks_partition_identity_and_special_cases():
+    M, d, C = 64, 3, 22
+    x = rng(51).normal(size=(M, d))
+    # the chunks partition the spectrum: removing each once removes everything exactly once
+    total = sum(x - orc.ablate_chunk(x, C, c) for c in range(C))
+    np.testing.assert_allclose(total, x, atol=1e-12)
+    # a single chunk is the whole spectrum
+    np.testing.assert_allclose(orc.ablate_chunk(x, 1, 0), 0.0, atol=1e-12)
+    # M chunks of one bin: chunk 0 is the DC bin, its removal subtracts the mean
+    np.testing.assert_allclose(orc.ablate_chunk(x, M, 0), x - x.mean(axis=0), atol=1e-12)
+    # a cosine at bin k0 has half of its amplitude in k0 and half in M - k0: removing the chunk that holds
+    # only k0 leaves half a cosine (real part of the one-sided remainder).  The real part puts a quarter
+    # back into each of the two bins, so removing M - k0 afterwards leaves a quarter of the cosine
+    k0 = 5
+    n = np.arange(M)
+    cosx = np.cos(2 * np.pi * k0 * n / M)[:, None]
+    np.testing.assert_allclose(orc.ablate_chunk(cosx, M, k0), 0.5 * cosx, atol=1e-12)
+    both = orc.ablate_chunk(orc.ablate_chunk(cosx, M, k0), M, M - k0)
+    np.testing.assert_allclose(both, 0.25 * cosx, atol=1e-12)
+    # ablation is linear
+    y = rng(52).normal(size=(M, d))
+    np.testing.assert_allclose(orc.ablate_chunk(2 * x - 3 * y, C, 4),
+                               2 * orc.ablate_chunk(x, C, 4) - 3 * orc.ablate_chunk(y, C, 4), atol=1e-12)
+
+
+def test_ablate_is_what_a_mask_without_the_chunk_reconstructs():
+    # zeroing chunk c == reconstructing from every bin outside chunk c (ties Eq. freq-zero to the
+    # reconstruction the hot path uses)
+    M, d, C, c = 48, 2, 6, 2
+    x = rng(53).normal(size=(M, d))
+    e = orc.chunk_bounds(M, C)
+    keep = np.array([k for k in range(M) if not (e[c] <= k < e[c + 1])])
+    np.testing.assert_allclose(orc.ablate_chunk(x, C, c), orc.reconstruct(orc.prefill(x, keep), M, M, keep),
+                               atol=1e-12)
+
+
+def test_select_bins_brute_force_with_ties():
+    M, C = 220, 22
+    r = rng(54)
+    delta = r.normal(size=(6, C))
+    delta[1, :] = 0.25                     # all equal: the lowest chunk indices win
+    delta[2, [3, 9, 17]] = delta[2].max() + 1.0   # three-way tie at the top
+    delta[3, 0] = -np.inf
+    for ratio in [0.094, 0.125, 0.25, 0.5, 1.0, 0.0, 0.01]:
+        n_c = min(max(int(math.floor(ratio * C + 0.5)), 1), C)
+        got = orc.select_bins(delta, M, ratio)
+        for l in range(delta.shape[0]):
+            # brute force: repeatedly take the best remaining chunk, lower index on ties
+            left = list(range(C))
+            keep = []
+            for _ in range(n_c):
+                best = left[0]
+                for c in left:
+                    if delta[l, c] > delta[l, best]:
+                        best = c
+                keep.append(best)
+                left.remove(best)
+            ref = sorted(k for c in keep for k in range((c * M) // C, ((c + 1) * M) // C))
+            assert got[l].dtype == np.int32 and list(got[l]) == ref
+    assert [len(b) for b in orc.select_bins(delta, M, 0.094)] == [20] * 6     # round(2.07) = 2 chunks of 10
+    assert list(orc.select_bins(delta, M, 0.125)[1]) == list(range(30))        # round(2.75) = 3, all-equal layer
+    assert len(orc.select_bins(delta, M, 0.25)[0]) == 60                       # 5.5 rounds half up to 6
+
+
+def test_select_bins_uneven_chunks_and_count_rule():
+    # M not divisible by C: floor boundaries; every layer's list is sorted, unique, inside [0, M)
+    M, C = 1000, 22
+    delta = rng(55).normal(size=(3, C))
+    for ratio in [0.1, 0.3]:
+        for b in orc.select_bins(delta, M, ratio):
+            assert np.all(np.diff(b) > 0) and b[0] >= 0 and b[-1] < M
+    top = int(np.argmax(delta[0]))
+    one = orc.select_bins(delta, M, 0.0)[0]   # never fewer than one chunk
+    assert list(one) == list(range((top * M) // C, ((top + 1) * M) // C))
