@@ -181,6 +181,23 @@ int64_t iwdft_num_tokens(const iwdft_ctx* ctx); /* T = tokens inside the coeffic
  * T >= M. */
 int iwdft_set_num_tokens(iwdft_ctx* ctx, int64_t T);
 
+/* Greedy frequency mask of the ablation study (Sec. 3.2): the M bins are cut into n_chunks contiguous
+ * chunks, chunk c = bins [floor(c M / n_chunks), floor((c+1) M / n_chunks)); per layer the
+ * clamp(floor(r * n_chunks + 1/2), 1, n_chunks) chunks with the largest importance delta (Eq. delta-ppl)
+ * are kept, the lower chunk index first among equal values.  All pointers are HOST memory:
+ * delta [n_layers][n_chunks] (no NaN), bin_offsets [n_layers + 1] (out), bins [bins_capacity] (out,
+ * per layer ascending -- the lists iwdft_desc takes).  bin_offsets is always filled, so a call with
+ * bins_capacity = 0 sizes the list (returns IWDFT_ERR_SIZE).  No GPU work. */
+int iwdft_select_bins(const float* delta, int32_t n_layers, int32_t n_chunks, int64_t M, double r,
+                      int64_t* bin_offsets, int32_t* bins, int64_t bins_capacity);
+
+/* Frequency ablation of one chunk (Sec. 3.2, Eq. freq-zero): per slice and channel the DFT along the token
+ * axis, the coefficients of the chunk's bins set to zero, the inverse DFT, real part.
+ * d_x, d_out: DEVICE [n_slices][M][head_dim], kv_dtype, must not overlap.  This build: head_dim 128 and
+ * M = 2^m, 256 <= M <= 8192 (IWDFT_ERR_UNSUPPORTED otherwise).  Needs no context; enqueues on hip_stream. */
+int iwdft_ablate_chunk(const void* d_x, void* d_out, int64_t n_slices, int64_t M, int32_t head_dim,
+                       int32_t kv_dtype, int32_t n_chunks, int32_t chunk, void* hip_stream);
+
 const char* iwdft_last_error(void); /* thread-local, static storage, never NULL */
 
 #ifdef __cplusplus

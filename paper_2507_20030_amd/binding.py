@@ -25,6 +25,7 @@ EXPORTED = [
     "iwdft_query_bytes", "iwdft_create", "iwdft_destroy", "iwdft_prefill", "iwdft_append",
     "iwdft_reconstruct", "compressed_decode_attn", "iwdft_append_attn", "iwdft_export_coeffs", "iwdft_export_bins",
     "iwdft_num_tokens", "iwdft_set_num_tokens", "iwdft_last_error", "iwdft_phase_timing", "iwdft_phase_times", "iwdft_prefill_kind",
+    "iwdft_select_bins", "iwdft_ablate_chunk",
 ]
 
 LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libiwdft.so")
@@ -73,6 +74,9 @@ def load_library() -> ctypes.CDLL:
     lib.compressed_decode_attn.argtypes = [vp, vp, vp, f32, vp]
     lib.iwdft_append_attn.argtypes = [vp, vp, vp, vp, vp, f32, vp]
     lib.iwdft_prefill_kind.argtypes = [vp]
+    lib.iwdft_select_bins.argtypes = [ctypes.POINTER(ctypes.c_float), i32, i32, i64, ctypes.c_double,
+                                      ctypes.POINTER(ctypes.c_int64), ctypes.POINTER(ctypes.c_int32), i64]
+    lib.iwdft_ablate_chunk.argtypes = [vp, vp, i64, i64, i32, i32, i32, i32, vp]
     lib.iwdft_phase_timing.argtypes = [vp, i32]
     lib.iwdft_phase_times.argtypes = [vp, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_int64)]
     lib.iwdft_export_coeffs.argtypes = [vp, i32, vp, vp, vp]
@@ -171,6 +175,31 @@ def compressed_decode_attn(ctx, q: torch.Tensor, out: torch.Tensor, scale: float
 def iwdft_append_attn(ctx, tok_k, tok_v, q, out, scale: float = 0.0, stream=None) -> None:
     _check(load_library().iwdft_append_attn(ctx, _ptr(tok_k), _ptr(tok_v), _ptr(q), _ptr(out), scale,
                                             _stream(stream)))
+
+
+def iwdft_select_bins(delta: np.ndarray, M: int, r: float):
+    """Per-layer kept-bin lists (int32 arrays) from a [layers, chunks] importance matrix."""
+    delta = np.ascontiguousarray(delta, dtype=np.float32)
+    n_layers, n_chunks = delta.shape
+    lib = load_library()
+    off = (ctypes.c_int64 * (n_layers + 1))()
+    dp = delta.ctypes.data_as(ctypes.POINTER(ctypes.c_float))
+    rc = lib.iwdft_select_bins(dp, n_layers, n_chunks, M, float(r), off, None, 0)   # sizing call
+    if rc != IWDFT_ERR_SIZE:
+        _check(rc)
+    bins = np.empty(max(int(off[n_layers]), 1), dtype=np.int32)
+    _check(lib.iwdft_select_bins(dp, n_layers, n_chunks, M, float(r), off,
+                                 bins.ctypes.data_as(ctypes.POINTER(ctypes.c_int32)), bins.size))
+    return [bins[off[l]:off[l + 1]].copy() for l in range(n_layers)]
+
+
+def iwdft_ablate_chunk(x: torch.Tensor, out: torch.Tensor, n_chunks: int, chunk: int, stream=None) -> None:
+    """x, out: [..., M, head_dim] contiguous device tensors of the same shape and dtype."""
+    M, D = x.shape[-2], x.shape[-1]
+    n_slices = x.numel() // (M * D)
+    _check(load_library().iwdft_ablate_chunk(_ptr(x), _ptr(out), n_slices, M, D,
+                                             IWDFT_F32 if x.dtype == torch.float32 else IWDFT_BF16,
+                                             n_chunks, chunk, _stream(stream)))
 
 
 def iwdft_prefill_kind(ctx) -> str:

@@ -8,7 +8,7 @@ from concurrent.futures import ThreadPoolExecutor
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libiwdft.so")
-SOURCES = ["api.hip", "append.hip", "prefill.hip", "prefill_fft.hip", "reconstruct.hip", "attn.hip"]
+SOURCES = ["api.hip", "append.hip", "prefill.hip", "prefill_fft.hip", "reconstruct.hip", "attn.hip", "ablate.hip"]
 FLAGS = [
     "-O3", "--offload-arch=gfx950", "-fPIC", "-std=c++17", "-fgpu-rdc" if False else "-fno-gpu-rdc",
     # packed-FP32 instruction selection is switched off for every device translation unit

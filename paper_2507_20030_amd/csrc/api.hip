@@ -493,4 +493,55 @@ int iwdft_append_attn(iwdft_ctx* ctx, const void* d_tok_k, const void* d_tok_v, 
   return IWDFT_OK;
 }
 
+int iwdft_select_bins(const float* delta, int32_t n_layers, int32_t n_chunks, int64_t M, double r,
+                      int64_t* bin_offsets, int32_t* bins, int64_t bins_capacity) {
+  if (!delta || !bin_offsets) return fail(IWDFT_ERR_ARG, "delta / bin_offsets is NULL");
+  if (n_layers <= 0 || n_chunks <= 0) return fail(IWDFT_ERR_ARG, "n_layers and n_chunks must be positive");
+  if (M < 1 || M > ((int64_t)1 << 30)) return fail(IWDFT_ERR_ARG, "M = %lld outside [1, 2^30]", (long long)M);
+  if (!(r >= 0.0) || !std::isfinite(r)) return fail(IWDFT_ERR_ARG, "retention ratio must be finite and >= 0");
+  if (bins_capacity < 0 || (bins_capacity > 0 && !bins)) return fail(IWDFT_ERR_ARG, "bins is NULL");
+  std::vector<int> keep;
+  int64_t total = 0;
+  bin_offsets[0] = 0;
+  for (int l = 0; l < n_layers; ++l) {
+    if (select_chunks(delta + (size_t)l * n_chunks, n_chunks, r, &keep) != 0)
+      return fail(IWDFT_ERR_ARG, "delta of layer %d holds a NaN", l);
+    for (int c : keep) {
+      const int64_t a = chunk_edge(c, M, n_chunks), b = chunk_edge(c + 1, M, n_chunks);
+      for (int64_t k = a; k < b; ++k, ++total)
+        if (total < bins_capacity) bins[total] = (int32_t)k;
+    }
+    bin_offsets[l + 1] = total;
+  }
+  if (total > bins_capacity)
+    return fail(IWDFT_ERR_SIZE, "bins holds %lld entries, %lld needed", (long long)bins_capacity, (long long)total);
+  for (int l = 0; l < n_layers; ++l)
+    if (bin_offsets[l + 1] == bin_offsets[l])
+      return fail(IWDFT_ERR_BINS, "layer %d keeps no bin (M smaller than the number of chunks)", l);
+  return IWDFT_OK;
+}
+
+int iwdft_ablate_chunk(const void* d_x, void* d_out, int64_t n_slices, int64_t M, int32_t head_dim,
+                       int32_t kv_dtype, int32_t n_chunks, int32_t chunk, void* hip_stream) {
+  if (!d_x || !d_out) return fail(IWDFT_ERR_ARG, "d_x / d_out is NULL");
+  if (n_slices < 0 || n_slices > 0x3fffff) return fail(IWDFT_ERR_ARG, "n_slices = %lld out of range", (long long)n_slices);
+  if (kv_dtype != IWDFT_F32 && kv_dtype != IWDFT_BF16) return fail(IWDFT_ERR_ARG, "bad kv_dtype %d", kv_dtype);
+  if (n_chunks <= 0 || chunk < 0 || chunk >= n_chunks)
+    return fail(IWDFT_ERR_ARG, "chunk %d outside [0, %d)", chunk, n_chunks);
+  if (M < 1) return fail(IWDFT_ERR_ARG, "M must be positive");
+  if (head_dim != kHeadDim) return fail(IWDFT_ERR_UNSUPPORTED, "head_dim %d: this build handles 128", head_dim);
+  if ((M & (M - 1)) != 0 || M < (int64_t)kFftMinM || M > 8192)
+    return fail(IWDFT_ERR_UNSUPPORTED, "iwdft_ablate_chunk needs M = 2^m with 256 <= M <= 8192 (got %lld)",
+                (long long)M);
+  const size_t esz = kv_dtype == IWDFT_BF16 ? 2 : 4;
+  const size_t bytes = (size_t)n_slices * (size_t)M * kHeadDim * esz;
+  const char *a = (const char*)d_x, *b = (const char*)d_out;
+  if (a < b + bytes && b < a + bytes && bytes) return fail(IWDFT_ERR_ARG, "d_x and d_out overlap");
+  if (n_slices == 0) return IWDFT_OK;
+  return launched(launch_ablate(d_x, d_out, (int)n_slices, (uint32_t)M, kv_dtype,
+                                (int)chunk_edge(chunk, M, n_chunks), (int)chunk_edge(chunk + 1, M, n_chunks),
+                                (hipStream_t)hip_stream),
+                  "ablation launch");
+}
+
 }  // extern "C"

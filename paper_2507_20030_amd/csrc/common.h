@@ -2,6 +2,8 @@
 // dtype conversion.  gfx950 only.
 #pragma once
 #include <hip/hip_runtime.h>
+
+#include <vector>
 #include <stdint.h>
 
 namespace iwdft {
@@ -154,6 +156,14 @@ hipError_t launch_step(const Params& P, const void* tok_k, const void* tok_v, co
                        float scale, float2* qc, float2* Pn, float* pe, void* stage_k, void* stage_v,
                        float* direct_scratch, bool use_fft, uint32_t t_shift, uint32_t ring_pos,
                        const PhaseEvents* marks, hipStream_t st);
+
+// Frequency-ablation tools (Sec. 3.2).  launch_ablate: x, out [n_slices][M][128], M = 2^8 .. 2^13, the bins
+// [lo, hi) zeroed.  select_chunks: the floor(r C + 1/2) (clamped to 1 .. C) chunks with the largest delta,
+// lower index first among equals, ascending; -1 if a delta is NaN.
+hipError_t launch_ablate(const void* x, void* out, int n_slices, uint32_t M, int kv_dtype, int lo, int hi,
+                         hipStream_t st);
+int64_t chunk_edge(int64_t c, int64_t M, int64_t C);
+int select_chunks(const float* delta, int n_chunks, double r, std::vector<int>* keep);
 
 // Raises a kernel's dynamic-LDS limit once per (kernel, device); one static instance per kernel.
 struct LdsLimit {
