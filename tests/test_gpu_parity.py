@@ -366,11 +366,57 @@ def test_fused_step_cfg2_windows_full_size():
     run_stream(cfg, wl.layer_bins(cfg), steps=3, fused=True, tag="cfg2w-fused")
 
 
-@pytest.mark.parametrize("prefill", ["fft", "dense"])
-def test_cfg2_full_size_sampled_slices(prefill):
+@pytest.mark.parametrize("prefill,fused", [("fft", True), ("fft", False), ("dense", False)])
+def test_cfg2_full_size_sampled_slices(prefill, fused):
+    # ("fft", True) is the launch configuration the benchmark times
     cfg = wl.CONFIGS["cfg2"]
     flags = B.IWDFT_FLAG_FFT_PREFILL if prefill == "fft" else B.IWDFT_FLAG_DENSE_PREFILL
-    run_stream(cfg, wl.layer_bins(cfg), flags=flags, steps=3, tag=f"cfg2-{prefill}")
+    run_stream(cfg, wl.layer_bins(cfg), flags=flags, steps=3, fused=fused, tag=f"cfg2-{prefill}-fused{int(fused)}")
+
+
+@pytest.mark.parametrize("L,n_bins", [(1, 1), (2, 1), (2, 2), (3, 2), (64, 1), (64, 64)])
+def test_degenerate_sizes(L, n_bins):
+    # one-token caches, a single kept bin, every bin kept; alternating two-call / fused steps
+    cfg = small_cfg(L=L, n_bins=n_bins, group=2, steps=4, n_layers=1, batch=2)
+    bins = [np.arange(n_bins, dtype=np.int32)]
+    for fused in (False, True):
+        run_stream(cfg, bins, rec=(0, L), fused=fused, tag=f"degenerate-L{L}-B{n_bins}-f{int(fused)}")
+
+
+def test_dc_only_mask_outputs_the_mean_value_row():
+    # |B| = {0}: every reconstructed slot is the same vector, so attention returns exactly the
+    # reconstructed V row whatever the query: (1/M) * sum of all tokens seen
+    cfg = small_cfg(L=1024, n_bins=1, group=2, steps=3, n_layers=1, batch=1, dtype="f32")
+    bins = [np.zeros(1, np.int32)]
+    K, V = wl.prefill_tensors(cfg, DEV)
+    cache = make_cache(cfg, bins)
+    cache.prefill(K, V)
+    tot = f64(V[0, 0]).sum(axis=1)                    # [kv heads, d]
+    for i in range(cfg.steps):
+        tk, tv, q = wl.decode_step(cfg, i, DEV)
+        out = cache.step(tk, tv, q)
+        tot = tot + f64(tv[0, 0])
+        ref = np.repeat(tot / cfg.L, cfg.group, axis=0)
+        assert rel_l2(f64(out[0, 0]), ref) < 1e-5
+    cache.close()
+
+
+@pytest.mark.parametrize("n_bins,kind", [(4096, "fft"), (4100, "direct")])
+def test_most_bins_the_fft_kernels_take_and_the_fallback_beyond(n_bins, kind):
+    # 4096 kept bins per layer is the limit of the FFT attention and FFT prefill kernels; one more and the
+    # library runs the direct synthesis and the dense prefill (same results, slower)
+    cfg = small_cfg(L=8192, n_bins=n_bins, group=2, steps=2, n_layers=1, batch=1, n_kv_heads=2, dtype="bf16")
+    bins = [np.sort(np.random.default_rng(3).choice(cfg.L, size=n_bins, replace=False)).astype(np.int32)]
+    cache = make_cache(cfg, bins)
+    assert B.iwdft_prefill_kind(cache.ctx) == ("fft" if kind == "fft" else "dense")
+    cache.close()
+    run_stream(cfg, bins, rec=(5, 40), fused=True, tag=f"maxbins-{n_bins}")
+
+
+def test_most_exact_tokens():
+    # S + R = 1024 is the most the library takes
+    cfg = small_cfg(L=512, n_bins=60, group=2, steps=3, n_layers=1, batch=1, n_sink=500, n_recent=524, dtype="bf16")
+    run_stream(cfg, random_bins(cfg, 43), fused=True, tag="max-exact")
 
 
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
