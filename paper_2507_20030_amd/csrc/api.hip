@@ -5,6 +5,7 @@
 #include <cstdarg>
 #include <cstdio>
 #include <cstring>
+#include <memory>
 #include <new>
 #include <vector>
 
@@ -219,21 +220,26 @@ int launched(hipError_t e, const char* what) {
 
 // Next set of phase events of a timed call (created on demand), or null when timing is off.
 int next_marks(iwdft_ctx* c, const PhaseEvents** out) {
-  *out = nullptr;
-  if (!c->timing) return IWDFT_OK;
-  if (c->marks_used == c->marks.size()) {
-    PhaseEvents m;
-    for (int i = 0; i < 4; ++i) {
-      hipError_t e = hipEventCreate(&m.ev[i]);
-      if (e != hipSuccess) {
-        for (int j = 0; j < i; ++j) (void)hipEventDestroy(m.ev[j]);
-        return fail(IWDFT_ERR_HIP, "hipEventCreate: %s", hipGetErrorString(e));
+  try {
+    *out = nullptr;
+    if (!c->timing) return IWDFT_OK;
+    if (c->marks_used == c->marks.size()) {
+      PhaseEvents m;
+      for (int i = 0; i < 4; ++i) {
+        hipError_t e = hipEventCreate(&m.ev[i]);
+        if (e != hipSuccess) {
+          for (int j = 0; j < i; ++j) (void)hipEventDestroy(m.ev[j]);
+          return fail(IWDFT_ERR_HIP, "hipEventCreate: %s", hipGetErrorString(e));
+        }
       }
+      c->marks.push_back(m);
     }
-    c->marks.push_back(m);
+    *out = &c->marks[c->marks_used++];
+    return IWDFT_OK;
+
+  } catch (...) {  // std::bad_alloc from the host-side containers: nothing may cross the C ABI
+    return fail(IWDFT_ERR_ARG, "out of host memory");
   }
-  *out = &c->marks[c->marks_used++];
-  return IWDFT_OK;
 }
 
 uint32_t t_shift(const iwdft_ctx* c) {  // (T - M) mod M
@@ -247,93 +253,98 @@ extern "C" {
 const char* iwdft_last_error(void) { return g_err; }
 
 int iwdft_query_bytes(const iwdft_desc* desc, size_t* state_bytes, size_t* workspace_bytes) {
-  if (!state_bytes || !workspace_bytes) return fail(IWDFT_ERR_ARG, "output pointer is NULL");
-  Plan pl;
-  int rc = make_plan(desc, &pl);
-  if (rc != IWDFT_OK) return rc;
-  *state_bytes = pl.state_bytes;
-  *workspace_bytes = pl.ws_bytes < 256 ? 256 : pl.ws_bytes;
-  return IWDFT_OK;
+  try {
+    if (!state_bytes || !workspace_bytes) return fail(IWDFT_ERR_ARG, "output pointer is NULL");
+    Plan pl;
+    int rc = make_plan(desc, &pl);
+    if (rc != IWDFT_OK) return rc;
+    *state_bytes = pl.state_bytes;
+    *workspace_bytes = pl.ws_bytes < 256 ? 256 : pl.ws_bytes;
+    return IWDFT_OK;
+
+  } catch (...) {  // std::bad_alloc from the host-side containers: nothing may cross the C ABI
+    return fail(IWDFT_ERR_ARG, "out of host memory");
+  }
 }
 
 int iwdft_create(const iwdft_desc* desc, void* d_state, size_t state_bytes, void* d_workspace,
                  size_t workspace_bytes, iwdft_ctx** out) {
-  if (!out) return fail(IWDFT_ERR_ARG, "out is NULL");
-  *out = nullptr;
-  iwdft_ctx* c = new (std::nothrow) iwdft_ctx();
-  if (!c) return fail(IWDFT_ERR_ARG, "out of host memory");
-  int rc = make_plan(desc, &c->plan);
-  if (rc != IWDFT_OK) { delete c; return rc; }
-  const Plan& pl = c->plan;
-  size_t need_ws = pl.ws_bytes < 256 ? 256 : pl.ws_bytes;
-  if (!d_state || !d_workspace) { delete c; return fail(IWDFT_ERR_ARG, "d_state / d_workspace is NULL"); }
-  if (((uintptr_t)d_state & 255) || ((uintptr_t)d_workspace & 255)) {
-    delete c;
-    return fail(IWDFT_ERR_ARG, "d_state and d_workspace must be 256-byte aligned");
-  }
-  if (state_bytes < pl.state_bytes) {
-    delete c;
-    return fail(IWDFT_ERR_SIZE, "state buffer has %zu bytes, %zu needed", state_bytes, pl.state_bytes);
-  }
-  if (workspace_bytes < need_ws) {
-    delete c;
-    return fail(IWDFT_ERR_SIZE, "workspace has %zu bytes, %zu needed", workspace_bytes, need_ws);
-  }
-  c->desc = *desc;
-  c->state = (char*)d_state;
-  c->ws = (char*)d_workspace;
-  if (hipGetDevice(&c->device) != hipSuccess) { delete c; return fail(IWDFT_ERR_HIP, "hipGetDevice failed"); }
+  try {
+    if (!out) return fail(IWDFT_ERR_ARG, "out is NULL");
+    *out = nullptr;
+    std::unique_ptr<iwdft_ctx> c(new iwdft_ctx());  // freed on every early return and on exceptions
+    int rc = make_plan(desc, &c->plan);
+    if (rc != IWDFT_OK) return rc;
+    const Plan& pl = c->plan;
+    size_t need_ws = pl.ws_bytes < 256 ? 256 : pl.ws_bytes;
+    if (!d_state || !d_workspace) { return fail(IWDFT_ERR_ARG, "d_state / d_workspace is NULL"); }
+    if (((uintptr_t)d_state & 255) || ((uintptr_t)d_workspace & 255)) {
+      return fail(IWDFT_ERR_ARG, "d_state and d_workspace must be 256-byte aligned");
+    }
+    if (state_bytes < pl.state_bytes) {
+      return fail(IWDFT_ERR_SIZE, "state buffer has %zu bytes, %zu needed", state_bytes, pl.state_bytes);
+    }
+    if (workspace_bytes < need_ws) {
+      return fail(IWDFT_ERR_SIZE, "workspace has %zu bytes, %zu needed", workspace_bytes, need_ws);
+    }
+    c->desc = *desc;
+    c->state = (char*)d_state;
+    c->ws = (char*)d_workspace;
+    if (hipGetDevice(&c->device) != hipSuccess) { return fail(IWDFT_ERR_HIP, "hipGetDevice failed"); }
 
-  // Device copies of geometry, bins and weights live at the head of the state buffer.
-  std::vector<float> w((size_t)pl.n_bins_total, 1.0f);
-  if (desc->bin_weights) memcpy(w.data(), desc->bin_weights, sizeof(float) * w.size());
-  hipError_t e = hipMemset(c->state, 0, pl.state_bytes);
-  if (e == hipSuccess)
-    e = hipMemcpy(c->state + pl.off_layers, pl.layers.data(), sizeof(LayerInfo) * pl.layers.size(),
-                  hipMemcpyHostToDevice);
-  if (e == hipSuccess)
-    e = hipMemcpy(c->state + pl.off_bins, desc->bins, sizeof(int32_t) * (size_t)pl.n_bins_total,
-                  hipMemcpyHostToDevice);
-  if (e == hipSuccess)
-    e = hipMemcpy(c->state + pl.off_weights, w.data(), sizeof(float) * w.size(), hipMemcpyHostToDevice);
-  if (e == hipSuccess)
-    e = hipMemcpy(c->state + pl.off_fold, pl.fold.data(), sizeof(uint16_t) * pl.fold.size(),
-                  hipMemcpyHostToDevice);
-  if (e != hipSuccess) {
-    delete c;
-    return fail(IWDFT_ERR_HIP, "initialising the state buffer: %s", hipGetErrorString(e));
-  }
-  c->desc.bin_offsets = nullptr;
-  c->desc.bins = nullptr;
-  c->desc.bin_weights = nullptr;
+    // Device copies of geometry, bins and weights live at the head of the state buffer.
+    std::vector<float> w((size_t)pl.n_bins_total, 1.0f);
+    if (desc->bin_weights) memcpy(w.data(), desc->bin_weights, sizeof(float) * w.size());
+    hipError_t e = hipMemset(c->state, 0, pl.state_bytes);
+    if (e == hipSuccess)
+      e = hipMemcpy(c->state + pl.off_layers, pl.layers.data(), sizeof(LayerInfo) * pl.layers.size(),
+                    hipMemcpyHostToDevice);
+    if (e == hipSuccess)
+      e = hipMemcpy(c->state + pl.off_bins, desc->bins, sizeof(int32_t) * (size_t)pl.n_bins_total,
+                    hipMemcpyHostToDevice);
+    if (e == hipSuccess)
+      e = hipMemcpy(c->state + pl.off_weights, w.data(), sizeof(float) * w.size(), hipMemcpyHostToDevice);
+    if (e == hipSuccess)
+      e = hipMemcpy(c->state + pl.off_fold, pl.fold.data(), sizeof(uint16_t) * pl.fold.size(),
+                    hipMemcpyHostToDevice);
+    if (e != hipSuccess) {
+      return fail(IWDFT_ERR_HIP, "initialising the state buffer: %s", hipGetErrorString(e));
+    }
+    c->desc.bin_offsets = nullptr;
+    c->desc.bins = nullptr;
+    c->desc.bin_weights = nullptr;
 
-  Params& P = c->P;
-  P.n_layers = desc->n_layers;
-  P.batch = desc->batch;
-  P.n_kv = desc->n_kv_heads;
-  P.G = pl.G;
-  P.n_slices = desc->n_layers * desc->batch * desc->n_kv_heads;
-  P.kv_dtype = desc->kv_dtype;
-  P.M = (uint32_t)desc->M;
-  P.Mmask = ((desc->M & (desc->M - 1)) == 0) ? (uint32_t)(desc->M - 1) : 0u;
-  if (desc->M == 1) P.Mmask = 0;  // M = 1: "mod 1" through the generic path
-  P.max_nb = pl.max_nb;
-  P.max_Bp = pl.max_Bp;
-  P.layers = (const LayerInfo*)(c->state + pl.off_layers);
-  P.bins = (const int32_t*)(c->state + pl.off_bins);
-  P.weights = (const float*)(c->state + pl.off_weights);
-  P.fold = (const uint16_t*)(c->state + pl.off_fold);
-  P.FK = (float2*)(c->state + pl.off_FK);
-  P.FV = (float2*)(c->state + pl.off_FV);
-  P.S = desc->n_sink;
-  P.R = desc->n_recent;
-  P.sinkK = c->state + pl.off_sinkK;
-  P.sinkV = c->state + pl.off_sinkV;
-  P.ringK = c->state + pl.off_ringK;
-  P.ringV = c->state + pl.off_ringV;
-  c->T = 0;
-  *out = c;
-  return IWDFT_OK;
+    Params& P = c->P;
+    P.n_layers = desc->n_layers;
+    P.batch = desc->batch;
+    P.n_kv = desc->n_kv_heads;
+    P.G = pl.G;
+    P.n_slices = desc->n_layers * desc->batch * desc->n_kv_heads;
+    P.kv_dtype = desc->kv_dtype;
+    P.M = (uint32_t)desc->M;
+    P.Mmask = ((desc->M & (desc->M - 1)) == 0) ? (uint32_t)(desc->M - 1) : 0u;
+    if (desc->M == 1) P.Mmask = 0;  // M = 1: "mod 1" through the generic path
+    P.max_nb = pl.max_nb;
+    P.max_Bp = pl.max_Bp;
+    P.layers = (const LayerInfo*)(c->state + pl.off_layers);
+    P.bins = (const int32_t*)(c->state + pl.off_bins);
+    P.weights = (const float*)(c->state + pl.off_weights);
+    P.fold = (const uint16_t*)(c->state + pl.off_fold);
+    P.FK = (float2*)(c->state + pl.off_FK);
+    P.FV = (float2*)(c->state + pl.off_FV);
+    P.S = desc->n_sink;
+    P.R = desc->n_recent;
+    P.sinkK = c->state + pl.off_sinkK;
+    P.sinkV = c->state + pl.off_sinkV;
+    P.ringK = c->state + pl.off_ringK;
+    P.ringV = c->state + pl.off_ringV;
+    c->T = 0;
+    *out = c.release();
+    return IWDFT_OK;
+
+  } catch (...) {  // std::bad_alloc from the host-side containers: nothing may cross the C ABI
+    return fail(IWDFT_ERR_ARG, "out of host memory");
+  }
 }
 
 int iwdft_destroy(iwdft_ctx* ctx) {
@@ -495,30 +506,35 @@ int iwdft_append_attn(iwdft_ctx* ctx, const void* d_tok_k, const void* d_tok_v, 
 
 int iwdft_select_bins(const float* delta, int32_t n_layers, int32_t n_chunks, int64_t M, double r,
                       int64_t* bin_offsets, int32_t* bins, int64_t bins_capacity) {
-  if (!delta || !bin_offsets) return fail(IWDFT_ERR_ARG, "delta / bin_offsets is NULL");
-  if (n_layers <= 0 || n_chunks <= 0) return fail(IWDFT_ERR_ARG, "n_layers and n_chunks must be positive");
-  if (M < 1 || M > ((int64_t)1 << 30)) return fail(IWDFT_ERR_ARG, "M = %lld outside [1, 2^30]", (long long)M);
-  if (!(r >= 0.0) || !std::isfinite(r)) return fail(IWDFT_ERR_ARG, "retention ratio must be finite and >= 0");
-  if (bins_capacity < 0 || (bins_capacity > 0 && !bins)) return fail(IWDFT_ERR_ARG, "bins is NULL");
-  std::vector<int> keep;
-  int64_t total = 0;
-  bin_offsets[0] = 0;
-  for (int l = 0; l < n_layers; ++l) {
-    if (select_chunks(delta + (size_t)l * n_chunks, n_chunks, r, &keep) != 0)
-      return fail(IWDFT_ERR_ARG, "delta of layer %d holds a NaN", l);
-    for (int c : keep) {
-      const int64_t a = chunk_edge(c, M, n_chunks), b = chunk_edge(c + 1, M, n_chunks);
-      for (int64_t k = a; k < b; ++k, ++total)
-        if (total < bins_capacity) bins[total] = (int32_t)k;
+  try {
+    if (!delta || !bin_offsets) return fail(IWDFT_ERR_ARG, "delta / bin_offsets is NULL");
+    if (n_layers <= 0 || n_chunks <= 0) return fail(IWDFT_ERR_ARG, "n_layers and n_chunks must be positive");
+    if (M < 1 || M > ((int64_t)1 << 30)) return fail(IWDFT_ERR_ARG, "M = %lld outside [1, 2^30]", (long long)M);
+    if (!(r >= 0.0) || !std::isfinite(r)) return fail(IWDFT_ERR_ARG, "retention ratio must be finite and >= 0");
+    if (bins_capacity < 0 || (bins_capacity > 0 && !bins)) return fail(IWDFT_ERR_ARG, "bins is NULL");
+    std::vector<int> keep;
+    int64_t total = 0;
+    bin_offsets[0] = 0;
+    for (int l = 0; l < n_layers; ++l) {
+      if (select_chunks(delta + (size_t)l * n_chunks, n_chunks, r, &keep) != 0)
+        return fail(IWDFT_ERR_ARG, "delta of layer %d holds a NaN", l);
+      for (int c : keep) {
+        const int64_t a = chunk_edge(c, M, n_chunks), b = chunk_edge(c + 1, M, n_chunks);
+        for (int64_t k = a; k < b; ++k, ++total)
+          if (total < bins_capacity) bins[total] = (int32_t)k;
+      }
+      bin_offsets[l + 1] = total;
     }
-    bin_offsets[l + 1] = total;
+    if (total > bins_capacity)
+      return fail(IWDFT_ERR_SIZE, "bins holds %lld entries, %lld needed", (long long)bins_capacity, (long long)total);
+    for (int l = 0; l < n_layers; ++l)
+      if (bin_offsets[l + 1] == bin_offsets[l])
+        return fail(IWDFT_ERR_BINS, "layer %d keeps no bin (M smaller than the number of chunks)", l);
+    return IWDFT_OK;
+
+  } catch (...) {  // std::bad_alloc from the host-side containers: nothing may cross the C ABI
+    return fail(IWDFT_ERR_ARG, "out of host memory");
   }
-  if (total > bins_capacity)
-    return fail(IWDFT_ERR_SIZE, "bins holds %lld entries, %lld needed", (long long)bins_capacity, (long long)total);
-  for (int l = 0; l < n_layers; ++l)
-    if (bin_offsets[l + 1] == bin_offsets[l])
-      return fail(IWDFT_ERR_BINS, "layer %d keeps no bin (M smaller than the number of chunks)", l);
-  return IWDFT_OK;
 }
 
 int iwdft_ablate_chunk(const void* d_x, void* d_out, int64_t n_slices, int64_t M, int32_t head_dim,
