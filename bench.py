@@ -4,7 +4,8 @@
 One *step* is one whole job over the named workload with all inputs already resident in HBM:
     iwdft_prefill(K, V)  ->  decode_steps x iwdft_append_attn(k_i, v_i, q_i)
 where iwdft_append_attn is the append followed by the decode attention with the update fused into
-the attention kernels (--split runs the two separate calls instead).  The reconstruction of
+the attention kernels and the coefficients written back every --write-every steps (--split runs the
+two separate calls instead).  The reconstruction of
 Eq. reconstruct-idft happens inside the attention kernels; the materialising iwdft_reconstruct call
 is timed separately and reported under "kernels", and so are the two separate calls of the metric
 (append tokens/s, decode attention us/step).
@@ -37,6 +38,8 @@ def main():
     ap.add_argument("--split", action="store_true",
                     help="decode with the two separate calls (iwdft_append, compressed_decode_attn) instead of "
                          "the fused iwdft_append_attn")
+    ap.add_argument("--write-every", type=int, default=8,
+                    help="fused decode step: write the coefficients back every this many steps (1 = every step)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="only run a plain 1 GiB device copy (reference for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE)")
@@ -65,36 +68,36 @@ def main():
     torch.cuda.set_device(0)
     bins = wl.layer_bins(cfg)
     K, V = wl.prefill_tensors(cfg, dev)
-    cache = B.Cache(cfg.n_layers, cfg.batch, cfg.n_kv_heads, cfg.n_q_heads, cfg.head_dim, cfg.torch_dtype,
-                    cfg.L, bins, device=dev)
+    fused = not args.split
+    J = max(1, args.write_every) if fused else 1
+
+    def new_cache(**kw):
+        return B.Cache(cfg.n_layers, cfg.batch, cfg.n_kv_heads, cfg.n_q_heads, cfg.head_dim, cfg.torch_dtype,
+                       cfg.L, bins, device=dev, **kw)
+    cache = new_cache(write_every=J)
     n_pool = min(dsteps, 32)  # decode inputs are cycled from a resident pool
     pool = [wl.decode_step(cfg, i, dev) for i in range(n_pool)]
     out = torch.empty_like(pool[0][2])
     stream = torch.cuda.current_stream()
 
-    fused = not args.split
-
-    def decode(i, marks=None):
+    def decode(c, i, marks=None, split=False):
         tk, tv, q = pool[i % n_pool]
-        if fused:
-            if marks is not None:
-                marks[0].record(stream)
-            cache.step(tk, tv, q, out, 0.0, stream)
-            if marks is not None:
-                marks[2].record(stream)
-        else:
-            if marks is not None:
-                marks[0].record(stream)
-            cache.append(tk, tv, stream)
+        if marks is not None:
+            marks[0].record(stream)
+        if split:
+            c.append(tk, tv, stream)
             if marks is not None:
                 marks[1].record(stream)
-            cache.attend(q, out, 0.0, stream)
-            if marks is not None:
-                marks[2].record(stream)
+            c.attend(q, out, 0.0, stream)
+        else:
+            c.step(tk, tv, q, out, 0.0, stream)
+        if marks is not None:
+            marks[2].record(stream)
 
     # Event records between the kernels cost a few us each, so only a sample of the decode steps of
-    # the timed region carries them: every 8th step has the library's phase marks around its three
-    # attention kernels, another every 8th has events around the call(s); the rest run unmarked.
+    # the timed region carries them.  In every group of 8 steps: step 2 has the library's phase marks
+    # around its three attention kernels, step 4 has events around the call(s), and step 7 -- the step
+    # that writes the coefficients back when write_every = 8 -- has events around the call as well.
     # HIP events are created at their first record, which costs far more than a record: all of them
     # are recorded once before the timed region.
     def mk(n):
@@ -102,9 +105,11 @@ def main():
         for e in evs:
             e.record(stream)
         return evs
-    ev = [{i: mk(3) for i in range(dsteps) if i % 8 == 4 or dsteps < 8} for _ in range(args.steps)]
+    sampled = lambda i: i % 8 in (4, 7) or dsteps < 8
+    ev = [{i: mk(3) for i in range(dsteps) if sampled(i)} for _ in range(args.steps)]
     pre = [mk(2) for _ in range(args.steps)]
-    marked = lambda i: i % 8 == 0
+    marked = lambda i: i % 8 == 2 or dsteps < 8
+    writes_back = lambda i: (i + 1) % J == 0    # decode step i of a job (pending count restarts at the prefill)
 
     def run_job(s):
         if s is not None:
@@ -115,7 +120,7 @@ def main():
         for i in range(dsteps):
             if marked(i):
                 B.iwdft_phase_timing(cache.ctx, True)
-            decode(i, ev[s].get(i) if s is not None else None)
+            decode(cache, i, ev[s].get(i) if s is not None else None, split=not fused)
             if marked(i):
                 B.iwdft_phase_timing(cache.ctx, False)
 
@@ -132,47 +137,62 @@ def main():
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
     phase_ms, phase_calls = B.iwdft_phase_times(cache.ctx)
-    phase_avg = [m / max(phase_calls, 1) for m in phase_ms]  # kernels A, B, C of the timed region
+    phase_avg = [m / max(phase_calls, 1) for m in phase_ms]  # kernels A, B, C of the marked steps
+    pre_kind = B.iwdft_prefill_kind(cache.ctx)
 
     pre_ms = np.array([p[0].elapsed_time(p[1]) for p in pre])
-    step_ms = np.array([[e[0].elapsed_time(e[2]) for e in row.values()] for row in ev])
-
-    # The two calls of the metric on their own (append, then decode attention), same state and inputs.
-    # In a fused run this pass comes after the timed region; in a --split run it is the timed region.
+    call_ms = lambda rows, pick, a=0, b=2: np.array([e[a].elapsed_time(e[b]) for row in rows
+                                                    for i, e in row.items() if pick(i)] or [float("nan")])
     if fused:
-        sp = [mk(3) for _ in range(dsteps)]
-        for i in range(dsteps):
-            tk, tv, q = pool[i % n_pool]
-            sp[i][0].record(stream)
-            cache.append(tk, tv, stream)
-            sp[i][1].record(stream)
-            cache.attend(q, out, 0.0, stream)
-            sp[i][2].record(stream)
+        plain_ms = call_ms(ev, lambda i: not writes_back(i))   # steps that only read the coefficients
+        wb_ms = call_ms(ev, writes_back)                       # steps that write them back
+    else:
+        app_ms, att_ms = call_ms(ev, lambda i: True, 0, 1), call_ms(ev, lambda i: True, 1, 2)
+    cache.close()
+    del cache
+
+    # After the timed region, on a second context that writes back at every step: the fused step with
+    # write_every = 1 (phase marks on every step), and the two separate calls the metric names.
+    c1 = new_cache()
+    c1.prefill(K, V, stream)
+    n_extra = min(dsteps, 64)
+    if fused:
+        for i in range(4):
+            decode(c1, i)
+        B.iwdft_phase_timing(c1.ctx, True)
+        e1 = [mk(3) for _ in range(n_extra)]
+        for i in range(n_extra):
+            decode(c1, i, e1[i])
+        torch.cuda.synchronize()
+        f1_phase, f1_calls = B.iwdft_phase_times(c1.ctx)
+        B.iwdft_phase_timing(c1.ctx, False)
+        f1_ms = np.array([e[0].elapsed_time(e[2]) for e in e1])
+        f1_phase = [m / max(f1_calls, 1) for m in f1_phase]
+        sp = [mk(3) for _ in range(n_extra)]
+        for i in range(n_extra):
+            decode(c1, i, sp[i], split=True)
         torch.cuda.synchronize()
         app_ms = np.array([e[0].elapsed_time(e[1]) for e in sp])
         att_ms = np.array([e[1].elapsed_time(e[2]) for e in sp])
-    else:
-        app_ms = np.array([[e[0].elapsed_time(e[1]) for e in row.values()] for row in ev])
-        att_ms = np.array([[e[1].elapsed_time(e[2]) for e in row.values()] for row in ev])
 
     # materialising reconstruction of one layer, timed on its own (not part of the job)
     r0, r1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     Kt = torch.empty((cfg.batch, cfg.n_kv_heads, cfg.L, cfg.head_dim), dtype=cfg.torch_dtype, device=dev)
     Vt = torch.empty_like(Kt)
-    B.iwdft_reconstruct(cache.ctx, 0, 0, cfg.L, Kt, Vt, stream)
+    B.iwdft_reconstruct(c1.ctx, 0, 0, cfg.L, Kt, Vt, stream)
     r0.record(stream)
-    B.iwdft_reconstruct(cache.ctx, 0, 0, cfg.L, Kt, Vt, stream)
+    B.iwdft_reconstruct(c1.ctx, 0, 0, cfg.L, Kt, Vt, stream)
     r1.record(stream)
     torch.cuda.synchronize()
     rec_ms = r0.elapsed_time(r1)
+    c1.close()
+    del c1, Kt, Vt
 
     # the dense (matrix-core) prefill on its own, whatever the job used
-    pre_kind = B.iwdft_prefill_kind(cache.ctx)
     if pre_kind == "dense":
         dense_ms = float(pre_ms.mean())
     else:
-        dcache = B.Cache(cfg.n_layers, cfg.batch, cfg.n_kv_heads, cfg.n_q_heads, cfg.head_dim, cfg.torch_dtype,
-                         cfg.L, bins, flags=B.IWDFT_FLAG_DENSE_PREFILL, device=dev)
+        dcache = new_cache(flags=B.IWDFT_FLAG_DENSE_PREFILL)
         dcache.prefill(K, V, stream)
         de = mk(2 * 3)
         for i in range(3):
@@ -192,27 +212,39 @@ def main():
     mfma_split = 2 if cfg.dtype == "bf16" else 3                           # fp16 hi/lo basis (x fp32 input split)
     kv_in_bytes = 2 * cfg.n_slices * cfg.L * cfg.head_dim * (2 if cfg.dtype == "bf16" else 4)
     app_avg, att_avg, pre_avg = float(app_ms.mean()), float(att_ms.mean()), float(pre_ms.mean())
-    step_avg = float(step_ms.mean())
     tokens = args.steps * dsteps * cfg.batch
     gbps = lambda nbytes, ms: nbytes / (ms * 1e-3) / 1e9
+    frac = lambda nbytes, ms: gbps(nbytes, ms) / HBM_PEAK_GBS
 
     traffic_all = {}
     tpath = os.path.join(ROOT, "profiles", "traffic.json")
     if os.path.exists(tpath):
         traffic_all = json.load(open(tpath))
 
-    if fused:
-        # dominant kernel of the job: phase A of the fused step, a read-modify-write of every K coefficient
-        roof_kernel = "attn_qc_kernel<UPD> (iwdft_append_attn, phase A: K update + scores)"
+    # Dominant kernel of the timed job, from the library's phase marks.
+    if not fused:
+        roof_kernel, roof_bytes, roof_ms = "append_kernel (iwdft_append)", append_bytes, app_avg
+        traffic = traffic_all.get(f"append_{cfg.name}")
+    elif J == 1:    # every step writes back; phase A is a read-modify-write of every K coefficient
+        roof_kernel = "attn_qc_kernel<update> (iwdft_append_attn, phase A: K update + scores)"
         roof_bytes, roof_ms = 2 * coef_bytes, phase_avg[0]
         traffic = traffic_all.get(f"step_qc_{cfg.name}")
+    elif phase_avg[2] >= phase_avg[0]:   # J - 1 of J steps only read: phase C streams every V coefficient once
+        roof_kernel = "attn_out_kernel<plain> (iwdft_append_attn, phase C: output from the V coefficients)"
+        roof_bytes, roof_ms = coef_bytes, phase_avg[2]
+        traffic = traffic_all.get(f"attn_out_{cfg.name}")
     else:
-        roof_kernel = "append_kernel (iwdft_append)"
-        roof_bytes, roof_ms = append_bytes, app_avg
-        traffic = traffic_all.get(f"append_{cfg.name}")
+        roof_kernel = "attn_qc_kernel<plain> (iwdft_append_attn, phase A: scores from the K coefficients)"
+        roof_bytes, roof_ms = coef_bytes, phase_avg[0]
+        traffic = traffic_all.get(f"attn_qc_{cfg.name}")
 
-    step_def = ("prefill + decode_steps x iwdft_append_attn (append fused into the decode attention)" if fused
-                else "prefill + decode_steps x (iwdft_append, compressed_decode_attn)")
+    if not fused:
+        step_def = "prefill + decode_steps x (iwdft_append, compressed_decode_attn)"
+    elif J == 1:
+        step_def = "prefill + decode_steps x iwdft_append_attn (append fused into the decode attention)"
+    else:
+        step_def = (f"prefill + decode_steps x iwdft_append_attn (append fused into the decode attention, "
+                    f"coefficients written back every {J} steps)")
     result = {
         "metric": "IWDFT tokens appended/sec + compressed decode-attn us/step (frac of HBM peak)",
         "value": tokens / elapsed,
@@ -232,19 +264,17 @@ def main():
                         f"{cfg.n_bins} kept bins/layer ({cfg.mask}), {dsteps} x (append + decode attention), "
                         f"{cfg.group} query heads per KV head",
             "decode_steps": dsteps,
+            "write_every": J,
             "step_definition": step_def,
         },
         "decode_attn_us_per_step": 1e3 * att_avg,
         "append_tokens_per_s": cfg.batch / (app_avg * 1e-3),
-        "decode_step_us": 1e3 * step_avg,
         "kernels": {
             "iwdft_append": {"avg_ms": app_avg, "min_ms": float(app_ms.min()), "algorithmic_GB": append_bytes / 1e9,
-                             "GBps": gbps(append_bytes, app_avg),
-                             "frac_hbm_peak": gbps(append_bytes, app_avg) / HBM_PEAK_GBS},
+                             "GBps": gbps(append_bytes, app_avg), "frac_hbm_peak": frac(append_bytes, app_avg)},
             "compressed_decode_attn": {"avg_ms": att_avg, "min_ms": float(att_ms.min()),
                                        "algorithmic_GB": attn_bytes / 1e9,
-                                       "GBps": gbps(attn_bytes, att_avg),
-                                       "frac_hbm_peak": gbps(attn_bytes, att_avg) / HBM_PEAK_GBS},
+                                       "GBps": gbps(attn_bytes, att_avg), "frac_hbm_peak": frac(attn_bytes, att_avg)},
             "iwdft_prefill": {"kind": pre_kind, "avg_ms": pre_avg,
                               "algorithmic_GB": (kv_in_bytes + 2 * coef_bytes) / 1e9,
                               "GBps": gbps(kv_in_bytes + 2 * coef_bytes, pre_avg),
@@ -262,29 +292,43 @@ def main():
             "achieved": gbps(roof_bytes, roof_ms),
             "peak": HBM_PEAK_GBS,
             "unit": "GB/s",
-            "frac": gbps(roof_bytes, roof_ms) / HBM_PEAK_GBS,
+            "frac": frac(roof_bytes, roof_ms),
             "traffic": traffic,
         },
     }
+    k = result["kernels"]
     if fused:
-        # every coefficient read once and written once per step: the same bytes as one append
-        result["kernels"]["iwdft_append_attn"] = {
-            "avg_ms": step_avg, "min_ms": float(step_ms.min()), "algorithmic_GB": append_bytes / 1e9,
-            "GBps": gbps(append_bytes, step_avg), "frac_hbm_peak": gbps(append_bytes, step_avg) / HBM_PEAK_GBS,
-            "phase_A_K_update_scores_ms": phase_avg[0], "phase_B_softmax_transforms_ms": phase_avg[1],
-            "phase_C_V_update_output_ms": phase_avg[2],
-            "phase_A_frac_hbm_peak": gbps(2 * coef_bytes, phase_avg[0]) / HBM_PEAK_GBS,
-            "phase_C_frac_hbm_peak": gbps(2 * coef_bytes, phase_avg[2]) / HBM_PEAK_GBS,
+        after = "separate context after the timed region"
+        k["iwdft_append"]["measured"] = k["compressed_decode_attn"]["measured"] = after
+        # write_every = 1: every coefficient read once and written once per step = the bytes of one append
+        k["iwdft_append_attn_write_every_1"] = {
+            "measured": after if J > 1 else "timed region", "avg_ms": float(f1_ms.mean()), "min_ms": float(f1_ms.min()),
+            "algorithmic_GB": append_bytes / 1e9, "frac_hbm_peak": frac(append_bytes, float(f1_ms.mean())),
+            "phase_A_K_update_scores_ms": f1_phase[0], "phase_B_softmax_transforms_ms": f1_phase[1],
+            "phase_C_V_update_output_ms": f1_phase[2],
+            "phase_A_frac_hbm_peak": frac(2 * coef_bytes, f1_phase[0]),
+            "phase_C_frac_hbm_peak": frac(2 * coef_bytes, f1_phase[2]),
         }
-        result["kernels"]["iwdft_append"]["measured"] = "separate calls after the timed region"
-        result["kernels"]["compressed_decode_attn"]["measured"] = "separate calls after the timed region"
+        avg_step = (float(plain_ms.mean()) * (J - 1) + float(wb_ms.mean())) / J if J > 1 else float(wb_ms.mean())
+        avg_bytes = attn_bytes + (append_bytes - attn_bytes) / J      # reads every step, writes every J-th
+        k["iwdft_append_attn"] = {
+            "write_every": J, "avg_ms": avg_step, "algorithmic_GB_per_step": avg_bytes / 1e9,
+            "frac_hbm_peak": frac(avg_bytes, avg_step),
+            "read_only_step_ms": float(plain_ms.mean()) if J > 1 else None,
+            "write_back_step_ms": float(wb_ms.mean()),
+            "marked_steps": "read-only" if J > 1 else "write-back",
+            "phase_A_ms": phase_avg[0], "phase_B_ms": phase_avg[1], "phase_C_ms": phase_avg[2],
+            "phase_A_frac_hbm_peak": frac(coef_bytes * (1 if J > 1 else 2), phase_avg[0]),
+            "phase_C_frac_hbm_peak": frac(coef_bytes * (1 if J > 1 else 2), phase_avg[2]),
+        }
+        result["decode_step_us"] = 1e3 * avg_step
     else:
-        result["kernels"]["compressed_decode_attn"].update(
+        k["compressed_decode_attn"].update(
             {"phase_A_ms": phase_avg[0], "phase_B_ms": phase_avg[1], "phase_C_ms": phase_avg[2]})
+        result["decode_step_us"] = 1e3 * (app_avg + att_avg)
 
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(cfg, bins, K, V, pool, np, torch)
-    cache.close()
     print(json.dumps(result), flush=True)
 
 

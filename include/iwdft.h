@@ -94,7 +94,8 @@ typedef struct {
   int32_t n_sink;             /* S >= 0: first S prefill tokens kept exact (attention sinks) */
   int32_t n_recent;           /* R >= 0: the R newest tokens kept exact (recent window);
                                  S + R <= 1024                                         */
-  uint32_t reserved;          /* must be 0 */
+  uint32_t write_every;       /* J: iwdft_append_attn writes the coefficients back on every J-th call only
+                                 (0 or 1: on every call; at most 8); see iwdft_append_attn         */
 } iwdft_desc;
 
 /* Sizes of the two caller-provided device buffers for this descriptor. */
@@ -148,7 +149,17 @@ int compressed_decode_attn(iwdft_ctx* ctx, const void* d_q, void* d_out, float s
  * of the decoding stage, Sec. 4.2.2), fused: each K coefficient is updated (Eq. infi-dft) on its
  * way into the scores and each V coefficient on its way into the output, so every coefficient is
  * read once and written once per step instead of read twice and written once.  Same arguments,
- * same result (up to rounding order) and same errors as the two calls in sequence.  T -> T+1. */
+ * same result (up to rounding order) and same errors as the two calls in sequence.  T -> T+1.
+ *
+ * desc.write_every = J > 1 defers the write-back: the step's token (the one leaving the recent window
+ * when R > 0) is kept in the workspace, and until J of them have gathered the coefficients are only
+ * read -- the tokens they do not hold yet enter scores and output through the exact rank-one terms
+ * F + x e^{j theta} contributes -- so every call still returns the attention over all T tokens, and the
+ * coefficients are written once per J steps.  Every other call on the context (append, attention,
+ * reconstruct, export) first writes the deferred tokens back, so results never depend on J beyond
+ * rounding order; only a caller that copies the state buffer itself (checkpoint) must call iwdft_flush
+ * first.  Deferral needs the FFT attention path and at most 8 query heads per KV head; without them
+ * J is taken as 1. */
 int iwdft_append_attn(iwdft_ctx* ctx, const void* d_tok_k, const void* d_tok_v, const void* d_q,
                       void* d_out, float scale, void* hip_stream);
 
@@ -165,6 +176,10 @@ int iwdft_phase_timing(iwdft_ctx* ctx, int enable);
  * phase in milliseconds (ms[0..2] = A, B, C; HOST) and the number of calls, and clears the list. */
 int iwdft_phase_times(iwdft_ctx* ctx, double* ms, int64_t* n_calls);
 
+/* Writes tokens deferred by iwdft_append_attn (desc.write_every > 1) into the coefficients; afterwards the
+ * state buffer alone describes the cache.  No-op when nothing is deferred. */
+int iwdft_flush(iwdft_ctx* ctx, void* hip_stream);
+
 /* The paper-convention coefficients S_T of one layer, for inspection and parity:
  * d_SK, d_SV: [batch][n_kv_heads][|B_layer|][head_dim][2] (re, im) fp32; either may be NULL. */
 int iwdft_export_coeffs(iwdft_ctx* ctx, int32_t layer, float* d_SK, float* d_SV,
@@ -177,8 +192,8 @@ int64_t iwdft_num_tokens(const iwdft_ctx* ctx); /* T = tokens inside the coeffic
                                                     recent tokens are not counted); 0 before prefill;
                                                     -1 if ctx is NULL */
 
-/* Sets T after the caller restored a saved copy of the state buffer (checkpoint / resume).
- * T >= M. */
+/* Sets T after the caller restored a saved copy of the state buffer (checkpoint / resume; the copy
+ * must have been taken after iwdft_flush if write-back is deferred).  T >= M. */
 int iwdft_set_num_tokens(iwdft_ctx* ctx, int64_t T);
 
 /* Greedy frequency mask of the ablation study (Sec. 3.2): the M bins are cut into n_chunks contiguous

@@ -25,7 +25,7 @@ EXPORTED = [
     "iwdft_query_bytes", "iwdft_create", "iwdft_destroy", "iwdft_prefill", "iwdft_append",
     "iwdft_reconstruct", "compressed_decode_attn", "iwdft_append_attn", "iwdft_export_coeffs", "iwdft_export_bins",
     "iwdft_num_tokens", "iwdft_set_num_tokens", "iwdft_last_error", "iwdft_phase_timing", "iwdft_phase_times", "iwdft_prefill_kind",
-    "iwdft_select_bins", "iwdft_ablate_chunk",
+    "iwdft_select_bins", "iwdft_ablate_chunk", "iwdft_flush",
 ]
 
 LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libiwdft.so")
@@ -46,7 +46,7 @@ class iwdft_desc(ctypes.Structure):
         ("bins", ctypes.POINTER(ctypes.c_int32)),
         ("bin_weights", ctypes.POINTER(ctypes.c_float)),
         ("flags", ctypes.c_uint32), ("n_sink", ctypes.c_int32), ("n_recent", ctypes.c_int32),
-        ("reserved", ctypes.c_uint32),
+        ("write_every", ctypes.c_uint32),
     ]
 
 
@@ -74,6 +74,7 @@ def load_library() -> ctypes.CDLL:
     lib.compressed_decode_attn.argtypes = [vp, vp, vp, f32, vp]
     lib.iwdft_append_attn.argtypes = [vp, vp, vp, vp, vp, f32, vp]
     lib.iwdft_prefill_kind.argtypes = [vp]
+    lib.iwdft_flush.argtypes = [vp, vp]
     lib.iwdft_select_bins.argtypes = [ctypes.POINTER(ctypes.c_float), i32, i32, i64, ctypes.c_double,
                                       ctypes.POINTER(ctypes.c_int64), ctypes.POINTER(ctypes.c_int32), i64]
     lib.iwdft_ablate_chunk.argtypes = [vp, vp, i64, i64, i32, i32, i32, i32, vp]
@@ -122,7 +123,7 @@ class Descriptor:
     def __init__(self, n_layers: int, batch: int, n_kv_heads: int, n_q_heads: int, head_dim: int,
                  kv_dtype: int, M: int, bins: Sequence[np.ndarray],
                  bin_weights: Optional[Sequence[np.ndarray]] = None, flags: int = 0,
-                 n_sink: int = 0, n_recent: int = 0):
+                 n_sink: int = 0, n_recent: int = 0, write_every: int = 0):
         self.bins = [np.ascontiguousarray(b, dtype=np.int32) for b in bins]
         self._offsets = np.zeros(len(self.bins) + 1, dtype=np.int64)
         self._offsets[1:] = np.cumsum([len(b) for b in self.bins])
@@ -135,7 +136,7 @@ class Descriptor:
             self._offsets.ctypes.data_as(ctypes.POINTER(ctypes.c_int64)),
             self._flat.ctypes.data_as(ctypes.POINTER(ctypes.c_int32)),
             self._w.ctypes.data_as(ctypes.POINTER(ctypes.c_float)) if self._w is not None else None,
-            flags, n_sink, n_recent, 0)
+            flags, n_sink, n_recent, write_every)
 
 
 def iwdft_query_bytes(desc: Descriptor):
@@ -202,6 +203,10 @@ def iwdft_ablate_chunk(x: torch.Tensor, out: torch.Tensor, n_chunks: int, chunk:
                                              n_chunks, chunk, _stream(stream)))
 
 
+def iwdft_flush(ctx, stream=None) -> None:
+    _check(load_library().iwdft_flush(ctx, _stream(stream)))
+
+
 def iwdft_prefill_kind(ctx) -> str:
     return {0: "dense", 1: "fft"}[load_library().iwdft_prefill_kind(ctx)]
 
@@ -238,13 +243,13 @@ class Cache:
     """Owns the torch buffers behind one iwdft_ctx; methods forward to the C calls."""
 
     def __init__(self, n_layers, batch, n_kv_heads, n_q_heads, head_dim, dtype: torch.dtype, M,
-                 bins, bin_weights=None, flags=0, device="cuda:0", n_sink=0, n_recent=0):
+                 bins, bin_weights=None, flags=0, device="cuda:0", n_sink=0, n_recent=0, write_every=0):
         if dtype not in (torch.float32, torch.bfloat16):
             raise ValueError("dtype must be float32 or bfloat16")
         self.dtype, self.device = dtype, torch.device(device)
         self.desc = Descriptor(n_layers, batch, n_kv_heads, n_q_heads, head_dim,
                                IWDFT_F32 if dtype == torch.float32 else IWDFT_BF16, M, bins, bin_weights, flags,
-                               n_sink, n_recent)
+                               n_sink, n_recent, write_every)
         self.state_bytes, self.ws_bytes = iwdft_query_bytes(self.desc)
         with torch.cuda.device(self.device):
             self.state = torch.empty(self.state_bytes, dtype=torch.uint8, device=self.device)
@@ -285,6 +290,9 @@ class Cache:
             out = torch.empty_like(q)
         iwdft_append_attn(self.ctx, tok_k, tok_v, q, out, scale, stream)
         return out
+
+    def flush(self, stream=None):
+        iwdft_flush(self.ctx, stream)
 
     def reconstruct(self, layer, a0, n_slots, want_k=True, want_v=True, stream=None):
         L, B, H, _, D = self.shape

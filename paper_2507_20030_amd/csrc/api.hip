@@ -37,9 +37,10 @@ struct Plan {  // byte offsets inside the two caller buffers, derived from a des
   int32_t G = 1, max_nb = 0, max_Bp = 0;
   bool use_fft = false;          // decode attention through FFTs
   bool use_fft_prefill = false;  // prefill through FFTs (else the dense MFMA contraction)
+  int write_every = 1;           // fused decode step: coefficients written back every this many tokens
   size_t off_layers = 0, off_bins = 0, off_weights = 0, off_fold = 0, off_FK = 0, off_FV = 0, state_bytes = 0;
   size_t off_sinkK = 0, off_sinkV = 0, off_ringK = 0, off_ringV = 0;
-  size_t off_qc = 0, off_Pn = 0, off_pe = 0, off_stageK = 0, off_stageV = 0, off_direct = 0, ws_bytes = 0;
+  size_t off_qc = 0, off_Pn = 0, off_pe = 0, off_pendK = 0, off_pendV = 0, off_ps = 0, off_direct = 0, ws_bytes = 0;
 };
 
 // Largest problem the FFT attention kernel keeps in registers / LDS.
@@ -58,7 +59,8 @@ int make_plan(const iwdft_desc* d, Plan* pl) {
                 d->n_kv_heads);
   if (d->kv_dtype != IWDFT_F32 && d->kv_dtype != IWDFT_BF16)
     return fail(IWDFT_ERR_ARG, "kv_dtype %d is neither IWDFT_F32 nor IWDFT_BF16", d->kv_dtype);
-  if (d->reserved != 0) return fail(IWDFT_ERR_ARG, "reserved must be 0");
+  if (d->write_every > (uint32_t)kMaxPend)
+    return fail(IWDFT_ERR_ARG, "write_every = %u exceeds %d", d->write_every, kMaxPend);
   if (d->flags & ~(uint32_t)(IWDFT_FLAG_DIRECT_SYNTHESIS | IWDFT_FLAG_DENSE_PREFILL | IWDFT_FLAG_FFT_PREFILL))
     return fail(IWDFT_ERR_ARG, "unknown bits in flags: 0x%x", d->flags);
   if ((d->flags & IWDFT_FLAG_DENSE_PREFILL) && (d->flags & IWDFT_FLAG_FFT_PREFILL))
@@ -175,8 +177,13 @@ int make_plan(const iwdft_desc* d, Plan* pl) {
   pl->off_qc = o; o = align256(o + sizeof(float2) * (size_t)ws);
   pl->off_Pn = o; o = align256(o + sizeof(float2) * (size_t)ws);
   pl->off_pe = o; o = align256(o + sizeof(float) * n_sl * (size_t)pl->G * (size_t)(d->n_sink + d->n_recent));
-  pl->off_stageK = o; o = align256(o + (d->n_recent ? esz * n_sl * kHeadDim : 0));
-  pl->off_stageV = o; o = align256(o + (d->n_recent ? esz * n_sl * kHeadDim : 0));
+  // Deferred write-back needs the FFT attention kernels (they weigh the pending tokens) and all
+  // query heads of a KV head in one pass; otherwise every step writes back.
+  pl->write_every = (d->write_every > 1 && pl->use_fft && heads_fit_one_pass(pl->G)) ? (int)d->write_every : 1;
+  const size_t pend_rows = (d->n_recent || pl->write_every > 1) ? (size_t)pl->write_every : 0;
+  pl->off_pendK = o; o = align256(o + esz * n_sl * pend_rows * kHeadDim);
+  pl->off_pendV = o; o = align256(o + esz * n_sl * pend_rows * kHeadDim);
+  pl->off_ps = o;    o = align256(o + (pl->write_every > 1 ? sizeof(float) * n_sl * (size_t)pl->G * kMaxPend : 0));
   pl->off_direct = o;
   if (!pl->use_fft)
     o = align256(o + sizeof(float) * (size_t)d->n_layers * (size_t)slices_per_layer *
@@ -195,6 +202,7 @@ struct iwdft_ctx {
   int64_t T = 0;
   char* state = nullptr;
   char* ws = nullptr;
+  int pend = 0;  // tokens counted in T that only the pending rows hold (deferred write-back), < write_every
   // phase timing (iwdft_phase_timing): events of the calls since the last read-out
   bool timing = false;
   std::vector<iwdft::PhaseEvents> marks;  // pool, reused after every read-out
@@ -244,6 +252,23 @@ int next_marks(iwdft_ctx* c, const PhaseEvents** out) {
 
 uint32_t t_shift(const iwdft_ctx* c) {  // (T - M) mod M
   return (uint32_t)((c->T - c->desc.M) % c->desc.M);
+}
+
+// Writes the tokens that the fused decode step has deferred into the coefficients, oldest first, one
+// streaming update each (the rare path: a call other than the fused step arrived in between).
+int flush_pending(iwdft_ctx* c, hipStream_t st) {
+  if (c->pend == 0) return IWDFT_OK;
+  const Plan& pl = c->plan;
+  const size_t esz = c->desc.kv_dtype == IWDFT_BF16 ? 2 : 4;
+  for (int j = 0; j < c->pend; ++j) {
+    const uint32_t tsh = (uint32_t)((c->T - c->pend + j - c->desc.M) % c->desc.M);
+    hipError_t e = launch_absorb(c->P, c->ws + pl.off_pendK + (size_t)j * kHeadDim * esz,
+                                 c->ws + pl.off_pendV + (size_t)j * kHeadDim * esz,
+                                 (int64_t)pl.write_every * kHeadDim, tsh, st);
+    if (e != hipSuccess) return fail(IWDFT_ERR_HIP, "write-back of deferred tokens: %s", hipGetErrorString(e));
+  }
+  c->pend = 0;
+  return IWDFT_OK;
 }
 
 }  // namespace
@@ -394,6 +419,7 @@ int iwdft_set_num_tokens(iwdft_ctx* ctx, int64_t T) {
   if (!ctx) return fail(IWDFT_ERR_ARG, "ctx is NULL");
   if (T < ctx->desc.M) return fail(IWDFT_ERR_ARG, "T = %lld is below M", (long long)T);
   ctx->T = T;
+  ctx->pend = 0;  // the restored buffer is taken as complete
   return IWDFT_OK;
 }
 
@@ -401,6 +427,7 @@ int iwdft_prefill(iwdft_ctx* ctx, const void* d_K, const void* d_V, void* hip_st
   int rc = check_ctx(ctx);
   if (rc != IWDFT_OK) return rc;
   if (!d_K || !d_V) return fail(IWDFT_ERR_ARG, "d_K / d_V is NULL");
+  ctx->pend = 0;  // the prefill overwrites the whole state
   rc = launched(ctx->plan.use_fft_prefill ? launch_prefill_fft(ctx->P, d_K, d_V, (hipStream_t)hip_stream)
                                           : launch_prefill(ctx->P, d_K, d_V, (hipStream_t)hip_stream),
                 "prefill launch");
@@ -414,6 +441,7 @@ int iwdft_append(iwdft_ctx* ctx, const void* d_tok_k, const void* d_tok_v, void*
   if (rc != IWDFT_OK) return rc;
   if (!d_tok_k || !d_tok_v) return fail(IWDFT_ERR_ARG, "d_tok_k / d_tok_v is NULL");
   if (ctx->T < ctx->desc.M) return fail(IWDFT_ERR_STATE, "iwdft_append before iwdft_prefill");
+  if ((rc = flush_pending(ctx, (hipStream_t)hip_stream)) != IWDFT_OK) return rc;
   // The recent ring was filled oldest-first at prefill, so after T - M appends the oldest token
   // sits in slot (T - M) mod R.
   const uint32_t ring_pos = ctx->P.R ? (uint32_t)((ctx->T - ctx->desc.M) % ctx->P.R) : 0u;
@@ -430,6 +458,7 @@ int iwdft_export_coeffs(iwdft_ctx* ctx, int32_t layer, float* d_SK, float* d_SV,
   if (layer < 0 || layer >= ctx->desc.n_layers) return fail(IWDFT_ERR_ARG, "layer %d out of range", layer);
   if (ctx->T < ctx->desc.M) return fail(IWDFT_ERR_STATE, "iwdft_export_coeffs before iwdft_prefill");
   if (!d_SK && !d_SV) return IWDFT_OK;
+  if ((rc = flush_pending(ctx, (hipStream_t)hip_stream)) != IWDFT_OK) return rc;
   return launched(launch_export(ctx->P, layer, d_SK, d_SV, t_shift(ctx), (float)(1.0 / (double)ctx->T),
                                 (hipStream_t)hip_stream),
                   "export launch");
@@ -455,6 +484,7 @@ int iwdft_reconstruct(iwdft_ctx* ctx, int32_t layer, int64_t a0, int64_t n_slots
     return fail(IWDFT_ERR_ARG, "slots [%lld, %lld) outside [0, M)", (long long)a0, (long long)(a0 + n_slots));
   if (ctx->T < ctx->desc.M) return fail(IWDFT_ERR_STATE, "iwdft_reconstruct before iwdft_prefill");
   if (n_slots == 0 || (!d_Kt && !d_Vt)) return IWDFT_OK;
+  if ((rc = flush_pending(ctx, (hipStream_t)hip_stream)) != IWDFT_OK) return rc;
   return launched(launch_reconstruct(ctx->P, layer, (uint32_t)a0, (uint32_t)n_slots, d_Kt, d_Vt,
                                      t_shift(ctx), (hipStream_t)hip_stream),
                   "reconstruct launch");
@@ -467,6 +497,7 @@ int compressed_decode_attn(iwdft_ctx* ctx, const void* d_q, void* d_out, float s
   if (ctx->T < ctx->desc.M) return fail(IWDFT_ERR_STATE, "compressed_decode_attn before iwdft_prefill");
   if (!std::isfinite(scale)) return fail(IWDFT_ERR_ARG, "scale is not finite");
   if (scale <= 0.0f) scale = 1.0f / std::sqrt((float)ctx->desc.head_dim);
+  if ((rc = flush_pending(ctx, (hipStream_t)hip_stream)) != IWDFT_OK) return rc;
   const Plan& pl = ctx->plan;
   const PhaseEvents* marks = nullptr;
   if ((rc = next_marks(ctx, &marks)) != IWDFT_OK) return rc;
@@ -494,14 +525,23 @@ int iwdft_append_attn(iwdft_ctx* ctx, const void* d_tok_k, const void* d_tok_v, 
   const uint32_t ring_pos = ctx->P.R ? (uint32_t)((ctx->T - ctx->desc.M) % ctx->P.R) : 0u;
   const PhaseEvents* marks = nullptr;
   if ((rc = next_marks(ctx, &marks)) != IWDFT_OK) return rc;
+  const uint32_t tsh0 = (uint32_t)((ctx->T - ctx->pend - ctx->desc.M) % ctx->desc.M);  // oldest pending token
   rc = launched(launch_step(ctx->P, d_tok_k, d_tok_v, d_q, d_out, scale, (float2*)(ctx->ws + pl.off_qc),
                             (float2*)(ctx->ws + pl.off_Pn), (float*)(ctx->ws + pl.off_pe),
-                            ctx->ws + pl.off_stageK, ctx->ws + pl.off_stageV, (float*)(ctx->ws + pl.off_direct),
-                            pl.use_fft, t_shift(ctx), ring_pos, marks, (hipStream_t)hip_stream),
+                            ctx->ws + pl.off_pendK, ctx->ws + pl.off_pendV, (float*)(ctx->ws + pl.off_ps),
+                            (float*)(ctx->ws + pl.off_direct), pl.use_fft, tsh0, ring_pos, ctx->pend,
+                            pl.write_every, marks, (hipStream_t)hip_stream),
                 "fused decode step launch");
   if (rc != IWDFT_OK) return rc;
+  ctx->pend = (ctx->pend + 1) % pl.write_every;  // back to 0: this step wrote the coefficients
   ctx->T += 1;
   return IWDFT_OK;
+}
+
+int iwdft_flush(iwdft_ctx* ctx, void* hip_stream) {
+  int rc = check_ctx(ctx);
+  if (rc != IWDFT_OK) return rc;
+  return flush_pending(ctx, (hipStream_t)hip_stream);
 }
 
 int iwdft_select_bins(const float* delta, int32_t n_layers, int32_t n_chunks, int64_t M, double r,

@@ -83,9 +83,21 @@ __global__ __launch_bounds__(kHeadDim) void ring_push_kernel(Params P, const voi
   else ((float*)ring)[dst] = ((const float*)tok)[src];
 }
 
+hipError_t launch_absorb(const Params& P, const void* xk, const void* xv, int64_t x_stride, uint32_t tsh,
+                         hipStream_t st) {
+  constexpr int DROWS = 32;
+  const int chunks = (P.max_nb + kAppendBinsPerBlock - 1) / kAppendBinsPerBlock;
+  const uint64_t blocks = (uint64_t)P.n_slices * chunks * (kHeadDim / DROWS) * 2;
+  if (blocks > 0x7fffffffull) return hipErrorInvalidConfiguration;
+  if (P.kv_dtype == 1)
+    append_kernel<true, DROWS><<<dim3((uint32_t)blocks), dim3(kAppendThreads), 0, st>>>(P, xk, xv, tsh, chunks, x_stride);
+  else
+    append_kernel<false, DROWS><<<dim3((uint32_t)blocks), dim3(kAppendThreads), 0, st>>>(P, xk, xv, tsh, chunks, x_stride);
+  return hipGetLastError();
+}
+
 hipError_t launch_append(const Params& P, const void* tok_k, const void* tok_v, uint32_t tsh,
                          uint32_t ring_pos, hipStream_t st) {
-  constexpr int DROWS = 32;
   // What is absorbed: the new token (R == 0) or the token ageing out of the recent window.
   const int esz = P.kv_dtype == 1 ? 2 : 4;
   const void* xk = tok_k;
@@ -96,14 +108,7 @@ hipError_t launch_append(const Params& P, const void* tok_k, const void* tok_v, 
     xv = (const char*)P.ringV + (size_t)ring_pos * kHeadDim * esz;
     x_stride = (int64_t)P.R * kHeadDim;
   }
-  const int chunks = (P.max_nb + kAppendBinsPerBlock - 1) / kAppendBinsPerBlock;
-  const uint64_t blocks = (uint64_t)P.n_slices * chunks * (kHeadDim / DROWS) * 2;
-  if (blocks > 0x7fffffffull) return hipErrorInvalidConfiguration;
-  if (P.kv_dtype == 1)
-    append_kernel<true, DROWS><<<dim3((uint32_t)blocks), dim3(kAppendThreads), 0, st>>>(P, xk, xv, tsh, chunks, x_stride);
-  else
-    append_kernel<false, DROWS><<<dim3((uint32_t)blocks), dim3(kAppendThreads), 0, st>>>(P, xk, xv, tsh, chunks, x_stride);
-  hipError_t e = hipGetLastError();
+  hipError_t e = launch_absorb(P, xk, xv, x_stride, tsh, st);
   if (e != hipSuccess || P.R == 0) return e;
   if (P.kv_dtype == 1) ring_push_kernel<true><<<dim3((uint32_t)P.n_slices, 2), dim3(kHeadDim), 0, st>>>(P, tok_k, tok_v, ring_pos);
   else ring_push_kernel<false><<<dim3((uint32_t)P.n_slices, 2), dim3(kHeadDim), 0, st>>>(P, tok_k, tok_v, ring_pos);

@@ -57,25 +57,65 @@ __device__ __forceinline__ const void* exact_row(const Params& P, bool value, in
 constexpr int qc_threads(bool upd) { return upd ? 512 : 256; }
 constexpr int qc_bins(bool upd) { return qc_threads(upd) * 2; }
 
-// Token to absorb in the fused decode step (see launch_step): x[slice * stride + channel], and the
-// slot shift (T - M) mod M of the step.
+// Tokens of the fused decode step that the stored coefficients do not hold yet (see launch_step):
+// row j of a slice is x[slice * stride + j * 128 + channel], j < np, and token j has the slot shift
+// (tsh + j) mod M.  The kernels come in three modes:
+//   kPlain  : coefficients are only read; the np pending tokens (possibly none) enter the result
+//             through rank-np corrections -- F + sum_j x_j e^{j theta_j} is what attention sees,
+//   kUpdate1: np == 1, the token is added to every coefficient on its way through, written back,
+//   kUpdateN: the same for np <= kMaxPend tokens at once (the deferred write-back of several steps).
+constexpr int kPlain = 0, kUpdate1 = 1, kUpdateN = 2;
+constexpr int kPlainStream = 3;  // kernel C only: kPlain with streaming (non-temporal) coefficient loads
 struct StepUpdate {
   const void* xk;
   const void* xv;
   int64_t stride;
   uint32_t tsh;
+  int np;
+  float* ps;  // kPlain with np > 0: [slice][query head][kMaxPend], Re sum_k e^{j theta_jk} Pn[k] (from kernel B)
 };
 
+// (a.xy, a.zw) * (b.xy, b.zw): two complex products side by side.
+__device__ __forceinline__ v4f cmul2(v4f a, v4f b) {
+  v4f r;
+  r.x = a.x * b.x - a.y * b.y;
+  r.y = a.x * b.y + a.y * b.x;
+  r.z = a.z * b.z - a.w * b.w;
+  r.w = a.z * b.w + a.w * b.z;
+  return r;
+}
+
+// Twiddles of a lane's two adjacent bins i0, i0 + 1 for slot shift p: (e^{j 2 pi k0 p / M}, e^{j 2 pi k1 p / M});
+// a bin beyond the layer's list gets 0, which keeps padding entries at zero.
+__device__ __forceinline__ v4f lane_twiddles(const Params& P, const LayerInfo& L, int i0, uint32_t p) {
+  v4f tw = (v4f)(0.f);
+  if (i0 < L.nb) {
+    const float2 w0 = cis(mulmod((uint32_t)P.bins[L.bin_off + i0], p, P.M, P.Mmask), P.M);
+    tw.x = w0.x;
+    tw.y = w0.y;
+    if (i0 + 1 < L.nb) {
+      const float2 w1 = cis(mulmod((uint32_t)P.bins[L.bin_off + i0 + 1], p, P.M, P.Mmask), P.M);
+      tw.z = w1.x;
+      tw.w = w1.y;
+    }
+  }
+  return tw;
+}
+
 // grid: (slice * chunks + chunk) * passes + pass.  Lane = two adjacent bins, loop over channels.
-// UPD: fused decode step -- every K coefficient first absorbs the token (the streaming update,
-// Eq. infi-dft in the fixed frame: F += x e^{+j 2 pi k (T-M)/M}), is written back, and the updated
-// value feeds qc, so that K coefficients are read once per step instead of twice (needs passes == 1).
-template <bool BF16, int GT, bool UPD>
-__global__ __launch_bounds__(qc_threads(UPD)) void attn_qc_kernel(Params P, const void* __restrict__ q,
+// Update modes (fused decode step): every K coefficient first absorbs the pending token(s) (the
+// streaming update, Eq. infi-dft in the fixed frame: F += x e^{+j 2 pi k (T-M)/M}), is written back, and
+// the updated value feeds qc, so that K coefficients are read once per step instead of twice (needs
+// passes == 1).  kPlain with pending tokens: qc[k] += sum_j (q . k_j) e^{j theta_jk} instead.
+template <bool BF16, int GT, int MODE>
+__global__ __launch_bounds__(qc_threads(MODE != kPlain)) void attn_qc_kernel(Params P, const void* __restrict__ q,
                                                             float2* __restrict__ qc, float* __restrict__ pe,
                                                             int chunks, int passes, StepUpdate up) {
+  constexpr bool UPD = MODE != kPlain;
   constexpr int kQcThreads = qc_threads(UPD), kQcBins = qc_bins(UPD);
   __shared__ float qs[GT][kHeadDim];
+  __shared__ float xs[MODE == kUpdateN ? kMaxPend : 1][kHeadDim];  // pending K rows
+  __shared__ float dq[MODE == kPlain ? kMaxPend : 1][GT];          // q . k_j of the pending tokens
   uint32_t bid = blockIdx.x;
   const int pass = bid % passes;
   bid /= passes;
@@ -92,6 +132,23 @@ __global__ __launch_bounds__(qc_threads(UPD)) void attn_qc_kernel(Params P, cons
         (g < P.G) ? load_kv<BF16>(q, ((int64_t)slice * P.G + g) * kHeadDim + (e % kHeadDim)) : 0.f;
   }
   __syncthreads();
+  if constexpr (MODE == kUpdateN) {
+    for (int e = threadIdx.x; e < up.np * kHeadDim; e += kQcThreads)
+      xs[e / kHeadDim][e % kHeadDim] = load_kv<BF16>(up.xk, (int64_t)slice * up.stride + e);
+    __syncthreads();
+  }
+  if constexpr (MODE == kPlain) {
+    if (up.np > 0) {  // block-uniform
+      for (int idx = threadIdx.x; idx < up.np * GT; idx += kQcThreads) {
+        const int j = idx / GT, g = idx % GT;
+        float dot = 0.f;
+        for (int c = 0; c < kHeadDim; ++c)
+          dot += qs[g][c] * load_kv<BF16>(up.xk, (int64_t)slice * up.stride + j * kHeadDim + c);
+        dq[j][g] = dot;
+      }
+      __syncthreads();
+    }
+  }
   const int E = P.S + P.R;
   if (chunk == 0 && E > 0) {  // raw scores q . k_e of the exact tokens, one (token, head) per thread
     for (int idx = threadIdx.x; idx < E * GT; idx += kQcThreads) {
@@ -120,28 +177,38 @@ __global__ __launch_bounds__(qc_threads(UPD)) void attn_qc_kernel(Params P, cons
   if (i0 >= L.Bp) return;
   v4f* row = (v4f*)(P.FK + L.coef_off + (int64_t)s * kHeadDim * L.Bp + i0);
   const int64_t stride = L.Bp / 2;
-  v4f tw = (v4f)(0.f);  // twiddles of this lane's two bins; padding entries keep 0 and are not written
+  // twiddles of this lane's two bins; padding entries keep 0 and are not written
   const bool live = i0 < L.nb;
-  if (UPD && live) {
-    const float2 w0 = cis(mulmod((uint32_t)P.bins[L.bin_off + i0], up.tsh, P.M, P.Mmask), P.M);
-    tw.x = w0.x;
-    tw.y = w0.y;
-    if (i0 + 1 < L.nb) {
-      const float2 w1 = cis(mulmod((uint32_t)P.bins[L.bin_off + i0 + 1], up.tsh, P.M, P.Mmask), P.M);
-      tw.z = w1.x;
-      tw.w = w1.y;
-    }
+  v4f tw = (v4f)(0.f);
+  if (UPD || up.np > 0) tw = lane_twiddles(P, L, i0, up.tsh);
+  v4f twn[MODE == kUpdateN ? kMaxPend : 1];  // kUpdateN: twiddle of every pending token
+  if constexpr (MODE == kUpdateN) {
+    const v4f w = lane_twiddles(P, L, i0, 1u);  // one slot further per token
+    twn[0] = tw;
+#pragma unroll
+    for (int j = 1; j < kMaxPend; ++j) twn[j] = cmul2(twn[j - 1], w);
   }
   v4f acc[GT];
 #pragma unroll
   for (int g = 0; g < GT; ++g) acc[g] = (v4f)(0.f);
+  if constexpr (MODE == kPlain) {
+    if (up.np > 0) {  // the pending tokens' share of qc
+      const v4f w = lane_twiddles(P, L, i0, 1u);
+      v4f t = tw;
+      for (int j = 0; j < up.np; ++j) {
+#pragma unroll
+        for (int g = 0; g < GT; ++g) acc[g] += dq[j][g] * t;
+        t = cmul2(t, w);
+      }
+    }
+  }
   constexpr int U = 8;
 #pragma unroll 1
   for (int d = 0; d < kHeadDim; d += U) {
     v4f f[U];
 #pragma unroll
     for (int u = 0; u < U; ++u) f[u] = __builtin_nontemporal_load(row + (d + u) * stride);
-    if constexpr (UPD) {
+    if constexpr (MODE == kUpdate1) {
       float x[U];
 #pragma unroll
       for (int u = 0; u < U; ++u) x[u] = load_kv<BF16>(up.xk, (int64_t)slice * up.stride + d + u);
@@ -150,6 +217,18 @@ __global__ __launch_bounds__(qc_threads(UPD)) void attn_qc_kernel(Params P, cons
         f[u] += x[u] * tw;
         if (live) __builtin_nontemporal_store(f[u], row + (d + u) * stride);
       }
+    }
+    if constexpr (MODE == kUpdateN) {
+#pragma unroll
+      for (int j = 0; j < kMaxPend; ++j) {
+        if (j < up.np) {
+#pragma unroll
+          for (int u = 0; u < U; ++u) f[u] += xs[j][d + u] * twn[j];
+        }
+      }
+#pragma unroll
+      for (int u = 0; u < U; ++u)
+        if (live) __builtin_nontemporal_store(f[u], row + (d + u) * stride);
     }
 #pragma unroll
     for (int u = 0; u < U; ++u)
@@ -200,14 +279,18 @@ __device__ __forceinline__ float wave_reduce_scatter(float (&v)[V], int lane) {
 // The coefficient loads are ordinary (cacheable) loads on purpose: what they leave in the
 // memory-side cache is V state the next append reads first (measured: append 357 -> 326 us on the
 // 32 x 8 x 2048-bin workload, this kernel +5 us).
-// UPD: fused decode step -- every V coefficient absorbs the token on its way through (written back,
-// the updated value is what attention uses), so V coefficients are read once per step too.  There
-// the state is touched once per step and nothing gains from caching it: streaming (non-temporal)
-// loads and stores measured 195 -> 177 us.
-template <bool BF16, int GT, bool UPD>
+// Update modes (fused decode step): every V coefficient absorbs the pending token(s) on its way through
+// (written back, the updated value is what attention uses), so V coefficients are read once per step
+// too.  There the state is touched once per step and nothing gains from caching it: streaming
+// (non-temporal) loads and stores measured 195 -> 177 us.  kPlain with pending tokens: the output gets
+// sum_j ps[j] v_j added at the end, and the loads stream as well (no append follows that could reuse them).
+template <bool BF16, int GT, int MODE>
 __global__ __launch_bounds__(kOutThreads) void attn_out_kernel(Params P, const float2* __restrict__ Pn,
                                                               void* __restrict__ out, const float* __restrict__ pe,
                                                               int passes, int per_xcd, int total, StepUpdate up) {
+  constexpr bool UPD = MODE == kUpdate1 || MODE == kUpdateN;
+  constexpr bool PLAIN = !UPD;
+  constexpr bool STREAM = MODE != kPlain;  // nothing re-reads the V coefficients soon: bypass the caches
   constexpr int V = kOutDC * GT;
   constexpr int VR = V > 64 ? 64 : V;  // values per reduction round
   __shared__ float red[kOutThreads / 64][V];
@@ -230,10 +313,17 @@ __global__ __launch_bounds__(kOutThreads) void attn_out_kernel(Params P, const f
   float acc[V];
 #pragma unroll
   for (int v = 0; v < V; ++v) acc[v] = 0.f;
-  float xr[UPD ? kOutDC : 1];
-  if constexpr (UPD) {
+  float xr[MODE == kUpdate1 ? kOutDC : 1];
+  if constexpr (MODE == kUpdate1) {
 #pragma unroll
     for (int dd = 0; dd < kOutDC; ++dd) xr[dd] = load_kv<BF16>(up.xv, (int64_t)slice * up.stride + d0 + dd);
+  }
+  __shared__ float xs[MODE == kUpdateN ? kMaxPend : 1][kOutDC];  // pending V rows, this block's channels
+  if constexpr (MODE == kUpdateN) {
+    for (int e = threadIdx.x; e < up.np * kOutDC; e += kOutThreads)
+      xs[e / kOutDC][e % kOutDC] =
+          load_kv<BF16>(up.xv, (int64_t)slice * up.stride + (e / kOutDC) * kHeadDim + d0 + (e % kOutDC));
+    __syncthreads();
   }
 
   for (int i0 = threadIdx.x * 2; i0 < L.Bp; i0 += kOutThreads * 2) {
@@ -244,8 +334,28 @@ __global__ __launch_bounds__(kOutThreads) void attn_out_kernel(Params P, const f
     v4f f[kOutDC];
 #pragma unroll
     for (int dd = 0; dd < kOutDC; ++dd)
-      f[dd] = UPD ? __builtin_nontemporal_load(Fv + dd * stride + i0 / 2) : Fv[dd * stride + i0 / 2];
-    if constexpr (UPD) {
+      f[dd] = STREAM ? __builtin_nontemporal_load(Fv + dd * stride + i0 / 2) : Fv[dd * stride + i0 / 2];
+    if constexpr (MODE == kUpdateN) {
+      if (i0 < L.nb) {  // padding entries are never written
+        v4f t = (v4f)(0.f), w = (v4f)(0.f);
+        const uint32_t k0 = (uint32_t)P.bins[L.bin_off + i0];
+        const float2 a0 = cis_poly(mulmod(k0, up.tsh, P.M, P.Mmask), P.M), b0 = cis_poly(k0, P.M);
+        t.x = a0.x, t.y = a0.y, w.x = b0.x, w.y = b0.y;
+        if (i0 + 1 < L.nb) {
+          const uint32_t k1 = (uint32_t)P.bins[L.bin_off + i0 + 1];
+          const float2 a1 = cis_poly(mulmod(k1, up.tsh, P.M, P.Mmask), P.M), b1 = cis_poly(k1, P.M);
+          t.z = a1.x, t.w = a1.y, w.z = b1.x, w.w = b1.y;
+        }
+        for (int j = 0; j < up.np; ++j) {
+#pragma unroll
+          for (int dd = 0; dd < kOutDC; ++dd) f[dd] += xs[j][dd] * t;
+          t = cmul2(t, w);
+        }
+#pragma unroll
+        for (int dd = 0; dd < kOutDC; ++dd) __builtin_nontemporal_store(f[dd], Fv + dd * stride + i0 / 2);
+      }
+    }
+    if constexpr (MODE == kUpdate1) {
       if (i0 < L.nb) {  // padding entries are never written
         v4f tw = (v4f)(0.f);
         const float2 w0 = cis_poly(mulmod((uint32_t)P.bins[L.bin_off + i0], up.tsh, P.M, P.Mmask), P.M);
@@ -291,6 +401,11 @@ __global__ __launch_bounds__(kOutThreads) void attn_out_kernel(Params P, const f
       const float* w = pe + ((int64_t)slice * P.G + g0 + g) * E;
       for (int e = 0; e < E; ++e)  // exact tokens: weights already divided by the softmax sum
         tot += w[e] * load_kv<BF16>(exact_row<BF16>(P, true, slice, e), d0 + dd);
+      if constexpr (PLAIN) {
+        const float* sj = up.ps + ((int64_t)slice * P.G + g0 + g) * kMaxPend;
+        for (int j = 0; j < up.np; ++j)  // pending tokens' share of the V coefficients
+          tot += sj[j] * load_kv<BF16>(up.xv, (int64_t)slice * up.stride + j * kHeadDim + d0 + dd);
+      }
       store_kv<BF16>(out, ((int64_t)slice * P.G + g0 + g) * kHeadDim + d0 + dd, tot);
     }
   }
@@ -340,9 +455,11 @@ __device__ __forceinline__ int64_t s_global_head(int slice, int G, int g) { retu
 template <int LOGQ, int NBT, bool MULTI>
 __global__ __launch_bounds__(kFftThreads, (MULTI && NBT > 4) ? 2 : 4) void attn_fft_kernel(Params P, const float2* __restrict__ qc,
                                                                  float2* __restrict__ Pn, float* __restrict__ pe,
-                                                                 float scale, int pairs) {
+                                                                 float scale, int pairs, int np, uint32_t ptsh,
+                                                                 float* __restrict__ ps) {
   extern __shared__ float2 smem[];
   __shared__ float2 scratch[kFftThreads / 64];
+  __shared__ float2 pscr[kFftThreads / 64][kMaxPend];
   const int tid = threadIdx.x;
   constexpr int Q = 1 << LOGQ;
   float2* buf = smem;                 // Q samples, padded
@@ -523,6 +640,11 @@ __global__ __launch_bounds__(kFftThreads, (MULTI && NBT > 4) ? 2 : 4) void attn_
   float2* o1 = o0 + L.Bp;
   const float inv_M = 1.0f / (float)P.M;
   const float iz0 = inv_M / Z.x, iz1 = has1 ? inv_M / Z.y : 0.f;
+  // Pending tokens of the fused decode step (not yet inside F_V): token j adds
+  // v_j * Re sum_k e^{j theta_jk} Pn[k] to the output; the sums are formed here, where Pn is at hand.
+  float2 sp[kMaxPend];  // (head g0, head g0 + 1)
+#pragma unroll
+  for (int jp = 0; jp < kMaxPend; ++jp) sp[jp] = make_float2(0.f, 0.f);
 #pragma unroll
   for (int j = 0; j < NBT; ++j) {
     const int i = j * kFftThreads + tid;
@@ -532,9 +654,38 @@ __global__ __launch_bounds__(kFftThreads, (MULTI && NBT > 4) ? 2 : 4) void attn_
         const float w = wts[i];
         r0 = make_float2(A0[j].x * (w * iz0), -A0[j].y * (w * iz0));
         r1 = make_float2(A1[j].x * (w * iz1), -A1[j].y * (w * iz1));
+        if (np > 0) {  // block-uniform
+          float2 t = cis_poly(mulmod(kk[j], ptsh, P.M, P.Mmask), P.M);
+          const float2 step = cis_poly(kk[j], P.M);
+#pragma unroll
+          for (int jp = 0; jp < kMaxPend; ++jp) {
+            if (jp < np) {
+              sp[jp].x += t.x * r0.x - t.y * r0.y;
+              sp[jp].y += t.x * r1.x - t.y * r1.y;
+              t = cmul(t, step);
+            }
+          }
+        }
       }
       o0[i] = r0;
       if (has1) o1[i] = r1;
+    }
+  }
+  if (np > 0) {
+#pragma unroll
+    for (int jp = 0; jp < kMaxPend; ++jp) {
+      if (jp < np) {
+        const float2 tot = make_float2(wave_sum(sp[jp].x), wave_sum(sp[jp].y));
+        if ((tid & 63) == 0) pscr[tid >> 6][jp] = tot;
+      }
+    }
+    __syncthreads();
+    if (tid < np) {
+      float2 tot = make_float2(0.f, 0.f);
+      for (int w = 0; w < kFftThreads / 64; ++w) tot = cadd(tot, pscr[w][tid]);
+      float* d0 = ps + (int64_t)s_global_head(slice, P.G, g0) * kMaxPend;
+      d0[tid] = tot.x;
+      if (has1) d0[kMaxPend + tid] = tot.y;
     }
   }
   for (int e = tid; e < E; e += kFftThreads) {  // raw scores -> weights p_e / Z (same thread, same entry)
@@ -640,11 +791,11 @@ static int heads_per_pass(int G) { return G >= 8 ? 8 : (G > 2 ? 4 : G); }  // 1,
 template <bool BF16>
 static hipError_t launch_attn_t(const Params& P, const void* q, void* out, float scale, float2* qc,
                                 float2* Pn, float* pe, float* direct_scratch, bool use_fft,
-                                const StepUpdate* up, const PhaseEvents* marks, hipStream_t st) {
+                                const StepUpdate* up, int mode, const PhaseEvents* marks, hipStream_t st) {
   const int GT = heads_per_pass(P.G);
   const int passes = (P.G + GT - 1) / GT;
-  const StepUpdate u = up ? *up : StepUpdate{nullptr, nullptr, 0, 0};
-  const int kQcThreads = qc_threads(up != nullptr), kQcBins = qc_bins(up != nullptr);
+  const StepUpdate u = up ? *up : StepUpdate{nullptr, nullptr, 0, 0, 0, nullptr};
+  const int kQcThreads = qc_threads(mode != kPlain), kQcBins = qc_bins(mode != kPlain);
   const int chunks = (P.max_Bp + kQcBins - 1) / kQcBins;
   const uint64_t gridA = (uint64_t)P.n_slices * chunks * passes;
   const uint64_t gridC = (uint64_t)P.n_slices * (kHeadDim / kOutDC) * passes;
@@ -659,11 +810,16 @@ static hipError_t launch_attn_t(const Params& P, const void* q, void* out, float
     case 4: KERNEL<BF16, 4, UPD><<<dim3((uint32_t)(GRID)), dim3(THREADS), 0, st>>>(__VA_ARGS__); break;  \
     default: KERNEL<BF16, 8, UPD><<<dim3((uint32_t)(GRID)), dim3(THREADS), 0, st>>>(__VA_ARGS__); break; \
   }
-#define IWDFT_GT_SWITCH(KERNEL, GRID, THREADS, ...)                         \
-  if (up) { IWDFT_GT_SWITCH1(KERNEL, true, GRID, THREADS, __VA_ARGS__) }    \
-  else { IWDFT_GT_SWITCH1(KERNEL, false, GRID, THREADS, __VA_ARGS__) }
+#define IWDFT_GT_SWITCH(KERNEL, GRID, THREADS, ...)                                              \
+  if (mode == kUpdate1) { IWDFT_GT_SWITCH1(KERNEL, kUpdate1, GRID, THREADS, __VA_ARGS__) }       \
+  else if (mode == kUpdateN) { IWDFT_GT_SWITCH1(KERNEL, kUpdateN, GRID, THREADS, __VA_ARGS__) }  \
+  else { IWDFT_GT_SWITCH1(KERNEL, kPlain, GRID, THREADS, __VA_ARGS__) }
 
-  if (up && passes != 1) return hipErrorInvalidValue;  // the fused step needs all heads in one pass
+  if (u.np > 0 && passes != 1) return hipErrorInvalidValue;  // the fused step needs all heads in one pass
+  if (u.np > kMaxPend || (mode == kUpdate1 && u.np != 1) || (mode != kPlain && u.np < 1) ||
+      (u.np > 0 && mode == kPlain && (!use_fft || !u.ps)))
+    return hipErrorInvalidValue;
+  const int np_plain = mode == kPlain ? u.np : 0;  // pending tokens kernel B has to weigh
   hipError_t e = hipSuccess;
 #define IWDFT_MARK(I)                                            \
   if (marks && (e = hipEventRecord(marks->ev[I], st)) != hipSuccess) return e;
@@ -687,7 +843,8 @@ static hipError_t launch_attn_t(const Params& P, const void* q, void* out, float
     e = lim.ensure((const void*)attn_fft_kernel<LQ, NBT, MULTI>, (int)lds);                              \
     if (e != hipSuccess) return e;                                                                       \
     attn_fft_kernel<LQ, NBT, MULTI><<<dim3(gridB), dim3(kFftThreads), lds, st>>>(P, qc, Pn, pe, scale,   \
-                                                                                pairs);                  \
+                                                                                pairs, np_plain, u.tsh,  \
+                                                                                u.ps);                   \
   }
 #define IWDFT_FFT_NBT(LQ, MULTI)                                                                         \
   {                                                                                                      \
@@ -714,7 +871,12 @@ static hipError_t launch_attn_t(const Params& P, const void* q, void* out, float
   IWDFT_MARK(2)
 
   const int per_xcd = (int)((gridC + 7) / 8);
-  IWDFT_GT_SWITCH(attn_out_kernel, (uint64_t)per_xcd * 8, kOutThreads, P, Pn, out, pe, passes, per_xcd, (int)gridC, u)
+  if (mode == kPlain && u.np > 0) {  // deferred write-back: no append follows that could reuse cached V state
+    IWDFT_GT_SWITCH1(attn_out_kernel, kPlainStream, (uint64_t)per_xcd * 8, kOutThreads, P, Pn, out, pe, passes, per_xcd,
+                     (int)gridC, u)
+  } else {
+    IWDFT_GT_SWITCH(attn_out_kernel, (uint64_t)per_xcd * 8, kOutThreads, P, Pn, out, pe, passes, per_xcd, (int)gridC, u)
+  }
 #undef IWDFT_GT_SWITCH
 #undef IWDFT_GT_SWITCH1
   e = hipGetLastError();
@@ -728,52 +890,71 @@ hipError_t launch_attn(const Params& P, const void* q, void* out, float scale, f
                        float* pe, float* direct_scratch, bool use_fft, const PhaseEvents* marks,
                        hipStream_t st) {
   return P.kv_dtype == 1
-             ? launch_attn_t<true>(P, q, out, scale, qc, Pn, pe, direct_scratch, use_fft, nullptr, marks, st)
-             : launch_attn_t<false>(P, q, out, scale, qc, Pn, pe, direct_scratch, use_fft, nullptr, marks, st);
+             ? launch_attn_t<true>(P, q, out, scale, qc, Pn, pe, direct_scratch, use_fft, nullptr, kPlain, marks, st)
+             : launch_attn_t<false>(P, q, out, scale, qc, Pn, pe, direct_scratch, use_fft, nullptr, kPlain, marks, st);
 }
 
-// Recent window, fused step: the oldest ring token moves to the staging row (it is what the
-// coefficients absorb in this step) and the new token takes its slot, so that the attention
-// kernels already see the updated window.  grid: slice ; y: tensor; 128 threads = channels.
+// Fused step: the token the coefficients have to absorb goes to row `row` of the slice's pending rows
+// ([slice][rows][128]).  With a recent window that is the oldest ring token, whose slot the new token
+// takes, so that the attention kernels already see the updated window; without one it is the new token
+// itself.  grid: slice ; y: tensor; 128 threads = channels.
 template <bool BF16>
-__global__ __launch_bounds__(kHeadDim) void ring_swap_kernel(Params P, const void* __restrict__ tok_k,
-                                                            const void* __restrict__ tok_v, void* stage_k,
-                                                            void* stage_v, uint32_t pos) {
+__global__ __launch_bounds__(kHeadDim) void pend_push_kernel(Params P, const void* __restrict__ tok_k,
+                                                            const void* __restrict__ tok_v, void* pend_k,
+                                                            void* pend_v, int rows, int row, uint32_t ring_pos) {
   const int slice = blockIdx.x;
   const void* tok = blockIdx.y ? tok_v : tok_k;
   void* ring = blockIdx.y ? P.ringV : P.ringK;
-  void* stage = blockIdx.y ? stage_v : stage_k;
+  void* pend = blockIdx.y ? pend_v : pend_k;
   const int64_t src = (int64_t)slice * kHeadDim + threadIdx.x;
-  const int64_t slot = ((int64_t)slice * P.R + pos) * kHeadDim + threadIdx.x;
+  const int64_t dst = ((int64_t)slice * rows + row) * kHeadDim + threadIdx.x;
+  const int64_t slot = ((int64_t)slice * P.R + ring_pos) * kHeadDim + threadIdx.x;
   if constexpr (BF16) {
-    ((uint16_t*)stage)[src] = ((uint16_t*)ring)[slot];
-    ((uint16_t*)ring)[slot] = ((const uint16_t*)tok)[src];
+    uint16_t x = ((const uint16_t*)tok)[src];
+    if (P.R > 0) {
+      const uint16_t old = ((uint16_t*)ring)[slot];
+      ((uint16_t*)ring)[slot] = x;
+      x = old;
+    }
+    ((uint16_t*)pend)[dst] = x;
   } else {
-    ((float*)stage)[src] = ((float*)ring)[slot];
-    ((float*)ring)[slot] = ((const float*)tok)[src];
+    float x = ((const float*)tok)[src];
+    if (P.R > 0) {
+      const float old = ((float*)ring)[slot];
+      ((float*)ring)[slot] = x;
+      x = old;
+    }
+    ((float*)pend)[dst] = x;
   }
 }
 
-bool step_can_fuse(const Params& P) { return (P.G + heads_per_pass(P.G) - 1) / heads_per_pass(P.G) == 1; }
+bool heads_fit_one_pass(int G) { return (G + heads_per_pass(G) - 1) / heads_per_pass(G) == 1; }
+bool step_can_fuse(const Params& P) { return heads_fit_one_pass(P.G); }
 
 hipError_t launch_step(const Params& P, const void* tok_k, const void* tok_v, const void* q, void* out,
-                       float scale, float2* qc, float2* Pn, float* pe, void* stage_k, void* stage_v,
-                       float* direct_scratch, bool use_fft, uint32_t tsh, uint32_t ring_pos,
-                       const PhaseEvents* marks, hipStream_t st) {
-  StepUpdate up{tok_k, tok_v, kHeadDim, tsh};
-  if (P.R > 0) {
+                       float scale, float2* qc, float2* Pn, float* pe, void* pend_k, void* pend_v, float* ps,
+                       float* direct_scratch, bool use_fft, uint32_t tsh0, uint32_t ring_pos, int pend_before,
+                       int write_every, const PhaseEvents* marks, hipStream_t st) {
+  if (write_every < 1 || write_every > kMaxPend || pend_before < 0 || pend_before >= write_every)
+    return hipErrorInvalidValue;
+  StepUpdate up{tok_k, tok_v, kHeadDim, tsh0, pend_before + 1, ps};
+  if (P.R > 0 || write_every > 1) {
     if (P.kv_dtype == 1)
-      ring_swap_kernel<true><<<dim3((uint32_t)P.n_slices, 2), dim3(kHeadDim), 0, st>>>(P, tok_k, tok_v, stage_k, stage_v, ring_pos);
+      pend_push_kernel<true><<<dim3((uint32_t)P.n_slices, 2), dim3(kHeadDim), 0, st>>>(
+          P, tok_k, tok_v, pend_k, pend_v, write_every, pend_before, ring_pos);
     else
-      ring_swap_kernel<false><<<dim3((uint32_t)P.n_slices, 2), dim3(kHeadDim), 0, st>>>(P, tok_k, tok_v, stage_k, stage_v, ring_pos);
+      pend_push_kernel<false><<<dim3((uint32_t)P.n_slices, 2), dim3(kHeadDim), 0, st>>>(
+          P, tok_k, tok_v, pend_k, pend_v, write_every, pend_before, ring_pos);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    up.xk = stage_k;
-    up.xv = stage_v;
+    up.xk = pend_k;
+    up.xv = pend_v;
+    up.stride = (int64_t)write_every * kHeadDim;
   }
+  const int mode = up.np < write_every ? kPlain : (write_every == 1 ? kUpdate1 : kUpdateN);
   return P.kv_dtype == 1
-             ? launch_attn_t<true>(P, q, out, scale, qc, Pn, pe, direct_scratch, use_fft, &up, marks, st)
-             : launch_attn_t<false>(P, q, out, scale, qc, Pn, pe, direct_scratch, use_fft, &up, marks, st);
+             ? launch_attn_t<true>(P, q, out, scale, qc, Pn, pe, direct_scratch, use_fft, &up, mode, marks, st)
+             : launch_attn_t<false>(P, q, out, scale, qc, Pn, pe, direct_scratch, use_fft, &up, mode, marks, st);
 }
 
 }  // namespace iwdft

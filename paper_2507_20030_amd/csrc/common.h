@@ -148,14 +148,23 @@ hipError_t launch_attn(const Params& P, const void* q, void* out, float scale, f
                        float2* Pn, float* pe, float* direct_scratch, bool use_fft,
                        const PhaseEvents* marks, hipStream_t st);
 
-// One decode step = append + attention with the update fused into the attention kernels (each
-// coefficient read once and written once).  stage_k / stage_v: [slice][128] kv_dtype rows for the
-// token leaving the recent window (used when R > 0).  step_can_fuse: all query heads fit one pass.
+// One decode step = append + attention with the update fused into the attention kernels.
+// write_every = 1: every coefficient is read once and written once per step.  write_every = J > 1: the
+// coefficients are written back only on every J-th step; in between the tokens they do not hold yet
+// (pend_before of them before this call, kept in pend_k / pend_v, [slice][J][128] kv_dtype) enter the
+// attention through rank-one corrections, so every step returns the same result (up to rounding order).
+// t_shift0: slot shift of the oldest pending token (of this step's token if none is pending);
+// ps: [slice][query head][kMaxPend] floats.  step_can_fuse: all query heads fit one pass.
+constexpr int kMaxPend = 8;
+bool heads_fit_one_pass(int G);
 bool step_can_fuse(const Params& P);
 hipError_t launch_step(const Params& P, const void* tok_k, const void* tok_v, const void* q, void* out,
-                       float scale, float2* qc, float2* Pn, float* pe, void* stage_k, void* stage_v,
-                       float* direct_scratch, bool use_fft, uint32_t t_shift, uint32_t ring_pos,
-                       const PhaseEvents* marks, hipStream_t st);
+                       float scale, float2* qc, float2* Pn, float* pe, void* pend_k, void* pend_v, float* ps,
+                       float* direct_scratch, bool use_fft, uint32_t t_shift0, uint32_t ring_pos,
+                       int pend_before, int write_every, const PhaseEvents* marks, hipStream_t st);
+// The streaming update alone for one row per slice, x[slice * x_slice_stride + channel] (no ring hand-over).
+hipError_t launch_absorb(const Params& P, const void* xk, const void* xv, int64_t x_slice_stride,
+                         uint32_t t_shift, hipStream_t st);
 
 // Frequency-ablation tools (Sec. 3.2).  launch_ablate: x, out [n_slices][M][128], M = 2^8 .. 2^13, the bins
 // [lo, hi) zeroed.  select_chunks: the floor(r C + 1/2) (clamped to 1 .. C) chunks with the largest delta,

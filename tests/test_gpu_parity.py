@@ -36,9 +36,10 @@ def c128(t):
     return t.detach().to("cpu").numpy().astype(np.complex128)
 
 
-def make_cache(cfg, bins, weights=None, flags=0):
+def make_cache(cfg, bins, weights=None, flags=0, write_every=0):
     return B.Cache(cfg.n_layers, cfg.batch, cfg.n_kv_heads, cfg.n_q_heads, cfg.head_dim, cfg.torch_dtype,
-                   cfg.L, bins, weights, flags, DEV, n_sink=cfg.n_sink, n_recent=cfg.n_recent)
+                   cfg.L, bins, weights, flags, DEV, n_sink=cfg.n_sink, n_recent=cfg.n_recent,
+                   write_every=write_every)
 
 
 class SliceOracle:
@@ -130,11 +131,12 @@ def check_masks(cache, bins):
         assert got.dtype == np.int32 and np.array_equal(got, np.asarray(b, np.int32)), f"mask of layer {l}"
 
 
-def run_stream(cfg, bins, weights=None, flags=0, steps=None, slices=None, rec=(0, 64), tag="", fused=False):
+def run_stream(cfg, bins, weights=None, flags=0, steps=None, slices=None, rec=(0, 64), tag="", fused=False,
+               write_every=0):
     steps = cfg.steps if steps is None else steps
     slices = wl.sample_slices(cfg) if slices is None else slices
     K, V = wl.prefill_tensors(cfg, DEV)
-    cache = make_cache(cfg, bins, weights, flags)
+    cache = make_cache(cfg, bins, weights, flags, write_every)
     check_masks(cache, bins)
     cache.prefill(K, V)
     assert cache.T == cfg.L
@@ -361,17 +363,101 @@ def test_phase_timing_marks_calls_without_changing_results():
     b.close()
 
 
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("L,S,R,group,J", [(256, 0, 0, 2, 2), (1024, 3, 5, 3, 8), (512, 0, 4, 1, 3), (2048, 0, 0, 8, 8),
+                                           (4096, 2, 0, 4, 5), (16384, 0, 3, 4, 8), (512, 2, 3, 16, 8),
+                                           (96, 0, 0, 2, 8)])
+def test_deferred_write_back_stream(dtype, L, S, R, group, J):
+    # the coefficients are written back every J-th fused step only; every step's attention still has to
+    # match the oracle, and so do the coefficients once the deferred tokens are flushed (19 steps: several
+    # write-backs and a partial batch at the end).  group 16 and M = 96 cannot defer and run with J = 1.
+    big = L > 8192
+    cfg = small_cfg(L=L, group=group, dtype=dtype, n_bins=min(77, L // 2 + 5), n_sink=S, n_recent=R, steps=19,
+                    n_layers=1 if big else 2)
+    run_stream(cfg, random_bins(cfg, 47), rec=(3, 50), fused=True, write_every=J,
+               tag=f"defer-{dtype}-L{L}-S{S}-R{R}-G{group}-J{J}")
+
+
+def test_deferred_write_back_mixed_with_other_calls():
+    # any call other than the fused step first writes the deferred tokens back: a random mix of calls
+    # gives, step for step, what the oracle gives
+    cfg = small_cfg(L=1024, n_bins=150, group=4, dtype="bf16", n_sink=2, n_recent=3, steps=40, n_layers=1)
+    bins = random_bins(cfg, 53)
+    K, V = wl.prefill_tensors(cfg, DEV)
+    cache = make_cache(cfg, bins, write_every=8)
+    cache.prefill(K, V)
+    slices = wl.sample_slices(cfg, 4)
+    ora = SliceOracle(cfg, bins, None, K, V, slices)
+    rng = np.random.default_rng(5)
+    G = cfg.group
+    for i in range(cfg.steps):
+        tk, tv, q = wl.decode_step(cfg, i, DEV)
+        ora.append(tk, tv)
+        op = rng.integers(0, 5)
+        if op <= 2:
+            out = cache.step(tk, tv, q)
+            ref = ora.attend(q)
+            w = max(rel_l2(f64(out[l, b, h * G:(h + 1) * G]), r) for (l, b, h), r in ref.items())
+            assert w < TOL_ATTN[cfg.torch_dtype], f"mixed step {i}: {w:.3e}"
+        else:
+            cache.append(tk, tv)
+            check_attn(cfg, cache, ora, q, f"mixed append/attend {i}")
+        if op == 1:
+            check_attn(cfg, cache, ora, q, f"mixed attend after step {i}")      # same state, plain attention
+        if op == 2 and i % 3 == 0:
+            check_coeffs(cache, ora, f"mixed export {i}")
+        if op == 0 and i % 4 == 0:
+            check_reconstruct(cfg, cache, ora, 7, 40, f"mixed reconstruct {i}")
+        assert cache.T == cfg.L + i + 1
+    check_coeffs(cache, ora, "mixed end")
+    cache.close()
+
+
+def test_deferred_write_back_equals_immediate_and_checkpoints_after_flush():
+    cfg = small_cfg(L=512, n_bins=100, group=4, dtype="bf16", n_sink=3, n_recent=4, steps=13)
+    bins = random_bins(cfg, 59)
+    K, V = wl.prefill_tensors(cfg, DEV)
+    a, b = make_cache(cfg, bins), make_cache(cfg, bins, write_every=8)
+    a.prefill(K, V)
+    b.prefill(K, V)
+    steps = [wl.decode_step(cfg, i, DEV) for i in range(cfg.steps)]
+    for tk, tv, q in steps[:11]:                      # 11 steps: one write-back, three tokens deferred
+        oa, ob = a.step(tk, tv, q), b.step(tk, tv, q)
+        assert rel_l2(f64(ob), f64(oa)) < 5e-3
+    b.flush()
+    for l in range(cfg.n_layers):
+        (ka, va), (kb, vb) = a.export_coeffs(l), b.export_coeffs(l)
+        assert rel_l2(c128(kb), c128(ka)) < 1e-6 and rel_l2(c128(vb), c128(va)) < 1e-6
+    saved, T = b.state.clone(), b.T                   # complete after the flush
+    tail = [b.step(tk, tv, q).clone() for tk, tv, q in steps[11:]]
+    b.state.copy_(saved)
+    B.iwdft_set_num_tokens(b.ctx, T)
+    again = [b.step(tk, tv, q).clone() for tk, tv, q in steps[11:]]
+    assert all(torch.equal(x, y) for x, y in zip(tail, again))
+    a.close()
+    b.close()
+
+
+def test_deferred_write_back_many_wraps():
+    # more steps than M: the slot shifts of the deferred tokens wrap around inside a batch
+    cfg = small_cfg(L=256, n_bins=60, group=2, steps=530, n_layers=1, batch=1, dtype="f32")
+    run_stream(cfg, random_bins(cfg, 61), fused=True, write_every=8, tag="defer-wraps")
+
+
 def test_fused_step_cfg2_windows_full_size():
     cfg = wl.CONFIGS["cfg2w"]
     run_stream(cfg, wl.layer_bins(cfg), steps=3, fused=True, tag="cfg2w-fused")
 
 
-@pytest.mark.parametrize("prefill,fused", [("fft", True), ("fft", False), ("dense", False)])
-def test_cfg2_full_size_sampled_slices(prefill, fused):
-    # ("fft", True) is the launch configuration the benchmark times
+@pytest.mark.parametrize("prefill,fused,J,steps", [("fft", True, 8, 10), ("fft", True, 1, 3), ("fft", False, 0, 3),
+                                                   ("dense", False, 0, 3)])
+def test_cfg2_full_size_sampled_slices(prefill, fused, J, steps):
+    # ("fft", True, 8) is the launch configuration the benchmark times: FFT prefill, fused decode step,
+    # coefficients written back every 8th step (10 steps: one write-back, two tokens left deferred)
     cfg = wl.CONFIGS["cfg2"]
     flags = B.IWDFT_FLAG_FFT_PREFILL if prefill == "fft" else B.IWDFT_FLAG_DENSE_PREFILL
-    run_stream(cfg, wl.layer_bins(cfg), flags=flags, steps=3, fused=fused, tag=f"cfg2-{prefill}-fused{int(fused)}")
+    run_stream(cfg, wl.layer_bins(cfg), flags=flags, steps=steps, fused=fused, write_every=J,
+               tag=f"cfg2-{prefill}-fused{int(fused)}-J{J}")
 
 
 @pytest.mark.parametrize("L,n_bins", [(1, 1), (2, 1), (2, 2), (3, 2), (64, 1), (64, 64)])
