@@ -16,6 +16,7 @@ float64 CPU oracle timed on a bounded sample of the same workload.
 """
 import argparse
 import json
+import math
 import os
 import sys
 import time
@@ -40,6 +41,8 @@ def main():
                          "the fused iwdft_append_attn")
     ap.add_argument("--write-every", type=int, default=8,
                     help="fused decode step: write the coefficients back every this many steps (1 = every step)")
+    ap.add_argument("--group", type=int, default=None,
+                    help="query heads per KV head (default: the workload's; 1 = the pure-bandwidth case)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="only run a plain 1 GiB device copy (reference for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE)")
@@ -63,6 +66,9 @@ def main():
         return
 
     cfg = wl.CONFIGS[args.config]
+    if args.group is not None:
+        import dataclasses
+        cfg = dataclasses.replace(cfg, group=args.group)
     dsteps = cfg.steps if args.decode_steps is None else args.decode_steps
     dev = "cuda:0"
     torch.cuda.set_device(0)
@@ -270,15 +276,18 @@ def main():
         "decode_attn_us_per_step": 1e3 * att_avg,
         "append_tokens_per_s": cfg.batch / (app_avg * 1e-3),
         "kernels": {
-            "iwdft_append": {"avg_ms": app_avg, "min_ms": float(app_ms.min()), "algorithmic_GB": append_bytes / 1e9,
+            "iwdft_append": {"avg_ms": app_avg, "median_ms": float(np.median(app_ms)), "min_ms": float(app_ms.min()),
+                             "algorithmic_GB": append_bytes / 1e9,
                              "GBps": gbps(append_bytes, app_avg), "frac_hbm_peak": frac(append_bytes, app_avg)},
-            "compressed_decode_attn": {"avg_ms": att_avg, "min_ms": float(att_ms.min()),
+            "compressed_decode_attn": {"avg_ms": att_avg, "median_ms": float(np.median(att_ms)),
+                                       "min_ms": float(att_ms.min()),
                                        "algorithmic_GB": attn_bytes / 1e9,
                                        "GBps": gbps(attn_bytes, att_avg), "frac_hbm_peak": frac(attn_bytes, att_avg)},
             "iwdft_prefill": {"kind": pre_kind, "avg_ms": pre_avg,
                               "algorithmic_GB": (kv_in_bytes + 2 * coef_bytes) / 1e9,
                               "GBps": gbps(kv_in_bytes + 2 * coef_bytes, pre_avg),
-                              "dense_equivalent_TFLOPps": prefill_useful_flop / (pre_avg * 1e-3) / 1e12},
+                              "dense_equivalent_TFLOPps": prefill_useful_flop / (pre_avg * 1e-3) / 1e12,
+                              "fft_TFLOP": 5.0 * cfg.L * math.log2(cfg.L) * cfg.n_slices * cfg.head_dim / 1e12},
             "iwdft_prefill_dense": {"avg_ms": dense_ms, "useful_TFLOP": prefill_useful_flop / 1e12,
                                     "useful_TFLOPps": prefill_useful_flop / (dense_ms * 1e-3) / 1e12,
                                     "executed_TFLOPps": mfma_split * prefill_useful_flop / (dense_ms * 1e-3) / 1e12,
