@@ -459,7 +459,7 @@ __global__ __launch_bounds__(kFftThreads, (MULTI && NBT > 4) ? 2 : 4) void attn_
                                                                  float* __restrict__ ps) {
   extern __shared__ float2 smem[];
   __shared__ float2 scratch[kFftThreads / 64];
-  __shared__ float2 pscr[kFftThreads / 64][kMaxPend];
+  __shared__ float pscr[kFftThreads / 64][2 * kMaxPend];
   const int tid = threadIdx.x;
   constexpr int Q = 1 << LOGQ;
   float2* buf = smem;                 // Q samples, padded
@@ -642,9 +642,9 @@ __global__ __launch_bounds__(kFftThreads, (MULTI && NBT > 4) ? 2 : 4) void attn_
   const float iz0 = inv_M / Z.x, iz1 = has1 ? inv_M / Z.y : 0.f;
   // Pending tokens of the fused decode step (not yet inside F_V): token j adds
   // v_j * Re sum_k e^{j theta_jk} Pn[k] to the output; the sums are formed here, where Pn is at hand.
-  float2 sp[kMaxPend];  // (head g0, head g0 + 1)
+  float sp[2 * kMaxPend];  // [token][head g0, head g0 + 1]
 #pragma unroll
-  for (int jp = 0; jp < kMaxPend; ++jp) sp[jp] = make_float2(0.f, 0.f);
+  for (int v = 0; v < 2 * kMaxPend; ++v) sp[v] = 0.f;
 #pragma unroll
   for (int j = 0; j < NBT; ++j) {
     const int i = j * kFftThreads + tid;
@@ -655,13 +655,14 @@ __global__ __launch_bounds__(kFftThreads, (MULTI && NBT > 4) ? 2 : 4) void attn_
         r0 = make_float2(A0[j].x * (w * iz0), -A0[j].y * (w * iz0));
         r1 = make_float2(A1[j].x * (w * iz1), -A1[j].y * (w * iz1));
         if (np > 0) {  // block-uniform
-          float2 t = cis_poly(mulmod(kk[j], ptsh, P.M, P.Mmask), P.M);
-          const float2 step = cis_poly(kk[j], P.M);
+          // hardware sine / cosine (~1e-6 absolute): these are weights of value rows, far inside the tolerance
+          float2 t = cis_fast((kk[j] * ptsh) & (P.M - 1u), P.M);
+          const float2 step = cis_fast(kk[j], P.M);
 #pragma unroll
           for (int jp = 0; jp < kMaxPend; ++jp) {
             if (jp < np) {
-              sp[jp].x += t.x * r0.x - t.y * r0.y;
-              sp[jp].y += t.x * r1.x - t.y * r1.y;
+              sp[2 * jp] += t.x * r0.x - t.y * r0.y;
+              sp[2 * jp + 1] += t.x * r1.x - t.y * r1.y;
               t = cmul(t, step);
             }
           }
@@ -672,20 +673,15 @@ __global__ __launch_bounds__(kFftThreads, (MULTI && NBT > 4) ? 2 : 4) void attn_
     }
   }
   if (np > 0) {
-#pragma unroll
-    for (int jp = 0; jp < kMaxPend; ++jp) {
-      if (jp < np) {
-        const float2 tot = make_float2(wave_sum(sp[jp].x), wave_sum(sp[jp].y));
-        if ((tid & 63) == 0) pscr[tid >> 6][jp] = tot;
-      }
-    }
+    // 16 sums over the wave at once: afterwards lane l holds the total of entry l >> 2
+    const float tot = wave_reduce_scatter<2 * kMaxPend>(sp, tid & 63);
+    if ((tid & 3) == 0) pscr[tid >> 6][(tid & 63) >> 2] = tot;
     __syncthreads();
-    if (tid < np) {
-      float2 tot = make_float2(0.f, 0.f);
-      for (int w = 0; w < kFftThreads / 64; ++w) tot = cadd(tot, pscr[w][tid]);
-      float* d0 = ps + (int64_t)s_global_head(slice, P.G, g0) * kMaxPend;
-      d0[tid] = tot.x;
-      if (has1) d0[kMaxPend + tid] = tot.y;
+    if (tid < 2 * np) {
+      float sum = 0.f;
+      for (int w = 0; w < kFftThreads / 64; ++w) sum += pscr[w][tid];
+      const int jp = tid >> 1, head = tid & 1;
+      if (head == 0 || has1) ps[((int64_t)s_global_head(slice, P.G, g0) + head) * kMaxPend + jp] = sum;
     }
   }
   for (int e = tid; e < E; e += kFftThreads) {  // raw scores -> weights p_e / Z (same thread, same entry)

@@ -205,6 +205,8 @@ def test_bin_weights_one_sided():
     bins = [np.arange(257, dtype=np.int32) for _ in range(cfg.n_layers)]
     w = [np.where((b == 0) | (b == 256), 1.0, 2.0).astype(np.float32) for b in bins]
     st = run_stream(cfg, bins, weights=w, steps=2, tag="one-sided")
+    # the weights also scale the deferred tokens' rank-one terms: fused steps with write-back every 4th
+    run_stream(cfg, bins, weights=w, steps=6, fused=True, write_every=4, tag="one-sided-deferred")
     # with every bin of a real signal represented, reconstruction at T = M is the input itself
     K, V = wl.prefill_tensors(cfg, DEV)
     cache = make_cache(cfg, bins, w)
