@@ -16,6 +16,10 @@
 //                       inverse FFT in LDS, softmax, forward FFT, gather the kept bins -> Pn
 //      attn_direct_kernel  same result by direct O(M |B|) sums (any M; reference path)
 //   C  attn_out_kernel  streams F_V once, o[c] = Re sum_k F_V[c][k] Pn[k]           (HBM-bound)
+// The fused decode step (launch_step) runs the same three kernels with the streaming update of
+// Eq. infi-dft folded in: A and C either add the step's token(s) to every coefficient on its way through
+// and write it back, or -- deferred write-back -- leave the coefficients alone and add the exact
+// contribution of the tokens they do not hold yet (see StepUpdate).
 #include "common.h"
 #include "fft_lds.h"
 
@@ -783,7 +787,7 @@ __global__ __launch_bounds__(kDirThreads) void attn_direct_kernel(Params P, cons
 // --------------------------------------------------------------------------------------- host
 static int heads_per_pass(int G) { return G >= 8 ? 8 : (G > 2 ? 4 : G); }  // 1, 2, 4 or 8
 
-// up != nullptr: fused decode step (the token is absorbed inside kernels A and C).
+// up / mode: the fused decode step's pending tokens and what kernels A and C do with them (see StepUpdate).
 template <bool BF16>
 static hipError_t launch_attn_t(const Params& P, const void* q, void* out, float scale, float2* qc,
                                 float2* Pn, float* pe, float* direct_scratch, bool use_fft,
@@ -799,12 +803,12 @@ static hipError_t launch_attn_t(const Params& P, const void* q, void* out, float
   if (gridA > 0x7fffffffull || gridC > 0x7fffffffull || gridBd > 0x7fffffffull)
     return hipErrorInvalidConfiguration;
 
-#define IWDFT_GT_SWITCH1(KERNEL, UPD, GRID, THREADS, ...)                                                \
+#define IWDFT_GT_SWITCH1(KERNEL, MODE, GRID, THREADS, ...)                                               \
   switch (GT) {                                                                                          \
-    case 1: KERNEL<BF16, 1, UPD><<<dim3((uint32_t)(GRID)), dim3(THREADS), 0, st>>>(__VA_ARGS__); break;  \
-    case 2: KERNEL<BF16, 2, UPD><<<dim3((uint32_t)(GRID)), dim3(THREADS), 0, st>>>(__VA_ARGS__); break;  \
-    case 4: KERNEL<BF16, 4, UPD><<<dim3((uint32_t)(GRID)), dim3(THREADS), 0, st>>>(__VA_ARGS__); break;  \
-    default: KERNEL<BF16, 8, UPD><<<dim3((uint32_t)(GRID)), dim3(THREADS), 0, st>>>(__VA_ARGS__); break; \
+    case 1: KERNEL<BF16, 1, MODE><<<dim3((uint32_t)(GRID)), dim3(THREADS), 0, st>>>(__VA_ARGS__); break;  \
+    case 2: KERNEL<BF16, 2, MODE><<<dim3((uint32_t)(GRID)), dim3(THREADS), 0, st>>>(__VA_ARGS__); break;  \
+    case 4: KERNEL<BF16, 4, MODE><<<dim3((uint32_t)(GRID)), dim3(THREADS), 0, st>>>(__VA_ARGS__); break;  \
+    default: KERNEL<BF16, 8, MODE><<<dim3((uint32_t)(GRID)), dim3(THREADS), 0, st>>>(__VA_ARGS__); break; \
   }
 #define IWDFT_GT_SWITCH(KERNEL, GRID, THREADS, ...)                                              \
   if (mode == kUpdate1) { IWDFT_GT_SWITCH1(KERNEL, kUpdate1, GRID, THREADS, __VA_ARGS__) }       \
