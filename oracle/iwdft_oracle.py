@@ -41,6 +41,7 @@ __all__ = [
     "closed_form", "reconstruct", "attention", "decode_attention",
     "stream_decode", "windowed_attention", "windowed_stream_decode",
     "chunk_bounds", "ablate_chunk", "select_bins",
+    "append_shortcut", "closed_form_shortcut",
 ]
 
 
@@ -246,4 +247,28 @@ def select_bins(delta, M, r):
         keep = sorted(order[:n_c])
         b = [np.arange(e[c], e[c + 1], dtype=np.int64) for c in keep]
         out.append(np.concatenate(b).astype(np.int32) if b else np.zeros(0, np.int32))
+    return out
+
+
+def append_shortcut(S, x_new, T, bins, M):
+    """The variant of Eq. infi-dft that Sec. 4.1 mentions for long contexts, with the factor
+    (N-1)/N of the old state taken as 1:  S_{T+1}[k] = W_k ( S_T[k] + x_T / (T+1) ).
+    Not what the hot path computes (old tokens keep their weight, so weights are no longer
+    equal); kept to measure how far the shortcut drifts from the exact rule."""
+    S = np.asarray(S, dtype=np.complex128)
+    x_new = np.asarray(x_new, dtype=np.float64)
+    return W(bins, M)[:, None] * (S + x_new[None, :] / float(T + 1))
+
+
+def closed_form_shortcut(xs, M, bins):
+    """What append_shortcut reaches after T - M steps, written out: the prefill tokens keep
+    weight 1/M for ever, token n >= M enters with weight 1/(n+1):
+    S_T[k] = W_k^(T-M) S_M[k] + sum_{n=M}^{T-1} x[n] W_k^(T-n) / (n+1).   xs: [T, d]."""
+    xs = np.asarray(xs, dtype=np.float64)
+    T = xs.shape[0]
+    k = np.asarray(bins, dtype=np.int64)
+    out = np.exp(-2j * np.pi * ((k * (T - M)) % M) / float(M))[:, None] * prefill(xs[:M], bins)
+    for n in range(M, T):
+        ph = np.exp(-2j * np.pi * ((k * (T - n)) % M) / float(M))
+        out = out + ph[:, None] * xs[n][None, :] / float(n + 1)
     return out

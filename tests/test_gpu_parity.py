@@ -469,6 +469,38 @@ def test_two_runs_are_bitwise_identical(prefill):
     assert all(torch.equal(a, b) for a, b in zip(outs[0], outs[1]))
 
 
+def test_shortcut_variant_through_prescaled_tokens():
+    # Sec. 4.1's (N-1)/N -> 1 shortcut needs no kernel of its own: in the stored (un-normalised) frame it
+    # is the exact update of a token scaled by M / (T + 1), and its state is T / M times what
+    # iwdft_export_coeffs returns.  Checked against the oracle's closed form of the shortcut; the distance
+    # to the exact rule (the drift the shortcut causes) is printed.
+    from oracle import iwdft_oracle as orc
+    cfg = small_cfg(L=256, n_bins=40, group=2, dtype="f32", steps=64, n_layers=1, batch=1)
+    bins = random_bins(cfg, 71)
+    K, V = wl.prefill_tensors(cfg, DEV)
+    cache = make_cache(cfg, bins)
+    cache.prefill(K, V)
+    hist = [f64(K[0, 0, h]) for h in range(cfg.n_kv_heads)]
+    for i in range(cfg.steps):
+        tk, tv, _ = wl.decode_step(cfg, i, DEV)
+        T = cfg.L + i
+        cache.append(tk * (cfg.L / (T + 1)), tv * (cfg.L / (T + 1)))
+        hist = [np.vstack([x, f64(tk[0, 0, h])[None, :]]) for h, x in enumerate(hist)]
+    T = cfg.L + cfg.steps
+    SK, _ = cache.export_coeffs(0)
+    worst, drift = 0.0, 0.0
+    for h in range(cfg.n_kv_heads):
+        got = c128(SK[0, h]) * (T / cfg.L)
+        ref = orc.closed_form_shortcut(hist[h], cfg.L, bins[0])
+        exact = orc.closed_form(hist[h], cfg.L, bins[0])
+        worst = max(worst, rel_l2(got, ref))
+        drift = max(drift, rel_l2(ref, exact))
+    print(f"\n[shortcut] rel-L2 vs oracle {worst:.2e}; drift of the shortcut from the exact rule after "
+          f"{cfg.steps} appends on M = {cfg.L}: {drift:.2e}", flush=True)
+    assert worst < 1e-4      # the scaled tokens are rounded to fp32 once more: still far inside the bar
+    cache.close()
+
+
 def test_deferred_write_back_many_wraps():
     # more steps than M: the slot shifts of the deferred tokens wrap around inside a batch
     cfg = small_cfg(L=256, n_bins=60, group=2, steps=530, n_layers=1, batch=1, dtype="f32")

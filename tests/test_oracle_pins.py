@@ -440,3 +440,43 @@ def test_select_bins_uneven_chunks_and_count_rule():
     top = int(np.argmax(delta[0]))
     one = orc.select_bins(delta, M, 0.0)[0]   # never fewer than one chunk
     assert list(one) == list(range((top * M) // C, ((top + 1) * M) // C))
+
+
+# ------------------------------------------------------------ the (N-1)/N -> 1 shortcut (Sec. 4.1)
+def test_shortcut_recursion_matches_its_closed_form_and_token_weights():
+    M, d, extra = 16, 3, 37
+    r = rng(60)
+    xs = r.normal(size=(M + extra, d))
+    bins = [0, 1, 5, 9, 15]
+    S = orc.prefill(xs[:M], bins)
+    for t in range(extra):
+        S = orc.append_shortcut(S, xs[M + t], M + t, bins, M)
+    np.testing.assert_allclose(S, orc.closed_form_shortcut(xs, M, bins), atol=1e-13)
+    # DC bin (W_0 = 1): mean of the prefill plus sum of x_n / (n + 1) -- old tokens are never scaled down
+    dc = xs[:M].mean(axis=0) + sum(xs[n] / (n + 1) for n in range(M, M + extra))
+    np.testing.assert_allclose(S[0], dc, atol=1e-13)
+    # a unit impulse appended at step n0 and nothing else: weight 1/(n0+1), slot T - n0
+    imp = np.zeros((M + extra, 1))
+    n0 = M + 4
+    imp[n0] = 1.0
+    T = M + extra
+    k = np.array(bins)
+    ref = np.exp(-2j * np.pi * k * (T - n0) / M)[:, None] / (n0 + 1)
+    np.testing.assert_allclose(orc.closed_form_shortcut(imp, M, bins), ref, atol=1e-14)
+
+
+def test_shortcut_differs_from_the_exact_rule_by_the_missing_decay():
+    # exact rule: every token weighs 1/T.  Shortcut: prefill tokens 1/M, token n 1/(n+1).  With only
+    # prefill tokens non-zero the two states differ exactly by the factor T/M.
+    M, d, extra = 8, 2, 5
+    xs = np.vstack([rng(61).normal(size=(M, d)), np.zeros((extra, d))])
+    bins = np.arange(M)
+    T = M + extra
+    np.testing.assert_allclose(orc.closed_form_shortcut(xs, M, bins), orc.closed_form(xs, M, bins) * T / M,
+                               atol=1e-13)
+    # in general the relative distance grows with the number of appended tokens
+    r = rng(62)
+    xs = r.normal(size=(64 + 64, 4))
+    d1 = [np.linalg.norm(orc.closed_form_shortcut(xs[:T], 64, bins) - orc.closed_form(xs[:T], 64, bins)) /
+          np.linalg.norm(orc.closed_form(xs[:T], 64, bins)) for T in (65, 80, 128)]
+    assert d1[0] < d1[1] < d1[2] and d1[0] < 0.05 and d1[2] > 0.3
