@@ -480,3 +480,33 @@ def test_shortcut_differs_from_the_exact_rule_by_the_missing_decay():
     d1 = [np.linalg.norm(orc.closed_form_shortcut(xs[:T], 64, bins) - orc.closed_form(xs[:T], 64, bins)) /
           np.linalg.norm(orc.closed_form(xs[:T], 64, bins)) for T in (65, 80, 128)]
     assert d1[0] < d1[1] < d1[2] and d1[0] < 0.05 and d1[2] > 0.3
+
+
+# ------------------------------------------------------------ why the coefficients stay fp32
+def test_half_precision_coefficient_storage_misses_the_bar():
+    # A study, not a pin: the streaming update with the accumulator rounded to fp16 after every
+    # token (what half-precision coefficient storage would do) against the float64 stream.  The update adds
+    # a term of size |x| to an accumulator of size |x| sqrt(T); fp16 carries 11 bits, so the added term
+    # loses most of its own bits and the rel-L2 error ends orders of magnitude above the 1e-4 target.
+    M, d, steps = 1024, 8, 256
+    r = rng(70)
+    xs = r.normal(size=(M + steps, d))
+    bins = np.arange(0, 256)
+    k = bins[:, None].astype(np.float64)
+    U = np.fft.fft(xs[:M], axis=0)[bins]                     # un-normalised state, as stored
+    Uh = (U.real.astype(np.float16) + 1j * U.imag.astype(np.float16)).astype(np.complex128)
+    err0 = np.linalg.norm(Uh - U) / np.linalg.norm(U)        # storage rounding alone
+    for t in range(steps):
+        tw = np.exp(2j * np.pi * ((bins * t) % M) / M)[:, None]   # fixed-frame update: F += x e^{+j 2 pi k (T-M)/M}
+        U = U + tw * xs[M + t][None, :]
+        Uh = Uh + tw * xs[M + t][None, :]
+        Uh = (Uh.real.astype(np.float16) + 1j * Uh.imag.astype(np.float16)).astype(np.complex128)
+    err = np.linalg.norm(Uh - U) / np.linalg.norm(U)
+    assert 1e-4 < err0 < 1e-3          # one rounding: ~3e-4, already above the target
+    assert err > 2e-3                  # and it grows with every token
+    # fp32 accumulators under the same schedule stay near 1e-7
+    U32 = np.fft.fft(xs[:M], axis=0)[bins].astype(np.complex64)
+    for t in range(steps):
+        tw = np.exp(2j * np.pi * ((bins * t) % M) / M)[:, None].astype(np.complex64)
+        U32 = (U32 + tw * xs[M + t][None, :].astype(np.float32)).astype(np.complex64)
+    assert np.linalg.norm(U32 - U) / np.linalg.norm(U) < 1e-6
