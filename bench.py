@@ -39,7 +39,7 @@ def main():
     ap.add_argument("--split", action="store_true",
                     help="decode with the two separate calls (iwdft_append, compressed_decode_attn) instead of "
                          "the fused iwdft_append_attn")
-    ap.add_argument("--write-every", type=int, default=8,
+    ap.add_argument("--write-every", type=int, default=16,
                     help="fused decode step: write the coefficients back every this many steps (1 = every step)")
     ap.add_argument("--group", type=int, default=None,
                     help="query heads per KV head (default: the workload's; 1 = the pure-bandwidth case)")
@@ -102,8 +102,8 @@ def main():
 
     # Event records between the kernels cost a few us each, so only a sample of the decode steps of
     # the timed region carries them.  In every group of 8 steps: step 2 has the library's phase marks
-    # around its three attention kernels, step 4 has events around the call(s), and step 7 -- the step
-    # that writes the coefficients back when write_every = 8 -- has events around the call as well.
+    # around its three attention kernels, steps 4 and 7 have events around the call(s); with write_every =
+    # 8 or 16 the steps that write the coefficients back are among the latter.
     # HIP events are created at their first record, which costs far more than a record: all of them
     # are recorded once before the timed region.
     def mk(n):

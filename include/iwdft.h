@@ -95,7 +95,7 @@ typedef struct {
   int32_t n_recent;           /* R >= 0: the R newest tokens kept exact (recent window);
                                  S + R <= 1024                                         */
   uint32_t write_every;       /* J: iwdft_append_attn writes the coefficients back on every J-th call only
-                                 (0 or 1: on every call; at most 8); see iwdft_append_attn         */
+                                 (0 or 1: on every call; at most 16); see iwdft_append_attn         */
 } iwdft_desc;
 
 /* Sizes of the two caller-provided device buffers for this descriptor. */
@@ -151,7 +151,7 @@ int compressed_decode_attn(iwdft_ctx* ctx, const void* d_q, void* d_out, float s
  * read once and written once per step instead of read twice and written once.  Same arguments,
  * same result (up to rounding order) and same errors as the two calls in sequence.  T -> T+1.
  *
- * desc.write_every = J > 1 defers the write-back: the step's token (the one leaving the recent window
+ * desc.write_every = J > 1 (J <= 16) defers the write-back: the step's token (the one leaving the recent window
  * when R > 0) is kept in the workspace, and until J of them have gathered the coefficients are only
  * read -- the tokens they do not hold yet enter scores and output through the exact rank-one terms
  * F + x e^{j theta} contributes -- so every call still returns the attention over all T tokens, and the

@@ -185,12 +185,18 @@ __global__ __launch_bounds__(qc_threads(MODE != kPlain)) void attn_qc_kernel(Par
   const bool live = i0 < L.nb;
   v4f tw = (v4f)(0.f);
   if (UPD || up.np > 0) tw = lane_twiddles(P, L, i0, up.tsh);
-  v4f twn[MODE == kUpdateN ? kMaxPend : 1];  // kUpdateN: twiddle of every pending token
+  // kUpdateN: twiddles of the first kTwGroup pending tokens; the later groups are these times w^(8 g)
+  constexpr int kTwGroup = 8;
+  static_assert(kMaxPend % kTwGroup == 0, "pending tokens are handled in groups");
+  v4f twn[MODE == kUpdateN ? kTwGroup : 1];
+  v4f w8 = (v4f)(0.f);
   if constexpr (MODE == kUpdateN) {
     const v4f w = lane_twiddles(P, L, i0, 1u);  // one slot further per token
     twn[0] = tw;
 #pragma unroll
-    for (int j = 1; j < kMaxPend; ++j) twn[j] = cmul2(twn[j - 1], w);
+    for (int j = 1; j < kTwGroup; ++j) twn[j] = cmul2(twn[j - 1], w);
+    const v4f w2 = cmul2(w, w), w4 = cmul2(w2, w2);
+    w8 = cmul2(w4, w4);
   }
   v4f acc[GT];
 #pragma unroll
@@ -223,11 +229,20 @@ __global__ __launch_bounds__(qc_threads(MODE != kPlain)) void attn_qc_kernel(Par
       }
     }
     if constexpr (MODE == kUpdateN) {
+      v4f shift = (v4f)(0.f);  // w^(8 g) of the current group of 8 tokens
+      shift.x = shift.z = 1.f;
 #pragma unroll
-      for (int j = 0; j < kMaxPend; ++j) {
-        if (j < up.np) {
+      for (int g8 = 0; g8 < kMaxPend; g8 += kTwGroup) {
+        if (g8 < up.np) {
 #pragma unroll
-          for (int u = 0; u < U; ++u) f[u] += xs[j][d + u] * twn[j];
+          for (int j = 0; j < kTwGroup; ++j) {
+            if (g8 + j < up.np) {
+              const v4f t = g8 ? cmul2(twn[j], shift) : twn[j];
+#pragma unroll
+              for (int u = 0; u < U; ++u) f[u] += xs[g8 + j][d + u] * t;
+            }
+          }
+          shift = cmul2(shift, w8);
         }
       }
 #pragma unroll
@@ -677,9 +692,10 @@ __global__ __launch_bounds__(kFftThreads, (MULTI && NBT > 4) ? 2 : 4) void attn_
     }
   }
   if (np > 0) {
-    // 16 sums over the wave at once: afterwards lane l holds the total of entry l >> 2
+    // all 2 * kMaxPend sums over the wave at once: afterwards lane l holds the total of entry l / rep
     const float tot = wave_reduce_scatter<2 * kMaxPend>(sp, tid & 63);
-    if ((tid & 3) == 0) pscr[tid >> 6][(tid & 63) >> 2] = tot;
+    constexpr int rep = 64 / (2 * kMaxPend);  // lanes that end up with the same total
+    if ((tid & 63) % rep == 0) pscr[tid >> 6][(tid & 63) / rep] = tot;
     __syncthreads();
     if (tid < 2 * np) {
       float sum = 0.f;

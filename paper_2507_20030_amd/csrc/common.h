@@ -155,7 +155,7 @@ hipError_t launch_attn(const Params& P, const void* q, void* out, float scale, f
 // attention through rank-one corrections, so every step returns the same result (up to rounding order).
 // t_shift0: slot shift of the oldest pending token (of this step's token if none is pending);
 // ps: [slice][query head][kMaxPend] floats.  step_can_fuse: all query heads fit one pass.
-constexpr int kMaxPend = 8;
+constexpr int kMaxPend = 16;
 bool heads_fit_one_pass(int G);
 bool step_can_fuse(const Params& P);
 hipError_t launch_step(const Params& P, const void* tok_k, const void* tok_v, const void* q, void* out,

@@ -50,7 +50,7 @@ def test_query_bytes_accounts_for_padded_rows():
     (dict(M=0), B.IWDFT_ERR_ARG),
     (dict(M=(1 << 30) + 1), B.IWDFT_ERR_ARG),
     (dict(flags=8), B.IWDFT_ERR_ARG),
-    (dict(write_every=9), B.IWDFT_ERR_ARG),
+    (dict(write_every=17), B.IWDFT_ERR_ARG),
     (dict(flags=B.IWDFT_FLAG_DENSE_PREFILL | B.IWDFT_FLAG_FFT_PREFILL), B.IWDFT_ERR_ARG),
     (dict(flags=B.IWDFT_FLAG_FFT_PREFILL), B.IWDFT_ERR_UNSUPPORTED),   # M = 64: below the FFT's smallest length
     (dict(flags=B.IWDFT_FLAG_FFT_PREFILL, M=768), B.IWDFT_ERR_UNSUPPORTED),  # not a power of two
@@ -96,8 +96,8 @@ def test_workspace_holds_the_deferred_tokens():
     bins = [np.arange(40), np.arange(40)]
     ws1 = B.iwdft_query_bytes(desc(M=1024, bins=bins))[1]
     ws8 = B.iwdft_query_bytes(desc(M=1024, bins=bins, write_every=8))[1]
-    # 8 rows of 128 bf16 for K and for V per slice, and 8 floats per (slice, query head)
-    assert ws8 - ws1 >= 2 * (4 * 8 * 128 * 2) + 4 * 2 * 8 * 4
+    # 8 rows of 128 bf16 for K and for V per slice, and 16 floats per (slice, query head)
+    assert ws8 - ws1 >= 2 * (4 * 8 * 128 * 2) + 4 * 2 * 16 * 4
     # M = 64 has no FFT attention path, so nothing is deferred and nothing is reserved
     assert B.iwdft_query_bytes(desc(write_every=8))[1] == B.iwdft_query_bytes(desc())[1]
 

@@ -368,13 +368,15 @@ def test_phase_timing_marks_calls_without_changing_results():
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
 @pytest.mark.parametrize("L,S,R,group,J", [(256, 0, 0, 2, 2), (1024, 3, 5, 3, 8), (512, 0, 4, 1, 3), (2048, 0, 0, 8, 8),
                                            (4096, 2, 0, 4, 5), (16384, 0, 3, 4, 8), (512, 2, 3, 16, 8),
-                                           (96, 0, 0, 2, 8)])
+                                           (96, 0, 0, 2, 8), (1024, 2, 3, 4, 16), (8192, 0, 0, 2, 13),
+                                           (32768, 0, 2, 4, 16)])
 def test_deferred_write_back_stream(dtype, L, S, R, group, J):
     # the coefficients are written back every J-th fused step only; every step's attention still has to
     # match the oracle, and so do the coefficients once the deferred tokens are flushed (19 steps: several
     # write-backs and a partial batch at the end).  group 16 and M = 96 cannot defer and run with J = 1.
     big = L > 8192
-    cfg = small_cfg(L=L, group=group, dtype=dtype, n_bins=min(77, L // 2 + 5), n_sink=S, n_recent=R, steps=19,
+    cfg = small_cfg(L=L, group=group, dtype=dtype, n_bins=min(77, L // 2 + 5), n_sink=S, n_recent=R,
+                    steps=19 if J <= 8 else 37,
                     n_layers=1 if big else 2)
     run_stream(cfg, random_bins(cfg, 47), rec=(3, 50), fused=True, write_every=J,
                tag=f"defer-{dtype}-L{L}-S{S}-R{R}-G{group}-J{J}")
@@ -512,11 +514,12 @@ def test_fused_step_cfg2_windows_full_size():
     run_stream(cfg, wl.layer_bins(cfg), steps=3, fused=True, tag="cfg2w-fused")
 
 
-@pytest.mark.parametrize("prefill,fused,J,steps", [("fft", True, 8, 10), ("fft", True, 1, 3), ("fft", False, 0, 3),
+@pytest.mark.parametrize("prefill,fused,J,steps", [("fft", True, 16, 18), ("fft", True, 8, 10), ("fft", True, 1, 3),
+                                                   ("fft", False, 0, 3),
                                                    ("dense", False, 0, 3)])
 def test_cfg2_full_size_sampled_slices(prefill, fused, J, steps):
-    # ("fft", True, 8) is the launch configuration the benchmark times: FFT prefill, fused decode step,
-    # coefficients written back every 8th step (10 steps: one write-back, two tokens left deferred)
+    # ("fft", True, 16) is the launch configuration the benchmark times: FFT prefill, fused decode step,
+    # coefficients written back every 16th step (18 steps: one write-back, two tokens left deferred)
     cfg = wl.CONFIGS["cfg2"]
     flags = B.IWDFT_FLAG_FFT_PREFILL if prefill == "fft" else B.IWDFT_FLAG_DENSE_PREFILL
     run_stream(cfg, wl.layer_bins(cfg), flags=flags, steps=steps, fused=fused, write_every=J,
