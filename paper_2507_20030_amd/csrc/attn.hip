@@ -77,7 +77,32 @@ struct StepUpdate {
   uint32_t tsh;
   int np;
   float* ps;  // kPlain with np > 0: [slice][query head][kMaxPend], Re sum_k e^{j theta_jk} Pn[k] (from kernel B)
+  // Non-null: the newest pending token (row np - 1) is not in the pending rows yet but still in the
+  // caller's token tensors ([slice][128]); the kernels read it there, and in kPlain mode kernel A stores
+  // its K row and kernel C its V row into the pending rows for the steps to come.
+  const void* nk;
+  const void* nv;
 };
+
+// Element `c` of pending row j of a slice (K: value = false, V: value = true).
+template <bool BF16>
+__device__ __forceinline__ float pend_elem(const StepUpdate& up, bool value, int slice, int j, int c) {
+  const void* fresh = value ? up.nv : up.nk;
+  if (fresh && j == up.np - 1) return load_kv<BF16>(fresh, (int64_t)slice * kHeadDim + c);
+  return load_kv<BF16>(value ? up.xv : up.xk, (int64_t)slice * up.stride + j * kHeadDim + c);
+}
+// Keeps the newest token for later steps: pending row np - 1, channels [c0, c0 + n), one per thread.
+template <bool BF16>
+__device__ __forceinline__ void pend_keep(const StepUpdate& up, bool value, int slice, int c0, int n) {
+  const void* fresh = value ? up.nv : up.nk;
+  if (!fresh || (int)threadIdx.x >= n) return;
+  const int c = c0 + threadIdx.x;
+  const int64_t src = (int64_t)slice * kHeadDim + c;
+  const int64_t dst = (int64_t)slice * up.stride + (int64_t)(up.np - 1) * kHeadDim + c;
+  void* rows = const_cast<void*>(value ? up.xv : up.xk);
+  if constexpr (BF16) ((uint16_t*)rows)[dst] = ((const uint16_t*)fresh)[src];
+  else ((float*)rows)[dst] = ((const float*)fresh)[src];
+}
 
 // (a.xy, a.zw) * (b.xy, b.zw): two complex products side by side.
 __device__ __forceinline__ v4f cmul2(v4f a, v4f b) {
@@ -138,7 +163,7 @@ __global__ __launch_bounds__(qc_threads(MODE != kPlain)) void attn_qc_kernel(Par
   __syncthreads();
   if constexpr (MODE == kUpdateN) {
     for (int e = threadIdx.x; e < up.np * kHeadDim; e += kQcThreads)
-      xs[e / kHeadDim][e % kHeadDim] = load_kv<BF16>(up.xk, (int64_t)slice * up.stride + e);
+      xs[e / kHeadDim][e % kHeadDim] = pend_elem<BF16>(up, false, slice, e / kHeadDim, e % kHeadDim);
     __syncthreads();
   }
   if constexpr (MODE == kPlain) {
@@ -147,9 +172,10 @@ __global__ __launch_bounds__(qc_threads(MODE != kPlain)) void attn_qc_kernel(Par
         const int j = idx / GT, g = idx % GT;
         float dot = 0.f;
         for (int c = 0; c < kHeadDim; ++c)
-          dot += qs[g][c] * load_kv<BF16>(up.xk, (int64_t)slice * up.stride + j * kHeadDim + c);
+          dot += qs[g][c] * pend_elem<BF16>(up, false, slice, j, c);
         dq[j][g] = dot;
       }
+      if (chunk == 0 && pass == 0) pend_keep<BF16>(up, false, slice, 0, kHeadDim);
       __syncthreads();
     }
   }
@@ -341,7 +367,7 @@ __global__ __launch_bounds__(kOutThreads) void attn_out_kernel(Params P, const f
   if constexpr (MODE == kUpdateN) {
     for (int e = threadIdx.x; e < up.np * kOutDC; e += kOutThreads)
       xs[e / kOutDC][e % kOutDC] =
-          load_kv<BF16>(up.xv, (int64_t)slice * up.stride + (e / kOutDC) * kHeadDim + d0 + (e % kOutDC));
+          pend_elem<BF16>(up, true, slice, e / kOutDC, d0 + (e % kOutDC));
     __syncthreads();
   }
 
@@ -423,10 +449,13 @@ __global__ __launch_bounds__(kOutThreads) void attn_out_kernel(Params P, const f
       if constexpr (PLAIN) {
         const float* sj = up.ps + ((int64_t)slice * P.G + g0 + g) * kMaxPend;
         for (int j = 0; j < up.np; ++j)  // pending tokens' share of the V coefficients
-          tot += sj[j] * load_kv<BF16>(up.xv, (int64_t)slice * up.stride + j * kHeadDim + d0 + dd);
+          tot += sj[j] * pend_elem<BF16>(up, true, slice, j, d0 + dd);
       }
       store_kv<BF16>(out, ((int64_t)slice * P.G + g0 + g) * kHeadDim + d0 + dd, tot);
     }
+  }
+  if constexpr (PLAIN) {
+    if (up.np > 0 && pass == 0) pend_keep<BF16>(up, true, slice, d0, kOutDC);  // this block's 16 channels
   }
 }
 
@@ -810,7 +839,7 @@ static hipError_t launch_attn_t(const Params& P, const void* q, void* out, float
                                 const StepUpdate* up, int mode, const PhaseEvents* marks, hipStream_t st) {
   const int GT = heads_per_pass(P.G);
   const int passes = (P.G + GT - 1) / GT;
-  const StepUpdate u = up ? *up : StepUpdate{nullptr, nullptr, 0, 0, 0, nullptr};
+  const StepUpdate u = up ? *up : StepUpdate{nullptr, nullptr, 0, 0, 0, nullptr, nullptr, nullptr};
   const int kQcThreads = qc_threads(mode != kPlain), kQcBins = qc_bins(mode != kPlain);
   const int chunks = (P.max_Bp + kQcBins - 1) / kQcBins;
   const uint64_t gridA = (uint64_t)P.n_slices * chunks * passes;
@@ -910,10 +939,9 @@ hipError_t launch_attn(const Params& P, const void* q, void* out, float scale, f
              : launch_attn_t<false>(P, q, out, scale, qc, Pn, pe, direct_scratch, use_fft, nullptr, kPlain, marks, st);
 }
 
-// Fused step: the token the coefficients have to absorb goes to row `row` of the slice's pending rows
-// ([slice][rows][128]).  With a recent window that is the oldest ring token, whose slot the new token
-// takes, so that the attention kernels already see the updated window; without one it is the new token
-// itself.  grid: slice ; y: tensor; 128 threads = channels.
+// Fused step with a recent window: the oldest ring token, which the coefficients have to absorb, goes to
+// row `row` of the slice's pending rows ([slice][rows][128]) and the new token takes its slot, so that the
+// attention kernels already see the updated window.  grid: slice ; y: tensor; 128 threads = channels.
 template <bool BF16>
 __global__ __launch_bounds__(kHeadDim) void pend_push_kernel(Params P, const void* __restrict__ tok_k,
                                                             const void* __restrict__ tok_v, void* pend_k,
@@ -953,8 +981,8 @@ hipError_t launch_step(const Params& P, const void* tok_k, const void* tok_v, co
                        int write_every, const PhaseEvents* marks, hipStream_t st) {
   if (write_every < 1 || write_every > kMaxPend || pend_before < 0 || pend_before >= write_every)
     return hipErrorInvalidValue;
-  StepUpdate up{tok_k, tok_v, kHeadDim, tsh0, pend_before + 1, ps};
-  if (P.R > 0 || write_every > 1) {
+  StepUpdate up{tok_k, tok_v, kHeadDim, tsh0, pend_before + 1, ps, nullptr, nullptr};
+  if (P.R > 0) {  // recent window: the ring hands its oldest token over before the attention kernels run
     if (P.kv_dtype == 1)
       pend_push_kernel<true><<<dim3((uint32_t)P.n_slices, 2), dim3(kHeadDim), 0, st>>>(
           P, tok_k, tok_v, pend_k, pend_v, write_every, pend_before, ring_pos);
@@ -966,6 +994,12 @@ hipError_t launch_step(const Params& P, const void* tok_k, const void* tok_v, co
     up.xk = pend_k;
     up.xv = pend_v;
     up.stride = (int64_t)write_every * kHeadDim;
+  } else if (write_every > 1) {  // the kernels take the new token from the caller and keep it themselves
+    up.xk = pend_k;
+    up.xv = pend_v;
+    up.stride = (int64_t)write_every * kHeadDim;
+    up.nk = tok_k;
+    up.nv = tok_v;
   }
   const int mode = up.np < write_every ? kPlain : (write_every == 1 ? kUpdate1 : kUpdateN);
   return P.kv_dtype == 1
