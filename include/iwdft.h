@@ -70,7 +70,7 @@ enum {
                                        M = 2^m >= 256 and <= 4096 kept bins per layer,
                                        else IWDFT_ERR_UNSUPPORTED.  With neither flag
                                        the library picks: FFT when it applies and some
-                                       layer keeps >= 256 bins                     */
+                                       layer keeps >= 384 bins                     */
 };
 
 typedef struct {

@@ -45,7 +45,7 @@ struct Plan {  // byte offsets inside the two caller buffers, derived from a des
 
 // Largest problem the FFT attention kernel keeps in registers / LDS.
 constexpr int kFftMaxBins = 4096;
-constexpr int kFftPrefillMinBins = 256;  // fewer kept bins per layer: the dense contraction is faster
+constexpr int kFftPrefillMinBins = 384;  // fewer kept bins per layer: the dense contraction is faster
 constexpr int kMaxExact = 1024;  // most sink + recent tokens (their scores sit in LDS)
 constexpr uint32_t kFftMinM = 256;
 constexpr int64_t kFftMaxQ = 8192;  // longest transform the FFT attention kernel holds in LDS
@@ -122,7 +122,7 @@ int make_plan(const iwdft_desc* d, Plan* pl) {
   pl->use_fft = pow2 && (uint64_t)d->M >= kFftMinM && pl->max_nb <= kFftMaxBins &&
                 !(d->flags & IWDFT_FLAG_DIRECT_SYNTHESIS);
   // Prefill: the FFT costs the same whatever the number of kept bins, the dense contraction grows
-  // with it; measured break-even on MI355X is near 256 kept bins per layer.
+  // with it; measured break-even on MI355X: about 300 kept bins per layer at M = 8192, 430 at M = 131072.
   const bool fft_pf_ok = pow2 && (uint64_t)d->M >= kFftMinM && pl->max_nb <= kFftMaxBins;
   if (d->flags & IWDFT_FLAG_FFT_PREFILL) {
     if (!fft_pf_ok)
