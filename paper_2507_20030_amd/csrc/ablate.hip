@@ -13,28 +13,6 @@ namespace iwdft {
 namespace {
 constexpr int kAbPairs = kHeadDim / 2;
 
-template <int LOGQ>
-__device__ __forceinline__ int digit_pos(int a) {  // LDS position <-> sample index of the DIT / DIF order
-  int p = 0;
-#pragma unroll
-  for (int t = 0; t < (LOGQ >> 1); ++t) p |= ((a >> (2 * t)) & 3) << (LOGQ - 2 * t - 2);
-  return p;
-}
-
-template <bool BF16>
-__device__ __forceinline__ float2 load2(const char* row) {
-  if constexpr (BF16) {
-    const uint32_t u = *(const uint32_t*)row;
-    return make_float2(__uint_as_float(u << 16), __uint_as_float(u & 0xffff0000u));
-  } else {
-    return *(const float2*)row;
-  }
-}
-template <bool BF16>
-__device__ __forceinline__ void store2(char* row, float2 v) {
-  if constexpr (BF16) *(uint32_t*)row = (uint32_t)f32_to_bf16(v.x) | ((uint32_t)f32_to_bf16(v.y) << 16);
-  else *(float2*)row = v;
-}
 }  // namespace
 
 // One workgroup = two adjacent channels of one slice, packed as one complex signal: forward transform,
@@ -68,8 +46,8 @@ __global__ __launch_bounds__(kFftThreads, 4) void ablate_kernel(const char* __re
     for (int it = 0; it < IT; ++it) {
       const int a = it * kFftThreads + tid;
       if (H % kFftThreads == 0 || a < H) {
-        za[it] = load2<BF16>(X + (int64_t)a * kRow);
-        if (LOGQ & 1) zc[it] = load2<BF16>(X + (int64_t)(a + H) * kRow);
+        za[it] = load_pair<BF16>(X + (int64_t)a * kRow);
+        if (LOGQ & 1) zc[it] = load_pair<BF16>(X + (int64_t)(a + H) * kRow);
       }
     }
 #pragma unroll
@@ -104,10 +82,10 @@ __global__ __launch_bounds__(kFftThreads, 4) void ablate_kernel(const char* __re
       const int p = digit_pos<LOGQ>(a);
       if (LOGQ & 1) {
         const float2 u = buf[pad(p)], w = buf[pad(p + 1)];
-        store2<BF16>(Y + (int64_t)a * kRow, cadd(u, w));
-        store2<BF16>(Y + (int64_t)(a + H) * kRow, csub(u, w));
+        store_pair<BF16>(Y + (int64_t)a * kRow, cadd(u, w));
+        store_pair<BF16>(Y + (int64_t)(a + H) * kRow, csub(u, w));
       } else {
-        store2<BF16>(Y + (int64_t)a * kRow, buf[pad(p)]);
+        store_pair<BF16>(Y + (int64_t)a * kRow, buf[pad(p)]);
       }
     }
   }

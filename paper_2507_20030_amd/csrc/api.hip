@@ -486,7 +486,7 @@ int iwdft_reconstruct(iwdft_ctx* ctx, int32_t layer, int64_t a0, int64_t n_slots
   if (n_slots == 0 || (!d_Kt && !d_Vt)) return IWDFT_OK;
   if ((rc = flush_pending(ctx, (hipStream_t)hip_stream)) != IWDFT_OK) return rc;
   return launched(launch_reconstruct(ctx->P, layer, (uint32_t)a0, (uint32_t)n_slots, d_Kt, d_Vt,
-                                     t_shift(ctx), (hipStream_t)hip_stream),
+                                     t_shift(ctx), ctx->plan.use_fft, (hipStream_t)hip_stream),
                   "reconstruct launch");
 }
 

@@ -134,8 +134,9 @@ hipError_t launch_append(const Params& P, const void* tok_k, const void* tok_v, 
                          uint32_t ring_pos, hipStream_t st);
 hipError_t launch_export(const Params& P, int layer, float* SK, float* SV, uint32_t t_shift,
                          float inv_T, hipStream_t st);
+// use_fft: the fold schedule (Params::fold) is valid, so long slot ranges may go through inverse FFTs.
 hipError_t launch_reconstruct(const Params& P, int layer, uint32_t a0, uint32_t n_slots, void* Kt,
-                              void* Vt, uint32_t t_shift, hipStream_t st);
+                              void* Vt, uint32_t t_shift, bool use_fft, hipStream_t st);
 // Optional timing marks of the three attention phases: ev[0] before A, ev[1] after A (q against
 // the K coefficients), ev[2] after B (softmax through the transforms), ev[3] after C (output from
 // the V coefficients).

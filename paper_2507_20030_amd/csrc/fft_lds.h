@@ -163,4 +163,32 @@ __device__ __forceinline__ void fft_dit(float2* buf, const float2* tab, int tid)
   }
 }
 
+// LDS position, in the digit-reversed order that fft_dit consumes and ifft_dif produces, of sample a (for
+// odd LOGQ: a < Q/2; its partner a + Q/2 sits right behind it and the pair still needs / has had the
+// radix-2 stage applied by the caller).
+template <int LOGQ>
+__device__ __forceinline__ int digit_pos(int a) {
+  int p = 0;
+#pragma unroll
+  for (int t = 0; t < (LOGQ >> 1); ++t) p |= ((a >> (2 * t)) & 3) << (LOGQ - 2 * t - 2);
+  return p;
+}
+
+// Two adjacent channels of one token row as a complex number (load), and back (store, bf16 rounded to
+// nearest even).
+template <bool BF16>
+__device__ __forceinline__ float2 load_pair(const char* row) {
+  if constexpr (BF16) {
+    const uint32_t u = *(const uint32_t*)row;
+    return make_float2(__uint_as_float(u << 16), __uint_as_float(u & 0xffff0000u));
+  } else {
+    return *(const float2*)row;
+  }
+}
+template <bool BF16>
+__device__ __forceinline__ void store_pair(char* row, float2 v) {
+  if constexpr (BF16) *(uint32_t*)row = (uint32_t)f32_to_bf16(v.x) | ((uint32_t)f32_to_bf16(v.y) << 16);
+  else *(float2*)row = v;
+}
+
 }  // namespace iwdft

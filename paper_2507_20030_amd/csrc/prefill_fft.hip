@@ -19,27 +19,6 @@ namespace iwdft {
 
 constexpr int kPairs = kHeadDim / 2;  // channel pairs = workgroups per (slice, tensor)
 
-// LDS position, in the digit-reversed order fft_dit consumes, of time sample a (for odd LOGQ:
-// a < Q/2; its partner a + Q/2 sits right behind it).
-template <int LOGQ>
-__device__ __forceinline__ int dit_pos(int a) {
-  int p = 0;
-#pragma unroll
-  for (int t = 0; t < (LOGQ >> 1); ++t) p |= ((a >> (2 * t)) & 3) << (LOGQ - 2 * t - 2);
-  return p;
-}
-
-// Two adjacent channels of one token row as a complex number.
-template <bool BF16>
-__device__ __forceinline__ float2 load_pair(const char* row) {
-  if constexpr (BF16) {
-    const uint32_t u = *(const uint32_t*)row;
-    return make_float2(__uint_as_float(u << 16), __uint_as_float(u & 0xffff0000u));
-  } else {
-    return *(const float2*)row;
-  }
-}
-
 // hardware block id -> (xcd = id & 7, idx = id >> 3); XCD x owns the (slice, tensor) pairs
 // x * per_xcd .. (x + 1) * per_xcd - 1, 64 consecutive idx each.
 template <int LOGQ, bool BF16, bool MULTI>
@@ -106,7 +85,7 @@ __global__ __launch_bounds__(kFftThreads, 4) void prefill_fft_kernel(Params P, c
         for (int it = 0; it < GRP; ++it) {
           const int a = (g0 + it) * kFftThreads + lt;
           if (H % kFftThreads == 0 || a < H) {  // first radix-2 stage of the decimation-in-time order
-            const int p = dit_pos<LOGQ>(a);
+            const int p = digit_pos<LOGQ>(a);
             buf[pad(p)] = cadd(za[it], zc[it]);
             buf[pad(p + 1)] = csub(za[it], zc[it]);
           }
@@ -124,7 +103,7 @@ __global__ __launch_bounds__(kFftThreads, 4) void prefill_fft_kernel(Params P, c
 #pragma unroll
       for (int it = 0; it < IT; ++it) {
         const int a = it * kFftThreads + lt;
-        if (Q % kFftThreads == 0 || a < Q) buf[pad(dit_pos<LOGQ>(a))] = za[it];
+        if (Q % kFftThreads == 0 || a < Q) buf[pad(digit_pos<LOGQ>(a))] = za[it];
       }
     }
     __syncthreads();  // (the first time also publishes tab)

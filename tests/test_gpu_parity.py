@@ -503,6 +503,41 @@ def test_shortcut_variant_through_prescaled_tokens():
     cache.close()
 
 
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("L,n_bins,steps", [(256, 100, 7), (512, 77, 3), (1024, 300, 1030), (2048, 77, 5), (4096, 1500, 2),
+                                            (8192, 600, 9), (16384, 900, 4), (32768, 2100, 3)])
+def test_reconstruct_long_ranges_through_ffts(dtype, L, n_bins, steps):
+    # long slot ranges take the inverse-FFT kernel (all transform lengths, the decimated form beyond 8192,
+    # a non-zero slot shift after appends, wrap-around of the shift); ranges: everything, an offset half,
+    # and a short one that stays with the direct contraction -- all against the oracle
+    big = L > 8192
+    cfg = small_cfg(L=L, dtype=dtype, n_bins=n_bins, steps=steps, group=1, n_layers=1 if big else 2,
+                    batch=1 if big else 2)
+    bins = random_bins(cfg, 73)
+    w = [np.random.default_rng(l).uniform(0.5, 2.0, size=len(b)).astype(np.float32) for l, b in enumerate(bins)]
+    K, V = wl.prefill_tensors(cfg, DEV)
+    cache = make_cache(cfg, bins, w)
+    cache.prefill(K, V)
+    ora = SliceOracle(cfg, bins, w, K, V, wl.sample_slices(cfg, 4))
+    for i in range(steps):
+        tk, tv, _ = wl.decode_step(cfg, i % 32, DEV)
+        cache.append(tk, tv)
+        ora.append(tk, tv)
+    for a0, n in [(0, L), (L // 4 + 3, L // 2), (5, 16)]:
+        check_reconstruct(cfg, cache, ora, a0, n, f"rec-fft-{dtype}-L{L} [{a0}, {a0 + n})")
+    # and the same numbers as the direct contraction (forced by the flag) to a few ulps of the output
+    direct = make_cache(cfg, bins, w, flags=B.IWDFT_FLAG_DIRECT_SYNTHESIS)
+    direct.prefill(K, V)
+    for i in range(steps):
+        tk, tv, _ = wl.decode_step(cfg, i % 32, DEV)
+        direct.append(tk, tv)
+    Ka, Va = cache.reconstruct(0, 0, L)
+    Kb, Vb = direct.reconstruct(0, 0, L)
+    assert rel_l2(f64(Ka), f64(Kb)) < TOL_REC[cfg.torch_dtype] and rel_l2(f64(Va), f64(Vb)) < TOL_REC[cfg.torch_dtype]
+    cache.close()
+    direct.close()
+
+
 def test_deferred_write_back_many_wraps():
     # more steps than M: the slot shifts of the deferred tokens wrap around inside a batch
     cfg = small_cfg(L=256, n_bins=60, group=2, steps=530, n_layers=1, batch=1, dtype="f32")
