@@ -77,31 +77,46 @@ struct StepUpdate {
   uint32_t tsh;
   int np;
   float* ps;  // kPlain with np > 0: [slice][query head][kMaxPend], Re sum_k e^{j theta_jk} Pn[k] (from kernel B)
-  // Non-null: the newest pending token (row np - 1) is not in the pending rows yet but still in the
-  // caller's token tensors ([slice][128]); the kernels read it there, and in kPlain mode kernel A stores
-  // its K row and kernel C its V row into the pending rows for the steps to come.
+  // Non-null: the step's token has not been filed yet; it is still in the caller's tensors ([slice][128])
+  // and the kernels do the filing themselves.  Without a recent window (ring_slot < 0) the token is the
+  // newest pending row (np - 1).  With one, the newest pending row is the token that ages out of the
+  // window -- still in ring slot `ring_slot` -- and the step's token stands in for that slot among the
+  // exact tokens; kernel C writes it there at its end.  In kPlain mode kernel A stores the K row and
+  // kernel C the V row of the newest pending token into the pending rows for the steps to come.
   const void* nk;
   const void* nv;
+  int ring_slot;
 };
 
 // Element `c` of pending row j of a slice (K: value = false, V: value = true).
 template <bool BF16>
-__device__ __forceinline__ float pend_elem(const StepUpdate& up, bool value, int slice, int j, int c) {
-  const void* fresh = value ? up.nv : up.nk;
-  if (fresh && j == up.np - 1) return load_kv<BF16>(fresh, (int64_t)slice * kHeadDim + c);
+__device__ __forceinline__ float pend_elem(const Params& P, const StepUpdate& up, bool value, int slice, int j,
+                                           int c) {
+  if (up.nk && j == up.np - 1) {
+    if (up.ring_slot >= 0)
+      return load_kv<BF16>(value ? P.ringV : P.ringK, ((int64_t)slice * P.R + up.ring_slot) * kHeadDim + c);
+    return load_kv<BF16>(value ? up.nv : up.nk, (int64_t)slice * kHeadDim + c);
+  }
   return load_kv<BF16>(value ? up.xv : up.xk, (int64_t)slice * up.stride + j * kHeadDim + c);
 }
-// Keeps the newest token for later steps: pending row np - 1, channels [c0, c0 + n), one per thread.
+// Keeps the newest pending token for later steps: row np - 1, channels [c0, c0 + n), one per thread.
 template <bool BF16>
-__device__ __forceinline__ void pend_keep(const StepUpdate& up, bool value, int slice, int c0, int n) {
-  const void* fresh = value ? up.nv : up.nk;
-  if (!fresh || (int)threadIdx.x >= n) return;
+__device__ __forceinline__ void pend_keep(const Params& P, const StepUpdate& up, bool value, int slice, int c0,
+                                          int n) {
+  if (!up.nk || (int)threadIdx.x >= n) return;
   const int c = c0 + threadIdx.x;
-  const int64_t src = (int64_t)slice * kHeadDim + c;
-  const int64_t dst = (int64_t)slice * up.stride + (int64_t)(up.np - 1) * kHeadDim + c;
-  void* rows = const_cast<void*>(value ? up.xv : up.xk);
-  if constexpr (BF16) ((uint16_t*)rows)[dst] = ((const uint16_t*)fresh)[src];
-  else ((float*)rows)[dst] = ((const float*)fresh)[src];
+  const float x = pend_elem<BF16>(P, up, value, slice, up.np - 1, c);  // exact: a storage-dtype value
+  store_kv<BF16>(const_cast<void*>(value ? up.xv : up.xk),
+                 (int64_t)slice * up.stride + (int64_t)(up.np - 1) * kHeadDim + c, x);
+}
+// Row e of the exact tokens during a fused step: the step's token stands in for the ring slot it is
+// about to take.
+template <bool BF16>
+__device__ __forceinline__ const void* exact_row_step(const Params& P, const StepUpdate& up, bool value, int slice,
+                                                      int e) {
+  if (up.nk && up.ring_slot >= 0 && e == P.S + up.ring_slot)
+    return (const char*)(value ? up.nv : up.nk) + (int64_t)slice * kHeadDim * (BF16 ? 2 : 4);
+  return exact_row<BF16>(P, value, slice, e);
 }
 
 // (a.xy, a.zw) * (b.xy, b.zw): two complex products side by side.
@@ -163,7 +178,7 @@ __global__ __launch_bounds__(qc_threads(MODE != kPlain)) void attn_qc_kernel(Par
   __syncthreads();
   if constexpr (MODE == kUpdateN) {
     for (int e = threadIdx.x; e < up.np * kHeadDim; e += kQcThreads)
-      xs[e / kHeadDim][e % kHeadDim] = pend_elem<BF16>(up, false, slice, e / kHeadDim, e % kHeadDim);
+      xs[e / kHeadDim][e % kHeadDim] = pend_elem<BF16>(P, up, false, slice, e / kHeadDim, e % kHeadDim);
     __syncthreads();
   }
   if constexpr (MODE == kPlain) {
@@ -172,10 +187,10 @@ __global__ __launch_bounds__(qc_threads(MODE != kPlain)) void attn_qc_kernel(Par
         const int j = idx / GT, g = idx % GT;
         float dot = 0.f;
         for (int c = 0; c < kHeadDim; ++c)
-          dot += qs[g][c] * pend_elem<BF16>(up, false, slice, j, c);
+          dot += qs[g][c] * pend_elem<BF16>(P, up, false, slice, j, c);
         dq[j][g] = dot;
       }
-      if (chunk == 0 && pass == 0) pend_keep<BF16>(up, false, slice, 0, kHeadDim);
+      if (chunk == 0 && pass == 0) pend_keep<BF16>(P, up, false, slice, 0, kHeadDim);
       __syncthreads();
     }
   }
@@ -184,7 +199,7 @@ __global__ __launch_bounds__(qc_threads(MODE != kPlain)) void attn_qc_kernel(Par
     for (int idx = threadIdx.x; idx < E * GT; idx += kQcThreads) {
       const int e = idx / GT, g = idx % GT;
       if (g0 + g >= P.G) continue;
-      const void* kr = exact_row<BF16>(P, false, slice, e);
+      const void* kr = exact_row_step<BF16>(P, up, false, slice, e);
       float dot = 0.f;
       for (int c = 0; c < kHeadDim; c += 8) {
         if constexpr (BF16) {
@@ -247,7 +262,7 @@ __global__ __launch_bounds__(qc_threads(MODE != kPlain)) void attn_qc_kernel(Par
     if constexpr (MODE == kUpdate1) {
       float x[U];
 #pragma unroll
-      for (int u = 0; u < U; ++u) x[u] = load_kv<BF16>(up.xk, (int64_t)slice * up.stride + d + u);
+      for (int u = 0; u < U; ++u) x[u] = pend_elem<BF16>(P, up, false, slice, 0, d + u);
 #pragma unroll
       for (int u = 0; u < U; ++u) {
         f[u] += x[u] * tw;
@@ -361,13 +376,13 @@ __global__ __launch_bounds__(kOutThreads) void attn_out_kernel(Params P, const f
   float xr[MODE == kUpdate1 ? kOutDC : 1];
   if constexpr (MODE == kUpdate1) {
 #pragma unroll
-    for (int dd = 0; dd < kOutDC; ++dd) xr[dd] = load_kv<BF16>(up.xv, (int64_t)slice * up.stride + d0 + dd);
+    for (int dd = 0; dd < kOutDC; ++dd) xr[dd] = pend_elem<BF16>(P, up, true, slice, 0, d0 + dd);
   }
   __shared__ float xs[MODE == kUpdateN ? kMaxPend : 1][kOutDC];  // pending V rows, this block's channels
   if constexpr (MODE == kUpdateN) {
     for (int e = threadIdx.x; e < up.np * kOutDC; e += kOutThreads)
       xs[e / kOutDC][e % kOutDC] =
-          pend_elem<BF16>(up, true, slice, e / kOutDC, d0 + (e % kOutDC));
+          pend_elem<BF16>(P, up, true, slice, e / kOutDC, d0 + (e % kOutDC));
     __syncthreads();
   }
 
@@ -445,17 +460,28 @@ __global__ __launch_bounds__(kOutThreads) void attn_out_kernel(Params P, const f
       const int E = P.S + P.R;
       const float* w = pe + ((int64_t)slice * P.G + g0 + g) * E;
       for (int e = 0; e < E; ++e)  // exact tokens: weights already divided by the softmax sum
-        tot += w[e] * load_kv<BF16>(exact_row<BF16>(P, true, slice, e), d0 + dd);
+        tot += w[e] * load_kv<BF16>(exact_row_step<BF16>(P, up, true, slice, e), d0 + dd);
       if constexpr (PLAIN) {
         const float* sj = up.ps + ((int64_t)slice * P.G + g0 + g) * kMaxPend;
         for (int j = 0; j < up.np; ++j)  // pending tokens' share of the V coefficients
-          tot += sj[j] * pend_elem<BF16>(up, true, slice, j, d0 + dd);
+          tot += sj[j] * pend_elem<BF16>(P, up, true, slice, j, d0 + dd);
       }
       store_kv<BF16>(out, ((int64_t)slice * P.G + g0 + g) * kHeadDim + d0 + dd, tot);
     }
   }
   if constexpr (PLAIN) {
-    if (up.np > 0 && pass == 0) pend_keep<BF16>(up, true, slice, d0, kOutDC);  // this block's 16 channels
+    if (up.np > 0 && pass == 0) pend_keep<BF16>(P, up, true, slice, d0, kOutDC);  // this block's 16 channels
+  }
+  if (up.nk && up.ring_slot >= 0 && pass == 0) {
+    // The step's token takes the ring slot (K and V, this block's 16 channels) once every read of the old
+    // content by this block is done; no other block touches these channels, and kernel A is long finished.
+    __syncthreads();
+    if (threadIdx.x < kOutDC) {
+      const int64_t src = (int64_t)slice * kHeadDim + d0 + threadIdx.x;
+      const int64_t dst = ((int64_t)slice * P.R + up.ring_slot) * kHeadDim + d0 + threadIdx.x;
+      store_kv<BF16>(P.ringK, dst, load_kv<BF16>(up.nk, src));
+      store_kv<BF16>(P.ringV, dst, load_kv<BF16>(up.nv, src));
+    }
   }
 }
 
@@ -839,7 +865,7 @@ static hipError_t launch_attn_t(const Params& P, const void* q, void* out, float
                                 const StepUpdate* up, int mode, const PhaseEvents* marks, hipStream_t st) {
   const int GT = heads_per_pass(P.G);
   const int passes = (P.G + GT - 1) / GT;
-  const StepUpdate u = up ? *up : StepUpdate{nullptr, nullptr, 0, 0, 0, nullptr, nullptr, nullptr};
+  const StepUpdate u = up ? *up : StepUpdate{nullptr, nullptr, 0, 0, 0, nullptr, nullptr, nullptr, -1};
   const int kQcThreads = qc_threads(mode != kPlain), kQcBins = qc_bins(mode != kPlain);
   const int chunks = (P.max_Bp + kQcBins - 1) / kQcBins;
   const uint64_t gridA = (uint64_t)P.n_slices * chunks * passes;
@@ -939,39 +965,6 @@ hipError_t launch_attn(const Params& P, const void* q, void* out, float scale, f
              : launch_attn_t<false>(P, q, out, scale, qc, Pn, pe, direct_scratch, use_fft, nullptr, kPlain, marks, st);
 }
 
-// Fused step with a recent window: the oldest ring token, which the coefficients have to absorb, goes to
-// row `row` of the slice's pending rows ([slice][rows][128]) and the new token takes its slot, so that the
-// attention kernels already see the updated window.  grid: slice ; y: tensor; 128 threads = channels.
-template <bool BF16>
-__global__ __launch_bounds__(kHeadDim) void pend_push_kernel(Params P, const void* __restrict__ tok_k,
-                                                            const void* __restrict__ tok_v, void* pend_k,
-                                                            void* pend_v, int rows, int row, uint32_t ring_pos) {
-  const int slice = blockIdx.x;
-  const void* tok = blockIdx.y ? tok_v : tok_k;
-  void* ring = blockIdx.y ? P.ringV : P.ringK;
-  void* pend = blockIdx.y ? pend_v : pend_k;
-  const int64_t src = (int64_t)slice * kHeadDim + threadIdx.x;
-  const int64_t dst = ((int64_t)slice * rows + row) * kHeadDim + threadIdx.x;
-  const int64_t slot = ((int64_t)slice * P.R + ring_pos) * kHeadDim + threadIdx.x;
-  if constexpr (BF16) {
-    uint16_t x = ((const uint16_t*)tok)[src];
-    if (P.R > 0) {
-      const uint16_t old = ((uint16_t*)ring)[slot];
-      ((uint16_t*)ring)[slot] = x;
-      x = old;
-    }
-    ((uint16_t*)pend)[dst] = x;
-  } else {
-    float x = ((const float*)tok)[src];
-    if (P.R > 0) {
-      const float old = ((float*)ring)[slot];
-      ((float*)ring)[slot] = x;
-      x = old;
-    }
-    ((float*)pend)[dst] = x;
-  }
-}
-
 bool heads_fit_one_pass(int G) { return (G + heads_per_pass(G) - 1) / heads_per_pass(G) == 1; }
 bool step_can_fuse(const Params& P) { return heads_fit_one_pass(P.G); }
 
@@ -981,25 +974,14 @@ hipError_t launch_step(const Params& P, const void* tok_k, const void* tok_v, co
                        int write_every, const PhaseEvents* marks, hipStream_t st) {
   if (write_every < 1 || write_every > kMaxPend || pend_before < 0 || pend_before >= write_every)
     return hipErrorInvalidValue;
-  StepUpdate up{tok_k, tok_v, kHeadDim, tsh0, pend_before + 1, ps, nullptr, nullptr};
-  if (P.R > 0) {  // recent window: the ring hands its oldest token over before the attention kernels run
-    if (P.kv_dtype == 1)
-      pend_push_kernel<true><<<dim3((uint32_t)P.n_slices, 2), dim3(kHeadDim), 0, st>>>(
-          P, tok_k, tok_v, pend_k, pend_v, write_every, pend_before, ring_pos);
-    else
-      pend_push_kernel<false><<<dim3((uint32_t)P.n_slices, 2), dim3(kHeadDim), 0, st>>>(
-          P, tok_k, tok_v, pend_k, pend_v, write_every, pend_before, ring_pos);
-    hipError_t e = hipGetLastError();
-    if (e != hipSuccess) return e;
-    up.xk = pend_k;
-    up.xv = pend_v;
-    up.stride = (int64_t)write_every * kHeadDim;
-  } else if (write_every > 1) {  // the kernels take the new token from the caller and keep it themselves
+  StepUpdate up{tok_k, tok_v, kHeadDim, tsh0, pend_before + 1, ps, nullptr, nullptr, -1};
+  if (P.R > 0 || write_every > 1) {  // the kernels file the step's token themselves (see StepUpdate)
     up.xk = pend_k;
     up.xv = pend_v;
     up.stride = (int64_t)write_every * kHeadDim;
     up.nk = tok_k;
     up.nv = tok_v;
+    up.ring_slot = P.R > 0 ? (int)ring_pos : -1;
   }
   const int mode = up.np < write_every ? kPlain : (write_every == 1 ? kUpdate1 : kUpdateN);
   return P.kv_dtype == 1
