@@ -27,6 +27,12 @@ def test_cfg5_wide_outlier_channels():
     run_stream(cfg, wl.layer_bins(cfg), steps=2, slices=wl.sample_slices(cfg, 6), tag="cfg5")
 
 
+def test_cfg5_fused_steps_with_deferred_write_back():
+    cfg = wl.CONFIGS["cfg5"]
+    run_stream(cfg, wl.layer_bins(cfg), steps=5, slices=wl.sample_slices(cfg, 6), fused=True, write_every=4,
+               tag="cfg5-fused-J4")
+
+
 def test_cfg4_long_context_drift():
     """1024 streaming appends with decode attention at every step; coefficients are compared with
     the oracle's recursion AND with its from-scratch closed form at steps 1, 16, 256, 1024."""

@@ -382,6 +382,15 @@ def test_deferred_write_back_stream(dtype, L, S, R, group, J):
                tag=f"defer-{dtype}-L{L}-S{S}-R{R}-G{group}-J{J}")
 
 
+@pytest.mark.parametrize("L,n_bins", [(16384, 1600), (16384, 3000), (8192, 4096), (32768, 900)])
+def test_deferred_write_back_every_fft_kernel_variant(L, n_bins):
+    # the pending tokens are weighed in the epilogue of attention kernel B, which exists in several
+    # register-budget variants (2, 4 or 8 kept bins per thread, one or many transform blocks): all of
+    # them with 16 deferred tokens, windows included
+    cfg = small_cfg(L=L, group=4, dtype="bf16", n_bins=n_bins, n_sink=2, n_recent=3, steps=18, n_layers=1, batch=1)
+    run_stream(cfg, random_bins(cfg, 79), rec=(3, 50), fused=True, write_every=16, tag=f"defer-variants-L{L}-B{n_bins}")
+
+
 def test_deferred_write_back_mixed_with_other_calls():
     # any call other than the fused step first writes the deferred tokens back: a random mix of calls
     # gives, step for step, what the oracle gives
