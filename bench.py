@@ -389,6 +389,8 @@ def cpu_baseline(cfg, bins, K, V, pool, np, torch):
         "append_s_per_step_scaled": t_app / steps * scale,
         "attn_s_per_step_scaled": t_att / steps * scale,
         "host_cores_available": len(os.sched_getaffinity(0)),
+        # slices are independent, so the oracle would scale over the host cores at best linearly
+        "value_all_cores_estimate": dsteps * cfg.batch / job_s * len(os.sched_getaffinity(0)),
     }
 
 
