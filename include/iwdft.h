@@ -209,7 +209,9 @@ int iwdft_select_bins(const float* delta, int32_t n_layers, int32_t n_chunks, in
 /* Frequency ablation of one chunk (Sec. 3.2, Eq. freq-zero): per slice and channel the DFT along the token
  * axis, the coefficients of the chunk's bins set to zero, the inverse DFT, real part.
  * d_x, d_out: DEVICE [n_slices][M][head_dim], kv_dtype, must not overlap.  This build: head_dim 128 and
- * M = 2^m, 256 <= M <= 8192 (IWDFT_ERR_UNSUPPORTED otherwise).  Needs no context; enqueues on hip_stream. */
+ * M = 2^m, 256 <= M <= 2^24 (IWDFT_ERR_UNSUPPORTED otherwise).  For M > 8192 the chunk's part is taken off the
+ * input 4096 bins at a time through d_out, so a bf16 result carries one more rounding per such piece.
+ * Needs no context; enqueues on hip_stream. */
 int iwdft_ablate_chunk(const void* d_x, void* d_out, int64_t n_slices, int64_t M, int32_t head_dim,
                        int32_t kv_dtype, int32_t n_chunks, int32_t chunk, void* hip_stream);
 

@@ -586,8 +586,8 @@ int iwdft_ablate_chunk(const void* d_x, void* d_out, int64_t n_slices, int64_t M
     return fail(IWDFT_ERR_ARG, "chunk %d outside [0, %d)", chunk, n_chunks);
   if (M < 1) return fail(IWDFT_ERR_ARG, "M must be positive");
   if (head_dim != kHeadDim) return fail(IWDFT_ERR_UNSUPPORTED, "head_dim %d: this build handles 128", head_dim);
-  if ((M & (M - 1)) != 0 || M < (int64_t)kFftMinM || M > 8192)
-    return fail(IWDFT_ERR_UNSUPPORTED, "iwdft_ablate_chunk needs M = 2^m with 256 <= M <= 8192 (got %lld)",
+  if ((M & (M - 1)) != 0 || M < (int64_t)kFftMinM || M > ((int64_t)1 << 24))
+    return fail(IWDFT_ERR_UNSUPPORTED, "iwdft_ablate_chunk needs M = 2^m with 256 <= M <= 2^24 (got %lld)",
                 (long long)M);
   const size_t esz = kv_dtype == IWDFT_BF16 ? 2 : 4;
   const size_t bytes = (size_t)n_slices * (size_t)M * kHeadDim * esz;

@@ -77,7 +77,7 @@ def test_ablate_chunk_argument_errors_need_no_gpu():
     assert f(p, q, 1, 1024, 64, 0, 22, 0, None) == B.IWDFT_ERR_UNSUPPORTED
     assert f(p, q, 1, 1000, 128, 0, 22, 0, None) == B.IWDFT_ERR_UNSUPPORTED
     assert f(p, q, 1, 128, 128, 0, 22, 0, None) == B.IWDFT_ERR_UNSUPPORTED
-    assert f(p, q, 1, 16384, 128, 0, 22, 0, None) == B.IWDFT_ERR_UNSUPPORTED
+    assert f(p, q, 1, 1 << 25, 128, 0, 22, 0, None) == B.IWDFT_ERR_UNSUPPORTED
     assert f(p, ctypes.c_void_p(4096 + 64), 1, 1024, 128, 0, 22, 0, None) == B.IWDFT_ERR_ARG   # overlap
     assert f(p, q, 0, 1024, 128, 0, 22, 0, None) == B.IWDFT_OK                                 # nothing to do
 
@@ -85,7 +85,9 @@ def test_ablate_chunk_argument_errors_need_no_gpu():
 @pytest.mark.gpu
 @pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
 @pytest.mark.parametrize("M,C,chunks", [(256, 22, (0, 7, 21)), (512, 5, (2,)), (1024, 22, (0, 11)), (2048, 1, (0,)),
-                                        (4096, 22, (3,)), (8192, 22, (0, 10, 21))])
+                                        (4096, 22, (3,)), (8192, 22, (0, 10, 21)),
+                                        # longer than one in-LDS transform: the subtractive form, in pieces
+                                        (16384, 1, (0,)), (16384, 3, (0, 2)), (32768, 22, (0, 10, 21))])
 def test_ablate_chunk_matches_the_oracle(dtype, M, C, chunks):
     dev = "cuda:0"
     g = torch.Generator(device=dev).manual_seed(M + C)
@@ -101,8 +103,13 @@ def test_ablate_chunk_matches_the_oracle(dtype, M, C, chunks):
         got = out.detach().cpu().to(torch.float64).numpy()
         for s in [(0, 0), (1, 1), (2, 0)]:
             ref = orc.ablate_chunk(xh[s], C, c)
-            err = np.linalg.norm(got[s] - ref) / max(np.linalg.norm(ref), 1e-30)
+            # one chunk holding every bin leaves nothing: the error is then measured against the input
+            den = np.linalg.norm(ref) if C > 1 else np.linalg.norm(xh[s])
+            err = np.linalg.norm(got[s] - ref) / max(den, 1e-30)
             # fp32 transforms: ~1e-6; bf16 output rounding alone is 2^-9 per element
             assert err < (1e-4 if dtype == torch.float32 else 4e-3), f"M={M} C={C} chunk={c} slice={s}: {err:.3e}"
         if C == 1:
-            assert float(out.float().abs().max()) < 1e-3 * float(x.float().abs().max())
+            # a chunk of more than 4096 bins is taken off in pieces, and bf16 rounds what is left between them
+            pieces = -(-(M // 2 + 1) // 4096) if M > 8192 else 1
+            bar = 1e-3 if (dtype == torch.float32 or pieces == 1) else pieces * 2.0 ** -8
+            assert float(out.float().abs().max()) < bar * float(x.float().abs().max())
