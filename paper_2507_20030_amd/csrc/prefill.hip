@@ -41,7 +41,8 @@ __device__ __forceinline__ float half_hi_f32(uint32_t pk) {
   return (float)__builtin_bit_cast(_Float16, (uint16_t)(pk >> 16));
 }
 
-// Raw tile registers of one thread: 4 items, each = 2 tokens x 8 channels.
+// Raw tile registers of one thread.  fp32 inputs: 4 items of 2 tokens x 8 channels; bf16 inputs: 2 items of
+// 4 tokens x 8 channels (one 16-byte load per token either way).
 template <bool BF16>
 struct TileRegs {
   uint4 v[BF16 ? 8 : 16];
@@ -52,19 +53,31 @@ template <bool BF16, bool FULL>
 __device__ __forceinline__ void load_tile(TileRegs<BF16>& r, const void* __restrict__ K,
                                           const void* __restrict__ V, int64_t slice_base, uint32_t n0,
                                           uint32_t M, int tid) {
-  const int p = tid & 31;
+  if constexpr (BF16) {
+    const int p = tid & 15;
 #pragma unroll
-  for (int it = 0; it < 4; ++it) {
-    const int q = (tid >> 5) + 8 * it;  // 8-channel group 0..31 (0..15 K, 16..31 V)
-    const void* X = (q >> 4) ? V : K;
-    const int ch = (q & 15) * 8;
+    for (int it = 0; it < 2; ++it) {
+      const int q = (tid >> 4) + 16 * it;  // 8-channel group 0..31 (0..15 K, 16..31 V)
+      const void* X = (q >> 4) ? V : K;
+      const int ch = (q & 15) * 8;
 #pragma unroll
-    for (int t = 0; t < 2; ++t) {
-      const uint32_t n = n0 + 2 * p + t;
-      const int64_t e = slice_base + (int64_t)n * kHeadDim + ch;  // element index
-      if constexpr (BF16) {
-        r.v[it * 2 + t] = (FULL || n < M) ? *(const uint4*)((const uint16_t*)X + e) : make_uint4(0, 0, 0, 0);
-      } else {
+      for (int t = 0; t < 4; ++t) {
+        const uint32_t n = n0 + 4 * p + t;
+        const int64_t e = slice_base + (int64_t)n * kHeadDim + ch;  // element index
+        r.v[it * 4 + t] = (FULL || n < M) ? *(const uint4*)((const uint16_t*)X + e) : make_uint4(0, 0, 0, 0);
+      }
+    }
+  } else {
+    const int p = tid & 31;
+#pragma unroll
+    for (int it = 0; it < 4; ++it) {
+      const int q = (tid >> 5) + 8 * it;
+      const void* X = (q >> 4) ? V : K;
+      const int ch = (q & 15) * 8;
+#pragma unroll
+      for (int t = 0; t < 2; ++t) {
+        const uint32_t n = n0 + 2 * p + t;
+        const int64_t e = slice_base + (int64_t)n * kHeadDim + ch;
         r.v[(it * 2 + t) * 2] = (FULL || n < M) ? *(const uint4*)((const float*)X + e) : make_uint4(0, 0, 0, 0);
         r.v[(it * 2 + t) * 2 + 1] = (FULL || n < M) ? *(const uint4*)((const float*)X + e + 4) : make_uint4(0, 0, 0, 0);
       }
@@ -72,31 +85,44 @@ __device__ __forceinline__ void load_tile(TileRegs<BF16>& r, const void* __restr
   }
 }
 
-// Converts to fp16 (hi, and lo for fp32 inputs) and writes token pairs transposed into LDS:
-// element (channel c, token n) of part `part` lives at lds[(part * 256 + c) * kPfRS + n].
-template <bool BF16, int IT0 = 0, int IT1 = 4>
+// Converts quarters [Q0, Q1) of a thread's tile registers to fp16 (hi, and lo for fp32 inputs) and writes them
+// transposed into LDS: element (channel c, token n) of part `part` lives at lds[(part * 256 + c) * kPfRS + n].
+// bf16: a quarter = 4 channels of one item, each written as 4 adjacent tokens (8 bytes); fp32: a quarter = one
+// item, each channel written as a token pair (4 bytes per part).
+template <bool BF16, int Q0 = 0, int Q1 = 4>
 __device__ __forceinline__ void store_tile(const TileRegs<BF16>& r, _Float16* __restrict__ buf, int tid) {
-  const int p = tid & 31;
+  if constexpr (BF16) {
+    const int p = tid & 15;
 #pragma unroll
-  for (int it = IT0; it < IT1; ++it) {
-    const int q = (tid >> 5) + 8 * it;
+    for (int qd = Q0; qd < Q1; ++qd) {
+      const int it = qd >> 1;
+      const int q = (tid >> 4) + 16 * it;
 #pragma unroll
-    for (int j = 0; j < 8; ++j) {
-      float x0, x1;
-      if constexpr (BF16) {
-        const uint4 a = r.v[it * 2], b = r.v[it * 2 + 1];
-        const uint32_t wa = (&a.x)[j >> 1], wb = (&b.x)[j >> 1];
-        x0 = __uint_as_float((j & 1) ? (wa & 0xffff0000u) : (wa << 16));
-        x1 = __uint_as_float((j & 1) ? (wb & 0xffff0000u) : (wb << 16));
-      } else {
-        const uint4 a = r.v[(it * 2) * 2 + (j >> 2)], b = r.v[(it * 2 + 1) * 2 + (j >> 2)];
-        x0 = __uint_as_float((&a.x)[j & 3]);
-        x1 = __uint_as_float((&b.x)[j & 3]);
+      for (int j = (qd & 1) * 4; j < (qd & 1) * 4 + 4; ++j) {
+        float x[4];
+#pragma unroll
+        for (int t = 0; t < 4; ++t) {
+          const uint4 a = r.v[it * 4 + t];
+          const uint32_t w = (&a.x)[j >> 1];
+          x[t] = __uint_as_float((j & 1) ? (w & 0xffff0000u) : (w << 16));
+        }
+        const int c = q * 8 + j;
+        *(uint2*)(buf + c * kPfRS + 4 * p) = make_uint2(pack_rtz(x[0], x[1]), pack_rtz(x[2], x[3]));
       }
-      const int c = q * 8 + j;
-      const uint32_t hi = pack_rtz(x0, x1);
-      *(uint32_t*)(buf + c * kPfRS + 2 * p) = hi;
-      if constexpr (!BF16) {
+    }
+  } else {
+    const int p = tid & 31;
+#pragma unroll
+    for (int it = Q0; it < Q1; ++it) {
+      const int q = (tid >> 5) + 8 * it;
+#pragma unroll
+      for (int j = 0; j < 8; ++j) {
+        const uint4 a = r.v[(it * 2) * 2 + (j >> 2)], b = r.v[(it * 2 + 1) * 2 + (j >> 2)];
+        const float x0 = __uint_as_float((&a.x)[j & 3]);
+        const float x1 = __uint_as_float((&b.x)[j & 3]);
+        const int c = q * 8 + j;
+        const uint32_t hi = pack_rtz(x0, x1);
+        *(uint32_t*)(buf + c * kPfRS + 2 * p) = hi;
         const uint32_t lo = pack_rtz(x0 - half_lo_f32(hi), x1 - half_hi_f32(hi));
         *(uint32_t*)(buf + (kPfCh + c) * kPfRS + 2 * p) = lo;
       }
@@ -209,12 +235,12 @@ __global__ __launch_bounds__(kPfThreads) void prefill_mfma_kernel(Params P, cons
     if constexpr (!BF16) acl[b] = *(const half8*)(lds + (kPfCh + b * 32) * kPfRS + a_off);
   }
 
-  for (uint32_t t = 0; t < n_tiles; ++t) {
+  // One 64-token tile: loads tile t_load into rl, converts rs (the tile after t) into the other LDS buffer,
+  // and runs the MFMAs of tile t.
+  auto tile_body = [&](uint32_t t, uint32_t t_load, TileRegs<BF16>& rl, TileRegs<BF16>& rs) __attribute__((always_inline)) {
     const _Float16* cur = lds + (t & 1) * kBufHalves;
     _Float16* nxt = lds + ((t + 1) & 1) * kBufHalves;
-    // The tile after the last one is a harmless reload of the last tile (keeps the body branch-free).
-    const uint32_t tn = (t + 1 < n_tiles) ? t + 1 : t;
-    load_tile<BF16, FULL>(regs, K, V, slice_base, tn * kPfTok, M, tid);
+    load_tile<BF16, FULL>(rl, K, V, slice_base, t_load * kPfTok, M, tid);
 
 #pragma unroll
     for (int st = 0; st < kSteps; ++st) {
@@ -236,8 +262,8 @@ __global__ __launch_bounds__(kPfThreads) void prefill_mfma_kernel(Params P, cons
         base = make_float2(c.x, -c.y);
         bn = make_basis(base, tw);
       }
-      if (st == kSteps - 2) store_tile<BF16, 0, 2>(regs, nxt, tid);
-      if (st == kSteps - 1) store_tile<BF16, 2, 4>(regs, nxt, tid);
+      if (st == kSteps - 2) store_tile<BF16, 0, 2>(rs, nxt, tid);
+      if (st == kSteps - 1) store_tile<BF16, 2, 4>(rs, nxt, tid);
 
       // ---- 32 (48 for fp32 inputs) MFMAs of this k-step ---------------------------------------
 #pragma unroll
@@ -270,6 +296,22 @@ __global__ __launch_bounds__(kPfThreads) void prefill_mfma_kernel(Params P, cons
       ac[b] = *(const half8*)(nxt + b * 32 * kPfRS + a_off);
       if constexpr (!BF16) acl[b] = *(const half8*)(nxt + (kPfCh + b * 32) * kPfRS + a_off);
     }
+  };
+  // Tiles beyond the last one are harmless reloads of the last tile (keeps the body branch-free).
+  const uint32_t last = n_tiles - 1;
+  if constexpr (BF16) {
+    // Two register sets: the global loads of a tile are issued two tiles before its MFMAs and one full tile
+    // before its conversion, so their latency never sits on the matrix pipe's path.
+    TileRegs<BF16> regs1;
+    load_tile<BF16, FULL>(regs1, K, V, slice_base, (last < 1u ? last : 1u) * kPfTok, M, tid);
+    uint32_t t = 0;
+    for (; t + 1 < n_tiles; t += 2) {
+      tile_body(t, t + 2 < last ? t + 2 : last, regs, regs1);
+      tile_body(t + 1, t + 3 < last ? t + 3 : last, regs1, regs);
+    }
+    if (t < n_tiles) tile_body(t, last, regs, regs1);
+  } else {
+    for (uint32_t t = 0; t < n_tiles; ++t) tile_body(t, t + 1 < last ? t + 1 : last, regs, regs);
   }
 
   if (!valid) return;
