@@ -210,6 +210,20 @@ def main():
         dcache.close()
         del dcache
 
+    # what the matrix cores sustain on the dense prefill's instruction with nothing else running (zero and
+    # random operands: the part is power-limited, and the second figure is the ceiling real data can approach)
+    probe = torch.empty(1 << 18, dtype=torch.float32, device=dev)
+    mfma_sustained = {}
+    for label, rnd in (("zero_operands", False), ("random_operands", True)):
+        B.iwdft_mfma_probe(probe, 200, rnd, stream)
+        pe = mk(2)
+        pe[0].record(stream)
+        flops = B.iwdft_mfma_probe(probe, 2000, rnd, stream)
+        pe[1].record(stream)
+        torch.cuda.synchronize()
+        mfma_sustained[label + "_TFLOPps"] = flops / (pe[0].elapsed_time(pe[1]) * 1e-3) / 1e12
+    del probe
+
     nb_total = sum(len(b) for b in bins) * cfg.batch * cfg.n_kv_heads      # kept bins x slices
     coef_bytes = nb_total * cfg.head_dim * 8                               # one tensor, complex fp32
     append_bytes = 2 * coef_bytes * 2                                      # K and V, read + write
@@ -292,7 +306,8 @@ def main():
                                     "useful_TFLOPps": prefill_useful_flop / (dense_ms * 1e-3) / 1e12,
                                     "executed_TFLOPps": mfma_split * prefill_useful_flop / (dense_ms * 1e-3) / 1e12,
                                     "frac_mfma_f16_peak": mfma_split * prefill_useful_flop / (dense_ms * 1e-3) / 1e12
-                                                          / MFMA_F16_PEAK_TFLOPS},
+                                                          / MFMA_F16_PEAK_TFLOPS,
+                                    "mfma_probe": mfma_sustained},
             "iwdft_reconstruct_one_layer": {"ms": rec_ms},
         },
         "roofline": {
