@@ -161,7 +161,7 @@ __global__ __launch_bounds__(kFftThreads, 2) void ablate_long_kernel(const char*
           const float2 w1 = buf[pad(r)], w2 = buf[pad(rm)];
           const float2 d0 = make_float2(0.5f * (w1.x + w2.x), 0.5f * (w1.y - w2.y));
           const float2 d1 = make_float2(0.5f * (w1.y + w2.y), 0.5f * (w2.x - w1.x));
-          const float2 tw = conjf2(cis_poly((k * b) & (M - 1u), M));
+          const float2 tw = conjf2(cis_poly2((k * b) & (M - 1u), M));
           acc0[j] = cadd(acc0[j], cmul(tw, d0));
           acc1[j] = cadd(acc1[j], cmul(tw, d1));
         }
@@ -183,7 +183,7 @@ __global__ __launch_bounds__(kFftThreads, 2) void ablate_long_kernel(const char*
         for (int j = 0; j < kFftNBT; ++j) {
           const uint32_t k = (uint32_t)(lo_p + j * kFftThreads + tid);
           if ((int)k < hi_p) {
-            const float2 tw = cis_poly((k * b) & (M - 1u), M);
+            const float2 tw = cis_poly2((k * b) & (M - 1u), M);
             const float2 z0 = cmul(make_float2(acc0[j].x * gain, acc0[j].y * gain), tw);
             const float2 z1 = cmul(make_float2(acc1[j].x * gain, acc1[j].y * gain), tw);
             const int r = k & (Q - 1), rm = (Q - r) & (Q - 1);

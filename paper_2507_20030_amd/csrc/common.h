@@ -71,8 +71,14 @@ __device__ __forceinline__ float2 cis(uint32_t p, uint32_t M) {
 // Same value, branch-free (straight-line code that can sit inside a software-pipelined loop):
 // octant reduction in exact arithmetic (p/M and q/8 are exact for power-of-two M), degree-7/8
 // Taylor polynomials on |theta| <= pi/8 (truncation < 1e-9), then a rotation by q * 45 degrees.
-__device__ __forceinline__ float2 cis_poly(uint32_t p, uint32_t M) {
-  const float x = (float)p / (float)M;            // in [0, 1)
+__device__ __forceinline__ float2 cis_poly_x(float x);
+__device__ __forceinline__ float2 cis_poly(uint32_t p, uint32_t M) { return cis_poly_x((float)p / (float)M); }
+// 1 / M for M = 2^m, exact (exponent negated), without the division sequence.
+__device__ __forceinline__ float rcp_pow2(uint32_t M) { return __uint_as_float(0x7f000000u - __float_as_uint((float)M)); }
+// cis_poly for M = 2^m.
+__device__ __forceinline__ float2 cis_poly2(uint32_t p, uint32_t M) { return cis_poly_x((float)p * rcp_pow2(M)); }
+// x = p / M in [0, 1).
+__device__ __forceinline__ float2 cis_poly_x(float x) {
   const float qf = rintf(x * 8.0f);               // nearest octant boundary, 0..8
   const float th = (x - qf * 0.125f) * 6.283185307179586f;  // |th| <= pi/8
   const float t2 = th * th;

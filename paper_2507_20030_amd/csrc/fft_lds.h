@@ -22,7 +22,7 @@ __device__ __forceinline__ float2 conjf2(float2 a) { return make_float2(a.x, -a.
 // power-of-two M this path requires; ~1e-6 absolute error, used only for the block twiddles of the
 // score synthesis where 1e-6 of a score is far below the output tolerance).
 __device__ __forceinline__ float2 cis_fast(uint32_t p, uint32_t M) {
-  const float f = (float)p / (float)M;
+  const float f = (float)p * rcp_pow2(M);
   return make_float2(__builtin_amdgcn_cosf(f), __builtin_amdgcn_sinf(f));
 }
 
@@ -78,7 +78,7 @@ __device__ __forceinline__ int butterfly_of(int t) {
 // otherwise the forward DIT order (narrow span first, conjugated twiddles).
 template <int LOGQ, int LS2, bool INV>
 __device__ __forceinline__ void fft_pass16(float2* buf, const float2* tab, int tid) {
-  constexpr int Q = 1 << LOGQ, q8 = Q >> 3, s2 = 1 << LS2, NB = Q / 16;
+  constexpr int Q = 1 << LOGQ, s2 = 1 << LS2, NB = Q / 16;
   constexpr int sh1 = LOGQ - LS2 - 4, sh2 = LOGQ - LS2 - 2;
 #pragma unroll
   for (int it = 0; it < (NB + kFftThreads - 1) / kFftThreads; ++it) {
@@ -90,20 +90,30 @@ __device__ __forceinline__ void fft_pass16(float2* buf, const float2* tab, int t
       float2 x[16];
 #pragma unroll
       for (int m = 0; m < 16; ++m) x[m] = base[m * s2 + ((m * s2) >> 5)];
+      // Twiddles of the pass from one table entry t = exp(+j 2 pi j / (16 s2)) (index < Q/16: inside the
+      // octant table as it stands): group b of the wide stage uses t * exp(+j 2 pi b / 16), the narrow stage
+      // t^4.
+      const float2 t1 = tab[j << sh1];
+      const float2 t2 = cmul(t1, t1);
+      const float2 t4 = cmul(t2, t2);
+      const float2 c1 = make_float2(0.92387953251128674f, 0.38268343236508977f);  // exp(j pi / 8)
+      const float2 c2 = make_float2(0.70710678118654752f, 0.70710678118654752f);  // exp(j pi / 4)
+      const float2 c3 = make_float2(0.38268343236508977f, 0.92387953251128674f);  // exp(j 3 pi / 8)
       if constexpr (INV) {
+        r4_dif(x[0], x[4], x[8], x[12], t1);
+        r4_dif(x[1], x[5], x[9], x[13], cmul(t1, c1));
+        r4_dif(x[2], x[6], x[10], x[14], cmul(t1, c2));
+        r4_dif(x[3], x[7], x[11], x[15], cmul(t1, c3));
 #pragma unroll
-        for (int b = 0; b < 4; ++b)
-          r4_dif(x[b], x[b + 4], x[b + 8], x[b + 12], tw_get(tab, ((b << LS2) + j) << sh1, q8));
-        const float2 w = tw_get(tab, j << sh2, q8);
-#pragma unroll
-        for (int a = 0; a < 4; ++a) r4_dif(x[4 * a], x[4 * a + 1], x[4 * a + 2], x[4 * a + 3], w);
+        for (int a = 0; a < 4; ++a) r4_dif(x[4 * a], x[4 * a + 1], x[4 * a + 2], x[4 * a + 3], t4);
       } else {
-        const float2 w = conjf2(tw_get(tab, j << sh2, q8));
+        const float2 w = conjf2(t4);
 #pragma unroll
         for (int a = 0; a < 4; ++a) r4_dit(x[4 * a], x[4 * a + 1], x[4 * a + 2], x[4 * a + 3], w);
-#pragma unroll
-        for (int b = 0; b < 4; ++b)
-          r4_dit(x[b], x[b + 4], x[b + 8], x[b + 12], conjf2(tw_get(tab, ((b << LS2) + j) << sh1, q8)));
+        r4_dit(x[0], x[4], x[8], x[12], conjf2(t1));
+        r4_dit(x[1], x[5], x[9], x[13], conjf2(cmul(t1, c1)));
+        r4_dit(x[2], x[6], x[10], x[14], conjf2(cmul(t1, c2)));
+        r4_dit(x[3], x[7], x[11], x[15], conjf2(cmul(t1, c3)));
       }
 #pragma unroll
       for (int m = 0; m < 16; ++m) base[m * s2 + ((m * s2) >> 5)] = x[m];

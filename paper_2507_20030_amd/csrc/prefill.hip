@@ -259,7 +259,7 @@ __global__ __launch_bounds__(kPfThreads) void prefill_mfma_kernel(Params P, cons
       } else {
         // exact basis phase at the first token this lane feeds in the next tile
         const uint32_t nn = (t + 1) * kPfTok + 8 * g;
-        const float2 c = cis_poly(FULL ? ((k * nn) & (M - 1u)) : mulmod(k, nn, M, Mmask), M);
+        const float2 c = FULL ? cis_poly2((k * nn) & (M - 1u), M) : cis_poly(mulmod(k, nn, M, Mmask), M);
         base = make_float2(c.x, -c.y);
         bn = make_basis(base, tw);
       }

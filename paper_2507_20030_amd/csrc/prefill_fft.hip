@@ -116,7 +116,7 @@ __global__ __launch_bounds__(kFftThreads, 4) void prefill_fft_kernel(Params P, c
         const float2 d0 = make_float2(0.5f * (w1.x + w2.x), 0.5f * (w1.y - w2.y));
         const float2 d1 = make_float2(0.5f * (w1.y + w2.y), 0.5f * (w2.x - w1.x));
         if constexpr (MULTI) {
-          const float2 tw = conjf2(cis_poly((kk[j] * b) & (P.M - 1u), P.M));  // e^{-j 2 pi k b / M}
+          const float2 tw = conjf2(cis_poly2((kk[j] * b) & (P.M - 1u), P.M));  // e^{-j 2 pi k b / M}
           acc0[j] = cadd(acc0[j], cmul(tw, d0));
           acc1[j] = cadd(acc1[j], cmul(tw, d1));
         } else {

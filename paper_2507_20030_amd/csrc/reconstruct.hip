@@ -142,7 +142,7 @@ __global__ __launch_bounds__(kFftThreads, 4) void reconstruct_fft_kernel(Params 
           const uint32_t fr = fold[i];
           const float w = wts[i] * gain;
           float2 tw = make_float2(1.f, 0.f);
-          if (MULTI) tw = cis_poly((k * b) & (P.M - 1u), P.M);
+          if (MULTI) tw = cis_poly2((k * b) & (P.M - 1u), P.M);
           const float2 f0 = F0[i], f1 = F1[i];
           const float2 z0 = cmul(make_float2(f0.x * w, f0.y * w), tw);
           const float2 z1 = cmul(make_float2(f1.x * w, f1.y * w), tw);
