@@ -148,11 +148,13 @@ int make_plan(const iwdft_desc* d, Plan* pl) {
         const int64_t k = d->bins[L.bin_off + i];
         const int64_t r = k & (Q - 1), rm = (Q - r) & (Q - 1);
         const int fd = cnt[r]++;
-        const int fm = cnt[rm]++;
-        if (fd > 255 || fm > 255) { pl->use_fft = false; break; }
+        // a bin whose mirror falls on its own slot (k = 0 or Q/2 mod Q) adds both halves in one write:
+        // its mirror byte is 0xff, "no round"
+        const int fm = r == rm ? 0xff : cnt[rm]++;
+        if (fd > 254 || (r != rm && fm > 254)) { pl->use_fft = false; break; }
         pl->fold[L.bin_off + i] = (uint16_t)(fd | (fm << 8));
         if (fd + 1 > rounds) rounds = fd + 1;
-        if (fm + 1 > rounds) rounds = fm + 1;
+        if (r != rm && fm + 1 > rounds) rounds = fm + 1;
       }
       L.fold_rounds = rounds;
     }

@@ -601,45 +601,58 @@ __global__ __launch_bounds__(kFftThreads, (MULTI && NBT > 4) ? 2 : 4) void attn_
     if (kTight) asm volatile("" : "+v"(lt));
     for (int e = tid; e < Q + (Q >> 5); e += kFftThreads) buf[e] = make_float2(0.f, 0.f);
     __syncthreads();
+    // Folded entry of bin j of this thread: (z0, z1) for the two heads, from inputs loaded as a group (all
+    // loads are issued before the first use: one latency, not one per bin).
+    auto place = [&](int j, uint32_t frj, float2 z0, float2 z1, int round) {
+      const int r = kk[j] & (Q - 1), rm = (Q - r) & (Q - 1);
+      if ((frj & 0xffu) == (uint32_t)round) {  //      z0  + j z1
+        float2 v = make_float2(z0.x - z1.y, z0.y + z1.x);
+        if (r == rm) v = make_float2(2.f * z0.x, 2.f * z1.x);  // ... plus the mirror term, same slot
+        if (round) v = cadd(v, buf[pad(r)]);
+        buf[pad(r)] = v;
+      }
+      if ((frj >> 8) == (uint32_t)round) {     // conj z0  + j conj z1
+        float2 v = make_float2(z0.x + z1.y, z1.x - z0.y);
+        if (round) v = cadd(v, buf[pad(rm)]);
+        buf[pad(rm)] = v;
+      }
+    };
+    // The entries are formed once and the rounds only place them, except in the 8-bins-per-thread kernel with
+    // the 128-register budget, which has no room to keep them and forms them again in every round.
+    constexpr bool kKeep = MULTI || NBT <= 4;
+    float2 z0[kKeep ? NBT : 1], z1[kKeep ? NBT : 1];
+    uint32_t fr[NBT];
     for (int round = 0; round < L.fold_rounds; ++round) {
-      // All loads of a group are issued before the first use (one latency per group, not per bin).
-      constexpr int GRP = NBT;
+      if (!kKeep || round == 0) {
+        float ww[NBT];
+        float2 y0[NBT], y1[NBT];
 #pragma unroll
-      for (int jb = 0; jb < NBT; jb += GRP) {
-        float ww[GRP];
-        float2 y0[GRP], y1[GRP];
-        uint32_t fr[GRP];
-#pragma unroll
-        for (int jj = 0; jj < GRP; ++jj) {
-          const int i = (jb + jj) * kFftThreads + tid;
+        for (int j = 0; j < NBT; ++j) {
+          const int i = j * kFftThreads + tid;
           const int ic = i < L.nb ? i : L.nb - 1;
-          ww[jj] = wts[ic] * gain;
-          y0[jj] = q0[ic];
-          y1[jj] = q1[ic];
-          fr[jj] = i < L.nb ? (uint32_t)fold[ic] : 0xffffu;  // 0xff: no round matches
+          ww[j] = wts[ic] * gain;
+          y0[j] = q0[ic];
+          y1[j] = q1[ic];
+          fr[j] = i < L.nb ? (uint32_t)fold[ic] : 0xffffu;  // 0xff: no round matches
         }
 #pragma unroll
-        for (int jj = 0; jj < GRP; ++jj) {
-          const int j = jb + jj;
+        for (int j = 0; j < NBT; ++j) {
           float2 twj = make_float2(1.f, 0.f);
           if (MULTI) twj = cis_fast((kk[j] * b) & (P.M - 1u), P.M);
-          const float w = ww[jj];
-          const float2 z0 = cmul(make_float2(y0[jj].x * w, y0[jj].y * w), twj);
-          const float2 z1 =
-              has1 ? cmul(make_float2(y1[jj].x * w, y1[jj].y * w), twj) : make_float2(0.f, 0.f);
-          const int r = kk[j] & (Q - 1), rm = (Q - r) & (Q - 1);
-          if ((fr[jj] & 0xffu) == (uint32_t)round) {  //      z0  + j z1
-            float2 v = make_float2(z0.x - z1.y, z0.y + z1.x);
-            if (round) v = cadd(v, buf[pad(r)]);
-            buf[pad(r)] = v;
-          }
-          if ((fr[jj] >> 8) == (uint32_t)round) {     // conj z0  + j conj z1
-            float2 v = make_float2(z0.x + z1.y, z1.x - z0.y);
-            if (round) v = cadd(v, buf[pad(rm)]);
-            buf[pad(rm)] = v;
+          const float w = ww[j];
+          const float2 a0 = cmul(make_float2(y0[j].x * w, y0[j].y * w), twj);
+          const float2 a1 = has1 ? cmul(make_float2(y1[j].x * w, y1[j].y * w), twj) : make_float2(0.f, 0.f);
+          if constexpr (kKeep) {
+            z0[j] = a0;
+            z1[j] = a1;
+          } else {
+            place(j, fr[j], a0, a1, round);
           }
         }
-        if (GRP < NBT) __builtin_amdgcn_sched_barrier(0);
+      }
+      if constexpr (kKeep) {
+#pragma unroll
+        for (int j = 0; j < NBT; ++j) place(j, fr[j], z0[j], z1[j], round);
       }
       __syncthreads();
     }

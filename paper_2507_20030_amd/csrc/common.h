@@ -42,6 +42,7 @@ struct Params {
   const int32_t* bins;
   const float* weights;
   const uint16_t* fold;  // per kept bin: low byte = round of its direct slot, high byte = round of its mirror slot
+                         // (0xff: the mirror falls on the direct slot and is added in the same write)
   float2* FK;
   float2* FV;
   // Exact tokens (Sec. 4.2.1): S sink tokens and a ring of R recent tokens per slice, kv_dtype,

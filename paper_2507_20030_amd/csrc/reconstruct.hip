@@ -149,6 +149,7 @@ __global__ __launch_bounds__(kFftThreads, 4) void reconstruct_fft_kernel(Params 
           const int r = k & (Q - 1), rm = (Q - r) & (Q - 1);
           if ((fr & 0xffu) == (uint32_t)round) {  //      z0  + j z1
             float2 v = make_float2(z0.x - z1.y, z0.y + z1.x);
+            if (r == rm) v = make_float2(2.f * z0.x, 2.f * z1.x);  // ... plus the mirror term, same slot
             if (round) v = cadd(v, buf[pad(r)]);
             buf[pad(r)] = v;
           }
