@@ -192,10 +192,11 @@ def test_cfg1_direct_synthesis_path():
 
 
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
-@pytest.mark.parametrize("L,group", [(256, 2), (1024, 3), (96, 1), (2048, 8)])
+@pytest.mark.parametrize("L,group", [(256, 2), (1024, 3), (96, 1), (160, 2), (2048, 8)])
 def test_ragged_random_masks(dtype, L, group):
     # odd bin counts (ragged rows), scattered bins (folding collisions), batch > 1, odd group size,
-    # non-power-of-two M (direct synthesis), wrap-around of the slot shift (steps > 0 with small M)
+    # non-power-of-two M (direct synthesis), wrap-around of the slot shift (steps > 0 with small M);
+    # 96 and 160 tokens: a ragged last tile and an odd number of 64-token tiles in the dense prefill
     cfg = small_cfg(L=L, group=group, dtype=dtype, n_bins=min(77, L // 2 + 5))
     run_stream(cfg, random_bins(cfg, 11), rec=(3, 50), tag=f"ragged-{dtype}-L{L}-G{group}")
 

@@ -87,7 +87,8 @@ def test_ablate_chunk_argument_errors_need_no_gpu():
 @pytest.mark.parametrize("M,C,chunks", [(256, 22, (0, 7, 21)), (512, 5, (2,)), (1024, 22, (0, 11)), (2048, 1, (0,)),
                                         (4096, 22, (3,)), (8192, 22, (0, 10, 21)),
                                         # longer than one in-LDS transform: the subtractive form, in pieces
-                                        (16384, 1, (0,)), (16384, 3, (0, 2)), (32768, 22, (0, 10, 21))])
+                                        (16384, 1, (0,)), (16384, 3, (0, 2)), (32768, 22, (0, 10, 21)),
+                                        (131072, 22, (7,))])   # the study's chunking at the longest baseline context
 def test_ablate_chunk_matches_the_oracle(dtype, M, C, chunks):
     dev = "cuda:0"
     g = torch.Generator(device=dev).manual_seed(M + C)
