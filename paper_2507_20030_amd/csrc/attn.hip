@@ -486,11 +486,12 @@ __global__ __launch_bounds__(kOutThreads) void attn_out_kernel(Params P, const f
 }
 
 // ------------------------------------------------------------------------------------- B (FFT)
-// Block-wide max / sum of two values at once (one per packed query head).
+// Block-wide max / sum of two values at once (one per packed query head).  One barrier each: the two use
+// different scratch rows and always alternate, so the barrier of the one separates the reads of the other from
+// its next writes.
 __device__ __forceinline__ float2 block_max2(float2 v, float2* scratch, int tid) {
   v.x = wave_max(v.x);
   v.y = wave_max(v.y);
-  __syncthreads();
   if ((tid & 63) == 0) scratch[tid >> 6] = v;
   __syncthreads();
   float2 r = scratch[0];
@@ -503,13 +504,12 @@ __device__ __forceinline__ float2 block_max2(float2 v, float2* scratch, int tid)
 __device__ __forceinline__ float2 block_sum2(float2 v, float2* scratch, int tid) {
   v.x = wave_sum(v.x);
   v.y = wave_sum(v.y);
+  if ((tid & 63) == 0) scratch[kFftThreads / 64 + (tid >> 6)] = v;
   __syncthreads();
-  if ((tid & 63) == 0) scratch[tid >> 6] = v;
-  __syncthreads();
-  float2 r = scratch[0];
+  float2 r = scratch[kFftThreads / 64];
   for (int w = 1; w < kFftThreads / 64; ++w) {
-    r.x += scratch[w].x;
-    r.y += scratch[w].y;
+    r.x += scratch[kFftThreads / 64 + w].x;
+    r.y += scratch[kFftThreads / 64 + w].y;
   }
   return r;
 }
@@ -532,7 +532,7 @@ __global__ __launch_bounds__(kFftThreads, (MULTI && NBT > 4) ? 2 : 4) void attn_
                                                                  float scale, int pairs, int np, uint32_t ptsh,
                                                                  float* __restrict__ ps) {
   extern __shared__ float2 smem[];
-  __shared__ float2 scratch[kFftThreads / 64];
+  __shared__ float2 scratch[2 * (kFftThreads / 64)];  // row 0: block_max2, row 1: block_sum2
   __shared__ float pscr[kFftThreads / 64][2 * kMaxPend];
   const int tid = threadIdx.x;
   constexpr int Q = 1 << LOGQ;
@@ -680,7 +680,8 @@ __global__ __launch_bounds__(kFftThreads, (MULTI && NBT > 4) ? 2 : 4) void attn_
     }
     const float2 bm = block_max2(lm, scratch, tid);
     const float2 mn = make_float2(fmaxf(mx.x, bm.x), fmaxf(mx.y, bm.y));
-    const float2 f = make_float2(exp2f(mx.x - mn.x), exp2f(mx.y - mn.y));  // exp2(-inf) = 0 first time
+    // exp2(-inf) = 0 the first time
+    const float2 f = make_float2(__builtin_amdgcn_exp2f(mx.x - mn.x), __builtin_amdgcn_exp2f(mx.y - mn.y));
     mx = mn;
     float2 ls = make_float2(0.f, 0.f);
 #pragma unroll
@@ -702,7 +703,7 @@ __global__ __launch_bounds__(kFftThreads, (MULTI && NBT > 4) ? 2 : 4) void attn_
         buf[pad(2 * bf + 1)] = c;
       }
     }
-    const float2 bs = block_sum2(ls, scratch, tid);  // its barriers also publish the writes above
+    const float2 bs = block_sum2(ls, scratch, tid);  // its barrier also publishes the writes above
     Z = make_float2(Z.x * f.x + bs.x, Z.y * f.y + bs.y);
     fft_dit<LOGQ>(buf, tab, lt);
 #pragma unroll
