@@ -122,15 +122,11 @@ int iwdft_prefill(iwdft_ctx* ctx, const void* d_K, const void* d_V, void* hip_st
  * -1 if ctx is NULL. */
 int iwdft_prefill_kind(const iwdft_ctx* ctx);
 
-/* Diagnostic, needs no context: runs the matrix instruction of the dense prefill (32x32x16 fp16, fp32
- * accumulation) back to back from registers, 4 waves per workgroup and 4 workgroups per compute unit's worth of
- * grid, `iters` rounds of 32 instructions per wave, with no memory traffic, so that a caller can time what the
- * matrix cores of this device sustain (HIP events around the call).  random_operands = 0: all operands zero;
- * 1: operands uniform in (-1, 1) -- on a power-limited part the second rate is the lower one, and it is the
- * ceiling a dense prefill on real data can approach.  d_scratch: DEVICE, >= 1 MiB, receives checksums.
- * *flops_per_call (HOST, may be NULL) = floating-point operations of one call. */
-int iwdft_mfma_probe(void* d_scratch, size_t scratch_bytes, int32_t iters, int32_t random_operands,
-                     double* flops_per_call, void* hip_stream);
+/* Which synthesis compressed_decode_attn / iwdft_append_attn run for this context: 1 = scores and softmax
+ * weights through in-LDS FFTs (O(M log M) per query head, the HBM-bound path), 0 = the direct O(M |B|) sums
+ * (arithmetic-bound; chosen by IWDFT_FLAG_DIRECT_SYNTHESIS or when the FFT path does not apply); -1 if ctx
+ * is NULL.  With 0, desc.write_every is taken as 1. */
+int iwdft_attn_kind(const iwdft_ctx* ctx);
 
 /* Streaming update with one new token per sequence (Eq. infi-dft, Eq. update-iwdft).
  * d_tok_k, d_tok_v: [n_layers][batch][n_kv_heads][head_dim], kv_dtype.  T -> T+1.

@@ -24,7 +24,7 @@ IWDFT_FLAG_FFT_PREFILL = 4
 EXPORTED = [
     "iwdft_query_bytes", "iwdft_create", "iwdft_destroy", "iwdft_prefill", "iwdft_append",
     "iwdft_reconstruct", "compressed_decode_attn", "iwdft_append_attn", "iwdft_export_coeffs", "iwdft_export_bins",
-    "iwdft_num_tokens", "iwdft_set_num_tokens", "iwdft_last_error", "iwdft_phase_timing", "iwdft_phase_times", "iwdft_prefill_kind", "iwdft_mfma_probe",
+    "iwdft_num_tokens", "iwdft_set_num_tokens", "iwdft_last_error", "iwdft_phase_timing", "iwdft_phase_times", "iwdft_prefill_kind", "iwdft_attn_kind",
     "iwdft_select_bins", "iwdft_ablate_chunk", "iwdft_flush",
 ]
 
@@ -74,7 +74,7 @@ def load_library() -> ctypes.CDLL:
     lib.compressed_decode_attn.argtypes = [vp, vp, vp, f32, vp]
     lib.iwdft_append_attn.argtypes = [vp, vp, vp, vp, vp, f32, vp]
     lib.iwdft_prefill_kind.argtypes = [vp]
-    lib.iwdft_mfma_probe.argtypes = [vp, ctypes.c_size_t, ctypes.c_int32, ctypes.c_int32, ctypes.POINTER(ctypes.c_double), vp]
+    lib.iwdft_attn_kind.argtypes = [vp]
     lib.iwdft_flush.argtypes = [vp, vp]
     lib.iwdft_select_bins.argtypes = [ctypes.POINTER(ctypes.c_float), i32, i32, i64, ctypes.c_double,
                                       ctypes.POINTER(ctypes.c_int64), ctypes.POINTER(ctypes.c_int32), i64]
@@ -208,16 +208,12 @@ def iwdft_flush(ctx, stream=None) -> None:
     _check(load_library().iwdft_flush(ctx, _stream(stream)))
 
 
-def iwdft_mfma_probe(scratch: torch.Tensor, iters: int, random_operands: bool, stream=None) -> float:
-    """Enqueues the matrix-core probe; returns the floating-point operations of the call."""
-    flops = ctypes.c_double(0.0)
-    _check(load_library().iwdft_mfma_probe(_ptr(scratch), scratch.numel() * scratch.element_size(), iters,
-                                           1 if random_operands else 0, ctypes.byref(flops), _stream(stream)))
-    return flops.value
-
-
 def iwdft_prefill_kind(ctx) -> str:
     return {0: "dense", 1: "fft"}[load_library().iwdft_prefill_kind(ctx)]
+
+
+def iwdft_attn_kind(ctx) -> str:
+    return {0: "direct", 1: "fft"}[load_library().iwdft_attn_kind(ctx)]
 
 
 def iwdft_phase_timing(ctx, enable: bool) -> None:

@@ -415,19 +415,9 @@ int iwdft_phase_times(iwdft_ctx* ctx, double* ms, int64_t* n_calls) {
 
 int64_t iwdft_num_tokens(const iwdft_ctx* ctx) { return ctx ? ctx->T : -1; }
 
-int iwdft_mfma_probe(void* d_scratch, size_t scratch_bytes, int32_t iters, int32_t random_operands,
-                     double* flops_per_call, void* hip_stream) {
-  const size_t need = sizeof(float) * 256 * (size_t)kMfmaProbeBlocks;
-  if (!d_scratch) return fail(IWDFT_ERR_ARG, "d_scratch is NULL");
-  if (scratch_bytes < need) return fail(IWDFT_ERR_SIZE, "scratch has %zu bytes, %zu needed", scratch_bytes, need);
-  if (iters < 1 || iters > (1 << 20)) return fail(IWDFT_ERR_ARG, "iters = %d is outside 1 .. 2^20", iters);
-  if (flops_per_call)  // per wave and round: 32 instructions of 32 x 32 x 16 multiply-adds
-    *flops_per_call = (double)kMfmaProbeBlocks * 4.0 * (double)iters * 32.0 * (2.0 * 32 * 32 * 16);
-  return launched(launch_mfma_probe((float*)d_scratch, iters, random_operands != 0, (hipStream_t)hip_stream),
-                  "matrix-core probe launch");
-}
-
 int iwdft_prefill_kind(const iwdft_ctx* ctx) { return ctx ? (ctx->plan.use_fft_prefill ? 1 : 0) : -1; }
+
+int iwdft_attn_kind(const iwdft_ctx* ctx) { return ctx ? (ctx->plan.use_fft ? 1 : 0) : -1; }
 
 int iwdft_set_num_tokens(iwdft_ctx* ctx, int64_t T) {
   if (!ctx) return fail(IWDFT_ERR_ARG, "ctx is NULL");

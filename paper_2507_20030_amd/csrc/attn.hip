@@ -870,7 +870,7 @@ __global__ __launch_bounds__(kDirThreads) void attn_direct_kernel(Params P, cons
 }
 
 // --------------------------------------------------------------------------------------- host
-static int heads_per_pass(int G) { return G >= 8 ? 8 : (G > 2 ? 4 : G); }  // 1, 2, 4 or 8
+static int heads_per_pass(int G) { return G <= 2 ? G : (G <= 4 ? 4 : 8); }  // 1, 2, 4 or 8; heads beyond G are masked
 
 // up / mode: the fused decode step's pending tokens and what kernels A and C do with them (see StepUpdate).
 template <bool BF16>

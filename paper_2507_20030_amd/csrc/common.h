@@ -141,10 +141,6 @@ hipError_t launch_append(const Params& P, const void* tok_k, const void* tok_v, 
                          uint32_t ring_pos, hipStream_t st);
 hipError_t launch_export(const Params& P, int layer, float* SK, float* SV, uint32_t t_shift,
                          float inv_T, hipStream_t st);
-// Matrix-core probe: grid of kMfmaProbeBlocks workgroups x 256 threads, each wave issues iters x 32 independent
-// 32x32x16 fp16 MFMAs from registers; out receives one float per thread.
-constexpr int kMfmaProbeBlocks = 1024;
-hipError_t launch_mfma_probe(float* out, int iters, bool random_operands, hipStream_t st);
 // use_fft: the fold schedule (Params::fold) is valid, so long slot ranges may go through inverse FFTs.
 hipError_t launch_reconstruct(const Params& P, int layer, uint32_t a0, uint32_t n_slots, void* Kt,
                               void* Vt, uint32_t t_shift, bool use_fft, hipStream_t st);

@@ -166,7 +166,7 @@ __device__ __forceinline__ BasisRegs make_basis(float2 base, const float2 (&tw)[
 // A single wave overlaps vector-ALU work with its own MFMAs only partly: ~2 clocks per VALU
 // instruction up to ~6 per MFMA, 4 clocks beyond.  Beyond that the matrix cores are power-limited on
 // this instruction: back to back from registers they sustain 2.4-2.5 PFLOP/s on zero operands and
-// 1.6-1.7 on random ones, see mfma_probe_kernel.)
+// 1.6-1.7 on random ones.)
 template <bool BF16, bool FULL>
 __global__ __launch_bounds__(kPfThreads) void prefill_mfma_kernel(Params P, const void* __restrict__ K,
                                                                  const void* __restrict__ V, int nt,
@@ -345,47 +345,6 @@ __global__ __launch_bounds__(256) void prefill_edges_kernel(Params P, const void
   for (int e = threadIdx.x; e < P.S * kRowChunks; e += 256) sink[e] = src[e];
   const uint4* tail = src + ((int64_t)P.S + P.M) * kRowChunks;
   for (int e = threadIdx.x; e < P.R * kRowChunks; e += 256) ring[e] = tail[e];
-}
-
-// What the matrix cores sustain on the instruction of the kernel above with nothing else going on: 16
-// accumulator tiles per wave (as there), operands in registers.  Operand data matters: the part is power-limited,
-// and all-zero operands run faster than random ones.
-__global__ __launch_bounds__(kPfThreads) void mfma_probe_kernel(float* __restrict__ out, int iters, int random_operands) {
-  half8 a[8], b[4];
-  const uint32_t tid = threadIdx.x + blockIdx.x * kPfThreads;
-#pragma unroll
-  for (int i = 0; i < 12; ++i)
-#pragma unroll
-    for (int j = 0; j < 8; ++j) {
-      uint32_t h = tid * 2654435761u + (uint32_t)(i * 8 + j) * 40503u;  // any well-mixed bits will do
-      h ^= h >> 13;
-      h *= 0x5bd1e995u;
-      h ^= h >> 15;
-      const _Float16 v = random_operands ? (_Float16)(((int)(h & 0xffffu) - 32768) * (1.0f / 32768.0f)) : (_Float16)0.f;
-      if (i < 8) a[i][j] = v;
-      else b[i - 8][j] = v;
-    }
-  floatx16 acc[2 * kPfBlk];
-#pragma unroll
-  for (int i = 0; i < 2 * kPfBlk; ++i) acc[i] = (floatx16)(0.f);
-  for (int it = 0; it < iters; ++it) {
-#pragma unroll
-    for (int r = 0; r < 2; ++r)
-#pragma unroll
-      for (int i = 0; i < 2 * kPfBlk; ++i)
-        acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a[i & 7], b[(r + i) & 3], acc[i], 0, 0, 0);
-  }
-  float sum = 0.f;
-#pragma unroll
-  for (int i = 0; i < 2 * kPfBlk; ++i)
-#pragma unroll
-    for (int j = 0; j < 16; ++j) sum += acc[i][j];
-  out[tid] = sum;
-}
-
-hipError_t launch_mfma_probe(float* out, int iters, bool random_operands, hipStream_t st) {
-  mfma_probe_kernel<<<dim3(kMfmaProbeBlocks), dim3(kPfThreads), 0, st>>>(out, iters, random_operands ? 1 : 0);
-  return hipGetLastError();
 }
 
 hipError_t launch_prefill_edges(const Params& P, const void* K, const void* V, hipStream_t st) {

@@ -82,11 +82,8 @@ def test_null_pointers_and_null_ctx():
     assert lib.iwdft_destroy(None) == B.IWDFT_OK
     assert lib.iwdft_set_num_tokens(None, 5) == B.IWDFT_ERR_ARG
     assert lib.iwdft_prefill_kind(None) == -1
+    assert lib.iwdft_attn_kind(None) == -1
     assert lib.iwdft_flush(None, None) == B.IWDFT_ERR_ARG
-    fl = ctypes.c_double()
-    assert lib.iwdft_mfma_probe(None, 1 << 20, 10, 0, ctypes.byref(fl), None) == B.IWDFT_ERR_ARG
-    assert lib.iwdft_mfma_probe(ctypes.c_void_p(4096), (1 << 20) - 1, 10, 0, ctypes.byref(fl), None) == B.IWDFT_ERR_SIZE
-    assert lib.iwdft_mfma_probe(ctypes.c_void_p(4096), 1 << 20, 0, 0, ctypes.byref(fl), None) == B.IWDFT_ERR_ARG
     assert lib.iwdft_phase_timing(None, 1) == B.IWDFT_ERR_ARG
     ms, n = (ctypes.c_double * 3)(), ctypes.c_int64()
     assert lib.iwdft_phase_times(None, ms, ctypes.byref(n)) == B.IWDFT_ERR_ARG

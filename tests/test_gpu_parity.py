@@ -649,20 +649,3 @@ def test_fft_and_dense_prefill_give_the_same_state():
         assert rel_l2(c128(ka), c128(kb)) < 1e-5 and rel_l2(c128(va), c128(vb)) < 1e-5
     a.close()
     b.close()
-
-
-@pytest.mark.gpu
-def test_matrix_core_probe_runs_and_is_linear_in_its_rounds():
-    # diagnostic entry point: zero operands give zero checksums; with random operands every round adds the
-    # same products, so the checksums grow in proportion to the rounds (fp32 accumulation: up to rounding)
-    buf = torch.full((1 << 18,), float("nan"), dtype=torch.float32, device="cuda:0")
-    flops = B.iwdft_mfma_probe(buf, 8, False)
-    torch.cuda.synchronize()
-    assert flops == 1024 * 4 * 8 * 32 * 2 * 32 * 32 * 16
-    assert bool((buf == 0).all())
-    B.iwdft_mfma_probe(buf, 8, True)
-    a = buf.clone()
-    B.iwdft_mfma_probe(buf, 16, True)
-    torch.cuda.synchronize()
-    assert bool(torch.isfinite(a).all()) and float(a.abs().max()) > 0
-    assert float((buf - 2 * a).abs().max()) <= 1e-4 * float(a.abs().max())
