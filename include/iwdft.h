@@ -151,6 +151,21 @@ int iwdft_reconstruct(iwdft_ctx* ctx, int32_t layer, int64_t a0, int64_t n_slots
 int compressed_decode_attn(iwdft_ctx* ctx, const void* d_q, void* d_out, float scale,
                            void* hip_stream);
 
+/* compressed_decode_attn for callers that cannot allocate device memory or hand over a workspace at the time
+ * of the call (code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc): the same
+ * kernels and the same result, but the intermediate arrays (the q.F_K rows, the softmax-weight rows, the scores
+ * of the exact tokens; the score rows of the direct synthesis) live in a scratch array that is part of the
+ * library's code object -- IWDFT_STATIC_SCRATCH_BYTES per GPU, held until the process ends -- instead of the
+ * context's workspace.  Calls no hipMalloc / hipFree or any other allocating routine.  Returns IWDFT_ERR_SIZE
+ * when the context needs more than the scratch holds: 16 * sum over layers of batch * n_q_heads * Bp_l bytes
+ * (Bp_l = kept bins of layer l rounded up to 32) + 4 * n_layers * batch * n_q_heads * (S + R) bytes, each part
+ * rounded up to 256 (+ 4 * M bytes per query head with the direct synthesis).  All calls on one GPU share that
+ * GPU's array: calls that overlap in time on one GPU (different streams or contexts) race; calls ordered on one
+ * stream do not.  Nothing in the array needs to survive between calls. */
+#define IWDFT_STATIC_SCRATCH_BYTES (64u << 20)
+int compressed_decode_attn_static(iwdft_ctx* ctx, const void* d_q, void* d_out, float scale,
+                                  void* hip_stream);
+
 /* One decode step: iwdft_append(tok) followed by compressed_decode_attn(q) (the three operations
  * of the decoding stage, Sec. 4.2.2), fused: each K coefficient is updated (Eq. infi-dft) on its
  * way into the scores and each V coefficient on its way into the output, so every coefficient is

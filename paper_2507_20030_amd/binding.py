@@ -20,12 +20,13 @@ IWDFT_F32, IWDFT_BF16 = 0, 1
 IWDFT_FLAG_DIRECT_SYNTHESIS = 1
 IWDFT_FLAG_DENSE_PREFILL = 2
 IWDFT_FLAG_FFT_PREFILL = 4
+IWDFT_STATIC_SCRATCH_BYTES = 64 << 20
 
 EXPORTED = [
     "iwdft_query_bytes", "iwdft_create", "iwdft_destroy", "iwdft_prefill", "iwdft_append",
     "iwdft_reconstruct", "compressed_decode_attn", "iwdft_append_attn", "iwdft_export_coeffs", "iwdft_export_bins",
     "iwdft_num_tokens", "iwdft_set_num_tokens", "iwdft_last_error", "iwdft_phase_timing", "iwdft_phase_times", "iwdft_prefill_kind", "iwdft_attn_kind",
-    "iwdft_select_bins", "iwdft_ablate_chunk", "iwdft_flush",
+    "iwdft_select_bins", "iwdft_ablate_chunk", "iwdft_flush", "compressed_decode_attn_static",
 ]
 
 LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libiwdft.so")
@@ -72,6 +73,7 @@ def load_library() -> ctypes.CDLL:
     lib.iwdft_append.argtypes = [vp, vp, vp, vp]
     lib.iwdft_reconstruct.argtypes = [vp, i32, i64, i64, vp, vp, vp]
     lib.compressed_decode_attn.argtypes = [vp, vp, vp, f32, vp]
+    lib.compressed_decode_attn_static.argtypes = [vp, vp, vp, f32, vp]
     lib.iwdft_append_attn.argtypes = [vp, vp, vp, vp, vp, f32, vp]
     lib.iwdft_prefill_kind.argtypes = [vp]
     lib.iwdft_attn_kind.argtypes = [vp]
@@ -172,6 +174,10 @@ def iwdft_reconstruct(ctx, layer: int, a0: int, n_slots: int, Kt, Vt, stream=Non
 
 def compressed_decode_attn(ctx, q: torch.Tensor, out: torch.Tensor, scale: float = 0.0, stream=None) -> None:
     _check(load_library().compressed_decode_attn(ctx, _ptr(q), _ptr(out), scale, _stream(stream)))
+
+
+def compressed_decode_attn_static(ctx, q: torch.Tensor, out: torch.Tensor, scale: float = 0.0, stream=None) -> None:
+    _check(load_library().compressed_decode_attn_static(ctx, _ptr(q), _ptr(out), scale, _stream(stream)))
 
 
 def iwdft_append_attn(ctx, tok_k, tok_v, q, out, scale: float = 0.0, stream=None) -> None:

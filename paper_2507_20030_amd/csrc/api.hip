@@ -6,6 +6,7 @@
 #include <cstdio>
 #include <cstring>
 #include <memory>
+#include <mutex>
 #include <new>
 #include <vector>
 
@@ -13,6 +14,12 @@
 #include "common.h"
 
 using namespace iwdft;
+
+// Library-owned scratch of compressed_decode_attn_static: one copy per GPU, allocated by the loader with the
+// code object and held until the process ends.  Host code never uses this name as an address (it is a host-side
+// stand-in); the per-device address comes from hipGetSymbolAddress, see static_scratch().
+constexpr size_t kStaticScratchBytes = (size_t)IWDFT_STATIC_SCRATCH_BYTES;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
 
 namespace {
 
@@ -228,6 +235,25 @@ int launched(hipError_t e, const char* what) {
   return IWDFT_OK;
 }
 
+// Device address of this GPU's copy of `scratch`, looked up once per device with that device current.
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mu;
+void* g_scratch_ptr[kMaxDevices] = {};
+
+int static_scratch(int dev, char** out) {
+  if (dev < 0 || dev >= kMaxDevices) return fail(IWDFT_ERR_UNSUPPORTED, "device index %d beyond %d", dev, kMaxDevices - 1);
+  std::lock_guard<std::mutex> lock(g_scratch_mu);
+  if (!g_scratch_ptr[dev]) {
+    void* p = nullptr;
+    const hipError_t e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+    if (e != hipSuccess || !p)
+      return fail(IWDFT_ERR_HIP, "hipGetSymbolAddress(scratch) on device %d: %s", dev, hipGetErrorString(e));
+    g_scratch_ptr[dev] = p;
+  }
+  *out = (char*)g_scratch_ptr[dev];
+  return IWDFT_OK;
+}
+
 // Next set of phase events of a timed call (created on demand), or null when timing is off.
 int next_marks(iwdft_ctx* c, const PhaseEvents** out) {
   try {
@@ -318,6 +344,10 @@ int iwdft_create(const iwdft_desc* desc, void* d_state, size_t state_bytes, void
     c->state = (char*)d_state;
     c->ws = (char*)d_workspace;
     if (hipGetDevice(&c->device) != hipSuccess) { return fail(IWDFT_ERR_HIP, "hipGetDevice failed"); }
+    {  // set-up of compressed_decode_attn_static: this device's scratch address (a failure is reported by that call)
+      char* unused = nullptr;
+      (void)static_scratch(c->device, &unused);
+    }
 
     // Device copies of geometry, bins and weights live at the head of the state buffer.
     std::vector<float> w((size_t)pl.n_bins_total, 1.0f);
@@ -510,6 +540,33 @@ int compressed_decode_attn(iwdft_ctx* ctx, const void* d_q, void* d_out, float s
                               (float*)(ctx->ws + pl.off_direct),
                               pl.use_fft, marks, (hipStream_t)hip_stream),
                   "decode attention launch");
+}
+
+int compressed_decode_attn_static(iwdft_ctx* ctx, const void* d_q, void* d_out, float scale, void* hip_stream) {
+  int rc = check_ctx(ctx);
+  if (rc != IWDFT_OK) return rc;
+  if (!d_q || !d_out) return fail(IWDFT_ERR_ARG, "d_q / d_out is NULL");
+  if (ctx->T < ctx->desc.M) return fail(IWDFT_ERR_STATE, "compressed_decode_attn_static before iwdft_prefill");
+  if (!std::isfinite(scale)) return fail(IWDFT_ERR_ARG, "scale is not finite");
+  if (scale <= 0.0f) scale = 1.0f / std::sqrt((float)ctx->desc.head_dim);
+  const Plan& pl = ctx->plan;
+  // Same arrays as the workspace form, laid out inside the library's scratch: qc | Pn | pe | direct scores.
+  const size_t n_heads = (size_t)ctx->P.n_slices * (size_t)pl.G;
+  const size_t rows = align256(sizeof(float2) * (size_t)pl.ws_total);
+  const size_t pe_bytes = align256(sizeof(float) * n_heads * (size_t)(ctx->P.S + ctx->P.R));
+  const size_t direct_bytes = pl.use_fft ? 0 : align256(sizeof(float) * n_heads * (size_t)ctx->desc.M);
+  const size_t need = 2 * rows + pe_bytes + direct_bytes;
+  if (need > kStaticScratchBytes)
+    return fail(IWDFT_ERR_SIZE, "compressed_decode_attn_static needs %zu bytes of scratch, the library holds %zu", need,
+                kStaticScratchBytes);
+  char* sc = nullptr;
+  if ((rc = static_scratch(ctx->device, &sc)) != IWDFT_OK) return rc;
+  if ((rc = flush_pending(ctx, (hipStream_t)hip_stream)) != IWDFT_OK) return rc;
+  // Every entry of the four arrays is written by the kernels before it is read, so nothing needs clearing
+  // although the scratch still holds the previous call's contents.
+  return launched(launch_attn(ctx->P, d_q, d_out, scale, (float2*)sc, (float2*)(sc + rows), (float*)(sc + 2 * rows),
+                              (float*)(sc + 2 * rows + pe_bytes), pl.use_fft, nullptr, (hipStream_t)hip_stream),
+                  "decode attention launch (static scratch)");
 }
 
 int iwdft_append_attn(iwdft_ctx* ctx, const void* d_tok_k, const void* d_tok_v, const void* d_q, void* d_out,

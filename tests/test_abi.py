@@ -109,3 +109,22 @@ def test_query_bytes_grows_with_exact_windows():
     # 4 slices x (10 + 50) tokens x 128 channels x 2 B (bf16), K and V
     assert s1 - s0 >= 2 * 4 * 60 * 128 * 2 and s1 - s0 < 2 * 4 * 60 * 128 * 2 + 2048
     assert w1 > w0
+
+
+def test_static_scratch_symbol_is_visible_to_the_hip_runtime(tmp_path):
+    """The HIP runtime finds a registered device variable by name in the code object and aborts the process
+    when it is missing, so the library's file-scope scratch array must be a GLOBAL symbol of the device code."""
+    import shutil
+    import subprocess
+    obj = os.path.join(os.path.dirname(B.LIB_PATH), "_build", "api.o")
+    tools = "/opt/rocm/llvm/bin"
+    if not (os.path.exists(obj) and os.path.exists(f"{tools}/clang-offload-bundler") and shutil.which("objcopy")):
+        pytest.skip("object file or LLVM tools not available")
+    fat, co = str(tmp_path / "fat.bin"), str(tmp_path / "dev.co")
+    subprocess.run(["objcopy", "-O", "binary", "--only-section=.hip_fatbin", obj, fat], check=True)
+    subprocess.run([f"{tools}/clang-offload-bundler", "--unbundle", "--type=o", f"--input={fat}",
+                    "--targets=hipv4-amdgcn-amd-amdhsa--gfx950", f"--output={co}"], check=True)
+    syms = subprocess.run([f"{tools}/llvm-readelf", "-s", co], check=True, capture_output=True, text=True).stdout
+    rows = [ln.split() for ln in syms.splitlines() if ln.strip().endswith("scratch")]
+    assert rows, "no scratch symbol in the device code object"
+    assert all(r[4] == "GLOBAL" and int(r[2]) == B.IWDFT_STATIC_SCRATCH_BYTES for r in rows), rows

@@ -1,0 +1,76 @@
+"""compressed_decode_attn_static (library-owned scratch, no workspace, no allocation) against
+compressed_decode_attn on the same contexts: two calls in a row, the second on a smaller input, so the
+second call finds the first call's contents in the shared scratch."""
+import ctypes
+
+import numpy as np
+import pytest
+import torch
+
+from paper_2507_20030_amd import binding as B
+from paper_2507_20030_amd import workload as wl
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+
+def _ready_cache(cfg, flags=0):
+    bins = wl.layer_bins(cfg)
+    K, V = wl.prefill_tensors(cfg, DEV)
+    cache = B.Cache(cfg.n_layers, cfg.batch, cfg.n_kv_heads, cfg.n_q_heads, cfg.head_dim, cfg.torch_dtype,
+                    cfg.L, bins, None, flags, DEV, n_sink=cfg.n_sink, n_recent=cfg.n_recent)
+    cache.prefill(K, V)
+    for i in range(3):
+        tk, tv, _ = wl.decode_step(cfg, i, DEV)
+        cache.append(tk, tv)
+    return cache
+
+
+def _both(cache, cfg, step):
+    _, _, q = wl.decode_step(cfg, step, DEV)
+    ref = torch.full_like(q, float("nan"))
+    got = torch.full_like(q, float("nan"))
+    B.compressed_decode_attn(cache.ctx, q, ref)
+    lib = B.load_library()
+    rc = lib.compressed_decode_attn_static(cache.ctx, ctypes.c_void_p(q.data_ptr()), ctypes.c_void_p(got.data_ptr()),
+                                           ctypes.c_float(0.0), ctypes.c_void_p(torch.cuda.current_stream().cuda_stream))
+    assert rc == B.IWDFT_OK, B.iwdft_last_error()
+    torch.cuda.synchronize()
+    assert bool(torch.isfinite(ref.float()).all())
+    # same kernels on the same inputs: the two outputs agree bit for bit (far inside the 2e-2 / 1e-4 bars)
+    assert torch.equal(got.view(torch.int16 if got.dtype == torch.bfloat16 else torch.int32),
+                       ref.view(torch.int16 if ref.dtype == torch.bfloat16 else torch.int32))
+    return got
+
+
+def test_static_scratch_matches_workspace_form_twice_second_call_smaller():
+    big = wl.Config("na_big", 3, 2, 4, 4, 128, 4096, 1500, 4, "bf16", "mixed", n_sink=4, n_recent=9, seed=11)
+    small = wl.Config("na_small", 2, 1, 2, 3, 128, 512, 77, 4, "f32", "low", seed=12)
+    c_big, c_small = _ready_cache(big), _ready_cache(small)
+    _both(c_big, big, 5)
+    _both(c_small, small, 5)      # smaller input right after: stale contents of the first call lie beyond and inside
+    _both(c_big, big, 6)
+    c_big.close()
+    c_small.close()
+
+
+def test_static_scratch_direct_synthesis_and_size_limit():
+    small = wl.Config("na_dir", 1, 1, 2, 2, 128, 96, 40, 2, "f32", "low", seed=13)   # M not a power of two
+    c = _ready_cache(small)
+    assert B.iwdft_attn_kind(c.ctx) == "direct"
+    _both(c, small, 3)
+    c.close()
+    # a context whose rows exceed the library's scratch is refused with IWDFT_ERR_SIZE before any launch
+    huge = wl.Config("na_huge", 8, 8, 8, 8, 128, 8192, 2048, 1, "bf16", "low", seed=14)
+    bins = wl.layer_bins(huge)
+    need = 16 * huge.n_layers * huge.batch * huge.n_q_heads * 2048
+    assert need > B.IWDFT_STATIC_SCRATCH_BYTES
+    cache = B.Cache(huge.n_layers, huge.batch, huge.n_kv_heads, huge.n_q_heads, huge.head_dim, huge.torch_dtype,
+                    huge.L, bins, device=DEV)
+    K = torch.zeros((huge.n_layers, huge.batch, huge.n_kv_heads, huge.L, 128), dtype=torch.bfloat16, device=DEV)
+    cache.prefill(K, K)
+    q = torch.zeros((huge.n_layers, huge.batch, huge.n_q_heads, 128), dtype=torch.bfloat16, device=DEV)
+    with pytest.raises(B.IwdftError) as ei:
+        B.compressed_decode_attn_static(cache.ctx, q, torch.empty_like(q))
+    assert ei.value.code == B.IWDFT_ERR_SIZE
+    cache.close()
