@@ -27,40 +27,131 @@ def test_cfg5_wide_outlier_channels():
     run_stream(cfg, wl.layer_bins(cfg), steps=2, slices=wl.sample_slices(cfg, 6), tag="cfg5")
 
 
-def test_cfg5_fused_steps_with_deferred_write_back():
+def test_cfg5_full_length_fused_deferred_write_back():
+    """All 128 decode steps of cfg5 in the launch configuration the benchmark times (fused step, coefficients
+    written back every 16th step: 8 write-backs), attention checked at every step on 4 slices."""
     cfg = wl.CONFIGS["cfg5"]
-    run_stream(cfg, wl.layer_bins(cfg), steps=5, slices=wl.sample_slices(cfg, 6), fused=True, write_every=4,
-               tag="cfg5-fused-J4")
+    run_stream(cfg, wl.layer_bins(cfg), slices=wl.sample_slices(cfg, 4), fused=True, write_every=16,
+               tag="cfg5-fused-J16-full")
 
 
-def test_cfg4_long_context_drift():
-    """1024 streaming appends with decode attention at every step; coefficients are compared with
-    the oracle's recursion AND with its from-scratch closed form at steps 1, 16, 256, 1024."""
+def test_cfg3_fused_deferred_write_back():
+    """cfg3 in the benchmark's launch configuration: 18 fused steps, one write-back of 16 tokens at M = 32768
+    (multi-block transforms with 16 pending tokens), two tokens left deferred for the final flush."""
+    cfg = wl.CONFIGS["cfg3"]
+    run_stream(cfg, wl.layer_bins(cfg), steps=18, fused=True, write_every=16, tag="cfg3-fused-J16")
+
+
+def test_cfg2_full_length_fused_deferred_write_back():
+    """All 256 decode steps of cfg2 (16 write-backs), attention checked at every step on 2 slices."""
+    cfg = wl.CONFIGS["cfg2"]
+    run_stream(cfg, wl.layer_bins(cfg), slices=wl.sample_slices(cfg, 2), fused=True, write_every=16,
+               tag="cfg2-fused-J16-full")
+
+
+def _max_rel_l2(a, b):
+    a, b = a.float(), b.float()
+    return float((a - b).norm() / b.norm().clamp_min(1e-30))
+
+
+@pytest.mark.parametrize("name", ["cfg2", "cfg3", "cfg4", "cfg5"])
+def test_every_slice_is_tied_to_the_sampled_ones(name):
+    """GPU against GPU at full size, over ALL slices (the oracle follows only a sample): (1) the benchmark's
+    configuration -- FFT prefill, fused steps, write-back every 16th -- run twice leaves the same bytes in the state
+    buffer and returns the same outputs; (2) the two-call path on top of the dense prefill agrees with it to
+    rounding on every slice: prefill state, outputs of all 17 steps, final state after the flush."""
+    cfg = wl.CONFIGS[name]
+    bins = wl.layer_bins(cfg)
+    K, V = wl.prefill_tensors(cfg, DEV)
+    steps = [wl.decode_step(cfg, i, DEV) for i in range(17)]   # write-back at step 16, one token left deferred
+
+    def run(flags, fused, J):
+        c = make_cache(cfg, bins, flags=flags, write_every=J)
+        c.prefill(K, V)
+        pre = [tuple(t.clone() for t in c.export_coeffs(l)) for l in (0, cfg.n_layers - 1)]
+        outs = []
+        for tk, tv, q in steps:
+            if fused:
+                outs.append(c.step(tk, tv, q).clone())
+            else:
+                c.append(tk, tv)
+                outs.append(c.attend(q).clone())
+        c.flush()
+        torch.cuda.synchronize()
+        return c, pre, outs
+
+    a, pre_a, outs_a = run(B.IWDFT_FLAG_FFT_PREFILL, True, 16)
+    state_a = a.state.clone()
+    a.close()
+    del a
+    b, pre_b, outs_b = run(B.IWDFT_FLAG_FFT_PREFILL, True, 16)
+    assert torch.equal(state_a, b.state), f"{name}: two identical runs left different state bytes"
+    assert all(torch.equal(x, y) for x, y in zip(outs_a, outs_b)), f"{name}: two identical runs gave different outputs"
+    del state_a, outs_b, pre_b
+    c, pre_c, outs_c = run(B.IWDFT_FLAG_DENSE_PREFILL, False, 0)
+    worst_pre = max(_max_rel_l2(x, y) for pa, pc in zip(pre_a, pre_c) for x, y in zip(pa, pc))
+    assert worst_pre < 2e-5, f"{name}: FFT vs dense prefill coefficients differ by {worst_pre:.2e}"
+    worst_out = max(_max_rel_l2(x, y) for x, y in zip(outs_a, outs_c))
+    assert worst_out < 1e-2, f"{name}: fused/deferred vs two-call outputs differ by {worst_out:.2e}"
+    per_slice = 0.0                               # no single slice may hide behind the norm of the others
+    for x, y in zip(outs_a, outs_c):
+        d = (x.float() - y.float()).flatten(2).norm(dim=2) / y.float().flatten(2).norm(dim=2).clamp_min(1e-30)
+        per_slice = max(per_slice, float(d.max()))
+    assert per_slice < 2e-2, f"{name}: worst (layer, sequence) output difference {per_slice:.2e}"
+    worst_state = 0.0
+    for l in range(cfg.n_layers):
+        (kb, vb), (kc, vc) = b.export_coeffs(l), c.export_coeffs(l)
+        for x, y in ((kb, kc), (vb, vc)):
+            d = (x - y).flatten(2).norm(dim=2) / y.flatten(2).norm(dim=2).clamp_min(1e-30)   # per (sequence, KV head)
+            worst_state = max(worst_state, float(d.max()))
+    assert worst_state < 2e-5, f"{name}: final coefficients of some slice differ by {worst_state:.2e}"
+    print(f"\n[{name} all slices] prefill {worst_pre:.2e} outputs {worst_out:.2e} (worst slice {per_slice:.2e}) "
+          f"state {worst_state:.2e}", flush=True)
+    b.close()
+    c.close()
+
+
+@pytest.mark.parametrize("fused", [False, True])
+def test_cfg4_long_context_drift(fused):
+    """1024 streaming appends with decode attention at every step -- as two calls, and as the fused step with the
+    coefficients written back every 16th step (the configuration the benchmark times); coefficients are compared
+    with the oracle's recursion AND with its from-scratch closed form at steps 1, 16, 256, 1024 (in the deferred
+    mode after iwdft_flush: at step 1 the token is still pending)."""
     from oracle import iwdft_oracle as orc
     cfg = wl.CONFIGS["cfg4"]
     bins = wl.layer_bins(cfg)
     slices = wl.sample_slices(cfg, 4)
     K, V = wl.prefill_tensors(cfg, DEV)
-    cache = make_cache(cfg, bins)
+    cache = make_cache(cfg, bins, write_every=16 if fused else 0)
     check_masks(cache, bins)
     cache.prefill(K, V)
     ora = SliceOracle(cfg, bins, None, K, V, slices)
     f64 = lambda t: t.detach().cpu().to(torch.float64).numpy()
     hist = {s: [f64(K[s]), []] for s in slices}          # prefill K of each slice + appended rows
     del K, V
-    stats = {"coef0": check_coeffs(cache, ora, "cfg4 prefill")}
+    tag = "cfg4-fused-J16" if fused else "cfg4"
+    stats = {"coef0": check_coeffs(cache, ora, f"{tag} prefill")}
     out = None
+    G = cfg.group
     for i in range(cfg.steps):
         tk, tv, q = wl.decode_step(cfg, i, DEV)
-        cache.append(tk, tv)
-        out = cache.attend(q, out)
+        if fused:
+            out = cache.step(tk, tv, q, out)
+        else:
+            cache.append(tk, tv)
+            out = cache.attend(q, out)
         ora.append(tk, tv)
         for s in slices:
             hist[s][1].append(f64(tk[s]))
         step = i + 1
         if step in (1, 16, 256, 1024):
-            stats[f"coef{step}"] = check_coeffs(cache, ora, f"cfg4 step {step}")
-            stats[f"attn{step}"] = check_attn(cfg, cache, ora, q, f"cfg4 step {step}")
+            ref = ora.attend(q)                            # the output this very step returned
+            w = max(np.linalg.norm(f64(out[l, b, h * G:(h + 1) * G]) - r) / np.linalg.norm(r) for (l, b, h), r in ref.items())
+            assert w < 2e-2, f"{tag} step {step}: attention rel-L2 {w:.3e}"
+            stats[f"attn{step}"] = float(w)
+            if fused:
+                cache.flush()
+            stats[f"coef{step}"] = check_coeffs(cache, ora, f"{tag} step {step}")
             worst = 0.0
             SK_layers = {}
             for s in slices:
@@ -71,9 +162,9 @@ def test_cfg4_long_context_drift():
                 ref = orc.closed_form(xs, cfg.L, bins[l])
                 got = SK_layers[l][b, h].cpu().numpy().astype(np.complex128)
                 worst = max(worst, float(np.linalg.norm(got - ref) / np.linalg.norm(ref)))
-            assert worst < 1e-4, f"cfg4 step {step}: drift vs from-scratch recompute {worst:.3e}"
+            assert worst < 1e-4, f"{tag} step {step}: drift vs from-scratch recompute {worst:.3e}"
             stats[f"scratch{step}"] = worst
     assert cache.T == cfg.L + cfg.steps
-    stats["rec"] = check_reconstruct(cfg, cache, ora, cfg.L - 64, 64, "cfg4 end")
-    print("\n[cfg4] " + " ".join(f"{k}={v:.2e}" for k, v in stats.items()), flush=True)
+    stats["rec"] = check_reconstruct(cfg, cache, ora, cfg.L - 64, 64, f"{tag} end")
+    print(f"\n[{tag}] " + " ".join(f"{k}={v:.2e}" for k, v in stats.items()), flush=True)
     cache.close()
