@@ -38,7 +38,7 @@ import numpy as np
 
 __all__ = [
     "W", "prefill", "append", "append_many", "slot", "fold_to_slots",
-    "closed_form", "reconstruct", "attention", "decode_attention",
+    "closed_form", "reconstruct", "reconstruct_grid", "attention", "decode_attention",
     "stream_decode", "windowed_attention", "windowed_stream_decode",
     "chunk_bounds", "ablate_chunk", "select_bins",
     "append_shortcut", "closed_form_shortcut",
@@ -129,6 +129,19 @@ def reconstruct(S, T, M, bins, weights=None):
     full = np.zeros((M, S.shape[1]), dtype=np.complex128)
     full[bins] = (w[:, None] * float(T)) * S
     return np.fft.ifft(full, axis=0).real
+
+
+def reconstruct_grid(S, T, M, bins, a0, stride, n_out, weights=None):
+    """The reconstruction of Eq. inverse-swdft evaluated on a strided grid of time slots only,
+    a_j = a0 + j * stride, j < n_out (a compressed token set; an extension of Sec. 4.2.2, which
+    reconstructs all M slots), as the sum it is:
+    x~[a_j] = (T/M) Re sum_{k in B} w_k S_T[k] exp(+j 2 pi k a_j / M).  Returns [n_out, d]."""
+    bins = np.asarray(bins, dtype=np.int64)
+    w = np.ones(len(bins)) if weights is None else np.asarray(weights, np.float64)
+    a = a0 + stride * np.arange(n_out, dtype=np.int64)
+    assert n_out == 0 or (a0 >= 0 and a[-1] < M and stride >= 1)
+    basis = np.exp(2j * np.pi * ((a[:, None] * bins[None, :]) % M) / float(M))      # [n_out, |B|]
+    return (basis @ (w[:, None] * np.asarray(S, dtype=np.complex128))).real * (float(T) / float(M))
 
 
 def attention(q, K, V, scale=None):

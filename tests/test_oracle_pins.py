@@ -206,6 +206,38 @@ def test_one_sided_weights_give_exact_inverse():
     np.testing.assert_allclose(orc.reconstruct(orc.prefill(x, bins), M, M, bins, w), x, atol=1e-13)
 
 
+# ------------------------------------------------- reconstruction on a strided grid
+def test_reconstruct_grid_matches_brute_force_and_the_subsampled_inverse_transform():
+    M, bins = 12, [0, 1, 4, 7, 11]                       # M not a power of two, unmirrored bins
+    xs = rng(30).normal(size=(M + 5, 3))
+    S, T = orc.append_many(orc.prefill(xs[:M], bins), xs[M:], M, bins, M)
+    w = [1.0, 2.0, 0.5, 1.5, 1.0]
+    for a0, stride, n in [(0, 1, 12), (1, 3, 4), (5, 2, 3), (11, 1, 1), (0, 12, 1), (2, 5, 2), (3, 4, 0)]:
+        for ww in (None, w):
+            got = orc.reconstruct_grid(S, T, M, bins, a0, stride, n, ww)
+            assert got.shape == (n, 3)
+            slots = [a0 + j * stride for j in range(n)]
+            # scalar sums with cmath, term by term
+            www = [1.0] * len(bins) if ww is None else ww
+            for j, a in enumerate(slots):
+                for c in range(3):
+                    tot = sum(www[i] * T * S[i, c] * cmath.exp(2j * math.pi * k * a / M) for i, k in enumerate(bins))
+                    assert abs(got[j, c] - tot.real / M) < 1e-12
+            # the zero-filled inverse FFT of the full-length reconstruction, subsampled
+            np.testing.assert_allclose(got, orc.reconstruct(S, T, M, bins, ww)[slots], atol=1e-12)
+
+
+def test_reconstruct_grid_all_bins_returns_the_tokens_on_the_grid():
+    M = 32
+    x = rng(31).normal(size=(M, 2))
+    bins = np.arange(M)
+    np.testing.assert_allclose(orc.reconstruct_grid(orc.prefill(x, bins), M, M, bins, 3, 4, 7), x[3::4][:7], atol=1e-12)
+    # after appends: the folded sums of the slot map, on the grid
+    xs = rng(32).normal(size=(M + 9, 2))
+    S, T = orc.append_many(orc.prefill(xs[:M], bins), xs[M:], M, bins, M)
+    np.testing.assert_allclose(orc.reconstruct_grid(S, T, M, bins, 1, 5, 6), orc.fold_to_slots(xs, M)[1::5][:6], atol=1e-11)
+
+
 # ------------------------------------------------------------------ attention
 def test_attention_matches_library_sdpa():
     q, K, V = rng(15).normal(size=(4, 16)), rng(16).normal(size=(40, 16)), rng(17).normal(size=(40, 16))
