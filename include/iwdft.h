@@ -66,11 +66,18 @@ enum {
                                        when M is not a power of two)               */
   IWDFT_FLAG_DENSE_PREFILL = 2u,    /* iwdft_prefill always runs the dense contraction
                                        at the kept bins (matrix cores)             */
-  IWDFT_FLAG_FFT_PREFILL = 4u       /* iwdft_prefill always runs FFTs + pruning; needs
+  IWDFT_FLAG_FFT_PREFILL = 4u,      /* iwdft_prefill always runs FFTs + pruning; needs
                                        M = 2^m >= 256 and <= 4096 kept bins per layer,
                                        else IWDFT_ERR_UNSUPPORTED.  With neither flag
                                        the library picks: FFT when it applies and some
                                        layer keeps >= 384 bins                     */
+  IWDFT_FLAG_SHORTCUT = 8u          /* the variant of the update that Sec. 4.1 mentions for long
+                                       contexts, the factor (N-1)/N of Eq. infi-dft taken as 1:
+                                       S_{T+1}[k] = W_k ( S_T[k] + x_T / (T+1) ).  Tokens no longer
+                                       weigh the same (prefill tokens keep 1/M, token n enters with
+                                       1/(n+1)); reconstruction and attention read the state as they
+                                       read S_T otherwise (gain T/M).  iwdft_append_attn then runs
+                                       its two calls in sequence and write_every is taken as 1.    */
 };
 
 typedef struct {
@@ -142,6 +149,13 @@ int iwdft_append(iwdft_ctx* ctx, const void* d_tok_k, const void* d_tok_v, void*
  * 0 <= a0, a0 + n_slots <= M. */
 int iwdft_reconstruct(iwdft_ctx* ctx, int32_t layer, int64_t a0, int64_t n_slots, void* d_Kt,
                       void* d_Vt, void* hip_stream);
+
+/* The same reconstruction on a strided grid of time slots: a0, a0 + stride, ..., n_slots of them
+ * (stride >= 1, a0 + (n_slots - 1) * stride < M) -- a compressed token set of n_slots < M rows instead of the
+ * original length that Sec. 4.2.2 reconstructs to (an extension; stride 1 is iwdft_reconstruct).
+ * d_Kt, d_Vt: [batch][n_kv_heads][n_slots][head_dim], kv_dtype; either may be NULL. */
+int iwdft_reconstruct_grid(iwdft_ctx* ctx, int32_t layer, int64_t a0, int64_t stride, int64_t n_slots,
+                           void* d_Kt, void* d_Vt, void* hip_stream);
 
 /* Decode attention over the assembled cache of every layer (Eq. kv-attn over Eq. kv-concat:
  * the S sink tokens, the M reconstructed slots, the R recent tokens, one softmax):

@@ -20,11 +20,12 @@ IWDFT_F32, IWDFT_BF16 = 0, 1
 IWDFT_FLAG_DIRECT_SYNTHESIS = 1
 IWDFT_FLAG_DENSE_PREFILL = 2
 IWDFT_FLAG_FFT_PREFILL = 4
+IWDFT_FLAG_SHORTCUT = 8
 IWDFT_STATIC_SCRATCH_BYTES = 64 << 20
 
 EXPORTED = [
     "iwdft_query_bytes", "iwdft_create", "iwdft_destroy", "iwdft_prefill", "iwdft_append",
-    "iwdft_reconstruct", "compressed_decode_attn", "iwdft_append_attn", "iwdft_export_coeffs", "iwdft_export_bins",
+    "iwdft_reconstruct", "iwdft_reconstruct_grid", "compressed_decode_attn", "iwdft_append_attn", "iwdft_export_coeffs", "iwdft_export_bins",
     "iwdft_num_tokens", "iwdft_set_num_tokens", "iwdft_last_error", "iwdft_phase_timing", "iwdft_phase_times", "iwdft_prefill_kind", "iwdft_attn_kind",
     "iwdft_select_bins", "iwdft_ablate_chunk", "iwdft_flush", "compressed_decode_attn_static",
 ]
@@ -72,6 +73,7 @@ def load_library() -> ctypes.CDLL:
     lib.iwdft_prefill.argtypes = [vp, vp, vp, vp]
     lib.iwdft_append.argtypes = [vp, vp, vp, vp]
     lib.iwdft_reconstruct.argtypes = [vp, i32, i64, i64, vp, vp, vp]
+    lib.iwdft_reconstruct_grid.argtypes = [vp, i32, i64, i64, i64, vp, vp, vp]
     lib.compressed_decode_attn.argtypes = [vp, vp, vp, f32, vp]
     lib.compressed_decode_attn_static.argtypes = [vp, vp, vp, f32, vp]
     lib.iwdft_append_attn.argtypes = [vp, vp, vp, vp, vp, f32, vp]
@@ -170,6 +172,10 @@ def iwdft_append(ctx, tok_k: torch.Tensor, tok_v: torch.Tensor, stream=None) -> 
 
 def iwdft_reconstruct(ctx, layer: int, a0: int, n_slots: int, Kt, Vt, stream=None) -> None:
     _check(load_library().iwdft_reconstruct(ctx, layer, a0, n_slots, _ptr(Kt), _ptr(Vt), _stream(stream)))
+
+
+def iwdft_reconstruct_grid(ctx, layer: int, a0: int, stride: int, n_slots: int, Kt, Vt, stream=None) -> None:
+    _check(load_library().iwdft_reconstruct_grid(ctx, layer, a0, stride, n_slots, _ptr(Kt), _ptr(Vt), _stream(stream)))
 
 
 def compressed_decode_attn(ctx, q: torch.Tensor, out: torch.Tensor, scale: float = 0.0, stream=None) -> None:
@@ -305,11 +311,14 @@ class Cache:
     def flush(self, stream=None):
         iwdft_flush(self.ctx, stream)
 
-    def reconstruct(self, layer, a0, n_slots, want_k=True, want_v=True, stream=None):
+    def reconstruct(self, layer, a0, n_slots, want_k=True, want_v=True, stream=None, stride=1):
         L, B, H, _, D = self.shape
         mk = lambda: torch.empty((B, H, n_slots, D), dtype=self.dtype, device=self.device)
         Kt, Vt = (mk() if want_k else None), (mk() if want_v else None)
-        iwdft_reconstruct(self.ctx, layer, a0, n_slots, Kt, Vt, stream)
+        if stride == 1:
+            iwdft_reconstruct(self.ctx, layer, a0, n_slots, Kt, Vt, stream)
+        else:
+            iwdft_reconstruct_grid(self.ctx, layer, a0, stride, n_slots, Kt, Vt, stream)
         return Kt, Vt
 
     def export_coeffs(self, layer, stream=None):

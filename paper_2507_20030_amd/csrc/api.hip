@@ -68,7 +68,8 @@ int make_plan(const iwdft_desc* d, Plan* pl) {
     return fail(IWDFT_ERR_ARG, "kv_dtype %d is neither IWDFT_F32 nor IWDFT_BF16", d->kv_dtype);
   if (d->write_every > (uint32_t)kMaxPend)
     return fail(IWDFT_ERR_ARG, "write_every = %u exceeds %d", d->write_every, kMaxPend);
-  if (d->flags & ~(uint32_t)(IWDFT_FLAG_DIRECT_SYNTHESIS | IWDFT_FLAG_DENSE_PREFILL | IWDFT_FLAG_FFT_PREFILL))
+  if (d->flags & ~(uint32_t)(IWDFT_FLAG_DIRECT_SYNTHESIS | IWDFT_FLAG_DENSE_PREFILL | IWDFT_FLAG_FFT_PREFILL |
+                             IWDFT_FLAG_SHORTCUT))
     return fail(IWDFT_ERR_ARG, "unknown bits in flags: 0x%x", d->flags);
   if ((d->flags & IWDFT_FLAG_DENSE_PREFILL) && (d->flags & IWDFT_FLAG_FFT_PREFILL))
     return fail(IWDFT_ERR_ARG, "flags ask for both the dense and the FFT prefill");
@@ -188,7 +189,9 @@ int make_plan(const iwdft_desc* d, Plan* pl) {
   pl->off_pe = o; o = align256(o + sizeof(float) * n_sl * (size_t)pl->G * (size_t)(d->n_sink + d->n_recent));
   // Deferred write-back needs the FFT attention kernels (they weigh the pending tokens) and all
   // query heads of a KV head in one pass; otherwise every step writes back.
-  pl->write_every = (d->write_every > 1 && pl->use_fft && heads_fit_one_pass(pl->G)) ? (int)d->write_every : 1;
+  pl->write_every = (d->write_every > 1 && pl->use_fft && heads_fit_one_pass(pl->G) && !(d->flags & IWDFT_FLAG_SHORTCUT))
+                        ? (int)d->write_every
+                        : 1;
   const size_t pend_rows = (d->n_recent || pl->write_every > 1) ? (size_t)pl->write_every : 0;
   pl->off_pendK = o; o = align256(o + esz * n_sl * pend_rows * kHeadDim);
   pl->off_pendV = o; o = align256(o + esz * n_sl * pend_rows * kHeadDim);
@@ -276,6 +279,13 @@ int next_marks(iwdft_ctx* c, const PhaseEvents** out) {
   } catch (...) {  // std::bad_alloc from the host-side containers: nothing may cross the C ABI
     return fail(IWDFT_ERR_ARG, "out of host memory");
   }
+}
+
+bool shortcut(const iwdft_ctx* c) { return (c->desc.flags & IWDFT_FLAG_SHORTCUT) != 0; }
+
+// Readers of the coefficients: gain T / M with the Sec. 4.1 shortcut (the stored state is then M S_T, not T S_T).
+void set_read_gain(iwdft_ctx* c) {
+  c->P.gain = shortcut(c) ? (float)((double)c->T / (double)c->desc.M) : 1.0f;
 }
 
 uint32_t t_shift(const iwdft_ctx* c) {  // (T - M) mod M
@@ -389,6 +399,8 @@ int iwdft_create(const iwdft_desc* desc, void* d_state, size_t state_bytes, void
     P.fold = (const uint16_t*)(c->state + pl.off_fold);
     P.FK = (float2*)(c->state + pl.off_FK);
     P.FV = (float2*)(c->state + pl.off_FV);
+    P.gain = 1.0f;
+    P.x_scale = 1.0f;
     P.S = desc->n_sink;
     P.R = desc->n_recent;
     P.sinkK = c->state + pl.off_sinkK;
@@ -479,8 +491,11 @@ int iwdft_append(iwdft_ctx* ctx, const void* d_tok_k, const void* d_tok_v, void*
   // The recent ring was filled oldest-first at prefill, so after T - M appends the oldest token
   // sits in slot (T - M) mod R.
   const uint32_t ring_pos = ctx->P.R ? (uint32_t)((ctx->T - ctx->desc.M) % ctx->P.R) : 0u;
+  // Sec. 4.1 shortcut: S <- W (S + x / (T + 1)); on the stored M S_T that is the exact update of x M / (T + 1).
+  ctx->P.x_scale = shortcut(ctx) ? (float)((double)ctx->desc.M / (double)(ctx->T + 1)) : 1.0f;
   rc = launched(launch_append(ctx->P, d_tok_k, d_tok_v, t_shift(ctx), ring_pos, (hipStream_t)hip_stream),
                 "append launch");
+  ctx->P.x_scale = 1.0f;
   if (rc != IWDFT_OK) return rc;
   ctx->T += 1;
   return IWDFT_OK;
@@ -493,7 +508,8 @@ int iwdft_export_coeffs(iwdft_ctx* ctx, int32_t layer, float* d_SK, float* d_SV,
   if (ctx->T < ctx->desc.M) return fail(IWDFT_ERR_STATE, "iwdft_export_coeffs before iwdft_prefill");
   if (!d_SK && !d_SV) return IWDFT_OK;
   if ((rc = flush_pending(ctx, (hipStream_t)hip_stream)) != IWDFT_OK) return rc;
-  return launched(launch_export(ctx->P, layer, d_SK, d_SV, t_shift(ctx), (float)(1.0 / (double)ctx->T),
+  return launched(launch_export(ctx->P, layer, d_SK, d_SV, t_shift(ctx),
+                                (float)(1.0 / (double)(shortcut(ctx) ? ctx->desc.M : ctx->T)),
                                 (hipStream_t)hip_stream),
                   "export launch");
 }
@@ -509,19 +525,29 @@ int iwdft_export_bins(iwdft_ctx* ctx, int32_t layer, int32_t* d_bins, void* hip_
                   "export bins");
 }
 
-int iwdft_reconstruct(iwdft_ctx* ctx, int32_t layer, int64_t a0, int64_t n_slots, void* d_Kt, void* d_Vt,
-                      void* hip_stream) {
+int iwdft_reconstruct_grid(iwdft_ctx* ctx, int32_t layer, int64_t a0, int64_t stride, int64_t n_slots, void* d_Kt,
+                           void* d_Vt, void* hip_stream) {
   int rc = check_ctx(ctx);
   if (rc != IWDFT_OK) return rc;
   if (layer < 0 || layer >= ctx->desc.n_layers) return fail(IWDFT_ERR_ARG, "layer %d out of range", layer);
-  if (a0 < 0 || n_slots < 0 || a0 + n_slots > ctx->desc.M)
-    return fail(IWDFT_ERR_ARG, "slots [%lld, %lld) outside [0, M)", (long long)a0, (long long)(a0 + n_slots));
+  if (stride < 1 || stride > ctx->desc.M) return fail(IWDFT_ERR_ARG, "stride %lld outside [1, M]", (long long)stride);
+  if (a0 < 0 || n_slots < 0 || a0 > ctx->desc.M || (n_slots > 0 && a0 + (n_slots - 1) * stride >= ctx->desc.M))
+    return fail(IWDFT_ERR_ARG, "slots %lld + %lld * [0, %lld) outside [0, M)", (long long)a0, (long long)stride,
+                (long long)n_slots);
   if (ctx->T < ctx->desc.M) return fail(IWDFT_ERR_STATE, "iwdft_reconstruct before iwdft_prefill");
   if (n_slots == 0 || (!d_Kt && !d_Vt)) return IWDFT_OK;
   if ((rc = flush_pending(ctx, (hipStream_t)hip_stream)) != IWDFT_OK) return rc;
-  return launched(launch_reconstruct(ctx->P, layer, (uint32_t)a0, (uint32_t)n_slots, d_Kt, d_Vt,
+  set_read_gain(ctx);
+  return launched(launch_reconstruct(ctx->P, layer, (uint32_t)a0, (uint32_t)stride, (uint32_t)n_slots, d_Kt, d_Vt,
                                      t_shift(ctx), ctx->plan.use_fft, (hipStream_t)hip_stream),
                   "reconstruct launch");
+}
+
+int iwdft_reconstruct(iwdft_ctx* ctx, int32_t layer, int64_t a0, int64_t n_slots, void* d_Kt, void* d_Vt,
+                      void* hip_stream) {
+  if (ctx && (a0 < 0 || n_slots < 0 || a0 + n_slots > ctx->desc.M))
+    return fail(IWDFT_ERR_ARG, "slots [%lld, %lld) outside [0, M)", (long long)a0, (long long)(a0 + n_slots));
+  return iwdft_reconstruct_grid(ctx, layer, a0, 1, n_slots, d_Kt, d_Vt, hip_stream);
 }
 
 int compressed_decode_attn(iwdft_ctx* ctx, const void* d_q, void* d_out, float scale, void* hip_stream) {
@@ -535,6 +561,7 @@ int compressed_decode_attn(iwdft_ctx* ctx, const void* d_q, void* d_out, float s
   const Plan& pl = ctx->plan;
   const PhaseEvents* marks = nullptr;
   if ((rc = next_marks(ctx, &marks)) != IWDFT_OK) return rc;
+  set_read_gain(ctx);
   return launched(launch_attn(ctx->P, d_q, d_out, scale, (float2*)(ctx->ws + pl.off_qc),
                               (float2*)(ctx->ws + pl.off_Pn), (float*)(ctx->ws + pl.off_pe),
                               (float*)(ctx->ws + pl.off_direct),
@@ -562,6 +589,7 @@ int compressed_decode_attn_static(iwdft_ctx* ctx, const void* d_q, void* d_out, 
   char* sc = nullptr;
   if ((rc = static_scratch(ctx->device, &sc)) != IWDFT_OK) return rc;
   if ((rc = flush_pending(ctx, (hipStream_t)hip_stream)) != IWDFT_OK) return rc;
+  set_read_gain(ctx);
   // Every entry of the four arrays is written by the kernels before it is read, so nothing needs clearing
   // although the scratch still holds the previous call's contents.
   return launched(launch_attn(ctx->P, d_q, d_out, scale, (float2*)sc, (float2*)(sc + rows), (float*)(sc + 2 * rows),
@@ -577,7 +605,8 @@ int iwdft_append_attn(iwdft_ctx* ctx, const void* d_tok_k, const void* d_tok_v, 
   if (ctx->T < ctx->desc.M) return fail(IWDFT_ERR_STATE, "iwdft_append_attn before iwdft_prefill");
   if (!std::isfinite(scale)) return fail(IWDFT_ERR_ARG, "scale is not finite");
   if (scale <= 0.0f) scale = 1.0f / std::sqrt((float)ctx->desc.head_dim);
-  if (!step_can_fuse(ctx->P)) {  // more query heads per KV head than one pass holds: plain sequence
+  if (!step_can_fuse(ctx->P) || shortcut(ctx)) {  // more query heads per KV head than one pass holds, or the
+                                                  // shortcut's per-token scale: plain sequence
     rc = iwdft_append(ctx, d_tok_k, d_tok_v, hip_stream);
     if (rc != IWDFT_OK) return rc;
     return compressed_decode_attn(ctx, d_q, d_out, scale, hip_stream);

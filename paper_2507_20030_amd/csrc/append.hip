@@ -57,7 +57,7 @@ __global__ __launch_bounds__(kAppendThreads) void append_kernel(Params P, const 
 #pragma unroll
     for (int u = 0; u < U; ++u) f[u] = __builtin_nontemporal_load(row + (dd + u) * stride);
 #pragma unroll
-    for (int u = 0; u < U; ++u) x[u] = load_kv<BF16>(tok, xbase + dd + u);
+    for (int u = 0; u < U; ++u) x[u] = load_kv<BF16>(tok, xbase + dd + u) * P.x_scale;
 #pragma unroll
     for (int u = 0; u < U; ++u) {
       f[u].x += x[u] * w0.x;

@@ -303,7 +303,13 @@ __global__ __launch_bounds__(qc_threads(MODE != kPlain)) void attn_qc_kernel(Par
 
 // ------------------------------------------------------------------------------------------ C
 constexpr int kOutThreads = 256;
-constexpr int kOutDC = 16;  // channels per block
+// Channels per block: 16, or 8 where 16 channels x 8 query heads of accumulators would leave one wave per SIMD.
+// (8 query heads, update modes: 256 registers + spills at 16 channels; measured 11.8 -> 7.5 ms per write-back launch on
+// 10240 slices x 1638 bins.  The read-only form is faster with 16.)
+constexpr int out_dc(int GT, int MODE) {
+  const bool upd = MODE == kUpdate1 || MODE == kUpdateN;
+  return (GT == 8 && upd) ? 8 : 16;
+}
 
 // Sum V values per lane over the whole wave; on return lane L holds the total of value
 // L >> (6 - log2 V)  (V <= 64, power of two).  Each step halves the number of live values.
@@ -332,7 +338,7 @@ __device__ __forceinline__ float wave_reduce_scatter(float (&v)[V], int lane) {
   return v[0];
 }
 
-// logical block: (slice * 8 + dchunk) * passes + pass.  Lane = two adjacent bins; a block walks all
+// logical block: (slice * (128 / channels per block) + dchunk) * passes + pass.  Lane = two adjacent bins; a block walks all
 // bins of its slice for 16 channels, so no cross-block reduction is needed.  Hardware block ids are
 // dealt round-robin to the 8 XCDs; they are remapped so that the 8 channel chunks of a slice run on
 // ONE XCD and fetch the slice's Pn rows into that XCD's L2 once instead of eight times.
@@ -351,6 +357,7 @@ __global__ __launch_bounds__(kOutThreads) void attn_out_kernel(Params P, const f
   constexpr bool UPD = MODE == kUpdate1 || MODE == kUpdateN;
   constexpr bool PLAIN = !UPD;
   constexpr bool STREAM = MODE != kPlain;  // nothing re-reads the V coefficients soon: bypass the caches
+  constexpr int kOutDC = out_dc(GT, MODE);
   constexpr int V = kOutDC * GT;
   constexpr int VR = V > 64 ? 64 : V;  // values per reduction round
   __shared__ float red[kOutThreads / 64][V];
@@ -554,7 +561,7 @@ __global__ __launch_bounds__(kFftThreads, (MULTI && NBT > 4) ? 2 : 4) void attn_
   const uint16_t* fold = P.fold + L.bin_off;
   // log2(e) is folded into the scores so that softmax can use the bare exp2 instruction;
   // 0.5: each bin is split into k and its mirror.
-  const float gain = 0.5f * 1.44269504088896341f * scale / (float)P.M;
+  const float gain = 0.5f * 1.44269504088896341f * scale * P.gain / (float)P.M;
 
   for (int m = tid; m <= (Q >> 3); m += kFftThreads) tab[m] = cis((uint32_t)m, (uint32_t)Q);
 
@@ -726,7 +733,7 @@ __global__ __launch_bounds__(kFftThreads, (MULTI && NBT > 4) ? 2 : 4) void attn_
 
   float2* o0 = Pn + L.ws_off + ((int64_t)s * P.G + g0) * L.Bp;
   float2* o1 = o0 + L.Bp;
-  const float inv_M = 1.0f / (float)P.M;
+  const float inv_M = P.gain / (float)P.M;
   const float iz0 = inv_M / Z.x, iz1 = has1 ? inv_M / Z.y : 0.f;
   // Pending tokens of the fused decode step (not yet inside F_V): token j adds
   // v_j * Re sum_k e^{j theta_jk} Pn[k] to the output; the sums are formed here, where Pn is at hand.
@@ -799,7 +806,7 @@ __global__ __launch_bounds__(kDirThreads) void attn_direct_kernel(Params P, cons
   const LayerInfo L = P.layers[layer];
   const float2* qrow = qc + L.ws_off + ((int64_t)s * P.G + g) * L.Bp;
   float* sc = scores + (int64_t)blockIdx.x * P.M;
-  const float gain = scale / (float)P.M;
+  const float gain = scale * P.gain / (float)P.M;
 
   for (int c0 = 0; c0 < L.nb; c0 += kDirStage) {
     const int cn = min(kDirStage, L.nb - c0);
@@ -847,7 +854,7 @@ __global__ __launch_bounds__(kDirThreads) void attn_direct_kernel(Params P, cons
 
   for (int e = tid; e < E; e += kDirThreads) per[e] = expf(per[e] * scale - mx) / Z;  // weights p_e / Z
   float2* orow = Pn + L.ws_off + ((int64_t)s * P.G + g) * L.Bp;
-  const float inv_M = 1.0f / (float)P.M;
+  const float inv_M = P.gain / (float)P.M;
   for (int i = tid; i < L.Bp; i += kDirThreads) {
     float2 r = make_float2(0.f, 0.f);
     if (i < L.nb) {
@@ -883,7 +890,8 @@ static hipError_t launch_attn_t(const Params& P, const void* q, void* out, float
   const int kQcThreads = qc_threads(mode != kPlain), kQcBins = qc_bins(mode != kPlain);
   const int chunks = (P.max_Bp + kQcBins - 1) / kQcBins;
   const uint64_t gridA = (uint64_t)P.n_slices * chunks * passes;
-  const uint64_t gridC = (uint64_t)P.n_slices * (kHeadDim / kOutDC) * passes;
+  const int dcC = out_dc(GT, mode == kPlain && u.np > 0 ? kPlainStream : mode);
+  const uint64_t gridC = (uint64_t)P.n_slices * (kHeadDim / dcC) * passes;
   const uint64_t gridBd = (uint64_t)P.n_slices * P.G;
   if (gridA > 0x7fffffffull || gridC > 0x7fffffffull || gridBd > 0x7fffffffull)
     return hipErrorInvalidConfiguration;

@@ -47,6 +47,10 @@ struct Params {
   float2* FV;
   // Exact tokens (Sec. 4.2.1): S sink tokens and a ring of R recent tokens per slice, kv_dtype,
   // [slice][S][128] and [slice][R][128].  Null / 0 when the windows are not used.
+  // 1 except with IWDFT_FLAG_SHORTCUT (Sec. 4.1, (N-1)/N taken as 1), where the host sets them per call: an
+  // absorbed token enters scaled by x_scale = M / (T + 1), and everything that reads the coefficients as the
+  // paper's S_T (reconstruction, scores, outputs) applies the extra gain = T / M.
+  float gain, x_scale;
   int32_t S, R;
   void* sinkK;
   void* sinkV;
@@ -142,7 +146,8 @@ hipError_t launch_append(const Params& P, const void* tok_k, const void* tok_v, 
 hipError_t launch_export(const Params& P, int layer, float* SK, float* SV, uint32_t t_shift,
                          float inv_T, hipStream_t st);
 // use_fft: the fold schedule (Params::fold) is valid, so long slot ranges may go through inverse FFTs.
-hipError_t launch_reconstruct(const Params& P, int layer, uint32_t a0, uint32_t n_slots, void* Kt,
+// Slots a0, a0 + stride, ..., n_slots of them (stride >= 1; the FFT kernel serves stride 1 only).
+hipError_t launch_reconstruct(const Params& P, int layer, uint32_t a0, uint32_t stride, uint32_t n_slots, void* Kt,
                               void* Vt, uint32_t t_shift, bool use_fft, hipStream_t st);
 // Optional timing marks of the three attention phases: ev[0] before A, ev[1] after A (q against
 // the K coefficients), ev[2] after B (softmax through the transforms), ev[3] after C (output from

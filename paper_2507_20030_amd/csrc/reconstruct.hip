@@ -17,7 +17,7 @@ constexpr int kRecBins = 32;   // bins per LDS tile
 
 // grid: ((s * atiles) + atile) * 2 + tensor ; 256 threads, each 4 channels x 8 slots.
 template <bool BF16>
-__global__ __launch_bounds__(256) void reconstruct_kernel(Params P, int layer, uint32_t a0,
+__global__ __launch_bounds__(256) void reconstruct_kernel(Params P, int layer, uint32_t a0, uint32_t stride,
                                                          uint32_t n_slots, void* __restrict__ Kt,
                                                          void* __restrict__ Vt, uint32_t tsh, int atiles) {
   __shared__ float2 Fs[kRecBins][kHeadDim + 1];
@@ -31,7 +31,7 @@ __global__ __launch_bounds__(256) void reconstruct_kernel(Params P, int layer, u
   if (!out) return;
   const LayerInfo L = P.layers[layer];
   const float2* F = (tensor ? P.FV : P.FK) + L.coef_off + (int64_t)s * kHeadDim * L.Bp;
-  const float inv_M = 1.0f / (float)P.M;
+  const float inv_M = P.gain / (float)P.M;
   const int tid = threadIdx.x;
   const int td = tid & 31, ta = tid >> 5;
 
@@ -54,8 +54,9 @@ __global__ __launch_bounds__(256) void reconstruct_kernel(Params P, int layer, u
     for (int e = tid; e < kRecBins * kRecSlots; e += 256) {  // twiddle tile
       const int i = i0 + e / kRecSlots, a = e % kRecSlots;
       float2 w = make_float2(0.f, 0.f);
-      const uint32_t slot = a0 + at * kRecSlots + a;
-      if (i < L.nb && slot < a0 + n_slots) {
+      const uint32_t rel = at * kRecSlots + a;            // output row; its slot is a0 + stride * rel < M
+      const uint32_t slot = a0 + stride * rel;
+      if (i < L.nb && rel < n_slots) {
         const uint32_t k = (uint32_t)P.bins[L.bin_off + i];
         const uint32_t sh = (slot % P.M + P.M - tsh) % P.M;  // (slot - t) mod M
         w = cis(mulmod(k, sh, P.M, P.Mmask), P.M);
@@ -123,7 +124,7 @@ __global__ __launch_bounds__(kFftThreads, 4) void reconstruct_fft_kernel(Params 
   const float* wts = P.weights + L.bin_off;
   const uint16_t* fold = P.fold + L.bin_off;
   const uint32_t Pb = MULTI ? (P.M >> LOGQ) : 1u;
-  const float gain = 0.5f / (float)P.M;
+  const float gain = 0.5f * P.gain / (float)P.M;
   char* orow = out + (int64_t)s * n_slots * kRow + pair * 2 * kElem;
 
   for (int m = tid; m <= (Q >> 3); m += kFftThreads) tab[m] = cis((uint32_t)m, (uint32_t)Q);
@@ -227,19 +228,19 @@ static hipError_t launch_reconstruct_fft_t(const Params& P, int layer, uint32_t 
 }
 
 // use_fft: the caller knows the layer's fold schedule is valid (the attention path uses FFTs too).
-hipError_t launch_reconstruct(const Params& P, int layer, uint32_t a0, uint32_t n_slots, void* Kt,
+hipError_t launch_reconstruct(const Params& P, int layer, uint32_t a0, uint32_t stride, uint32_t n_slots, void* Kt,
                               void* Vt, uint32_t tsh, bool use_fft, hipStream_t st) {
   // The transform produces all M slots; the direct contraction costs O(|B|) per requested slot.
-  if (use_fft && reconstruct_fft_ok(P) && (uint64_t)n_slots * 8 >= P.M)
+  if (stride == 1 && use_fft && reconstruct_fft_ok(P) && (uint64_t)n_slots * 8 >= P.M)
     return P.kv_dtype == 1 ? launch_reconstruct_fft_t<true>(P, layer, a0, n_slots, Kt, Vt, tsh, st)
                            : launch_reconstruct_fft_t<false>(P, layer, a0, n_slots, Kt, Vt, tsh, st);
   const int atiles = (int)((n_slots + kRecSlots - 1) / kRecSlots);
   const uint64_t blocks = (uint64_t)P.batch * P.n_kv * atiles * 2;
   if (blocks > 0x7fffffffull) return hipErrorInvalidConfiguration;
   if (P.kv_dtype == 1)
-    reconstruct_kernel<true><<<dim3((uint32_t)blocks), dim3(256), 0, st>>>(P, layer, a0, n_slots, Kt, Vt, tsh, atiles);
+    reconstruct_kernel<true><<<dim3((uint32_t)blocks), dim3(256), 0, st>>>(P, layer, a0, stride, n_slots, Kt, Vt, tsh, atiles);
   else
-    reconstruct_kernel<false><<<dim3((uint32_t)blocks), dim3(256), 0, st>>>(P, layer, a0, n_slots, Kt, Vt, tsh, atiles);
+    reconstruct_kernel<false><<<dim3((uint32_t)blocks), dim3(256), 0, st>>>(P, layer, a0, stride, n_slots, Kt, Vt, tsh, atiles);
   return hipGetLastError();
 }
 

@@ -49,7 +49,7 @@ def test_query_bytes_accounts_for_padded_rows():
     (dict(kv_dtype=7), B.IWDFT_ERR_ARG),
     (dict(M=0), B.IWDFT_ERR_ARG),
     (dict(M=(1 << 30) + 1), B.IWDFT_ERR_ARG),
-    (dict(flags=8), B.IWDFT_ERR_ARG),
+    (dict(flags=1 << 20), B.IWDFT_ERR_ARG),
     (dict(write_every=17), B.IWDFT_ERR_ARG),
     (dict(flags=B.IWDFT_FLAG_DENSE_PREFILL | B.IWDFT_FLAG_FFT_PREFILL), B.IWDFT_ERR_ARG),
     (dict(flags=B.IWDFT_FLAG_FFT_PREFILL), B.IWDFT_ERR_UNSUPPORTED),   # M = 64: below the FFT's smallest length

@@ -5,6 +5,7 @@ import numpy as np
 import pytest
 import torch
 
+from paper_2507_20030_amd import binding as B
 from paper_2507_20030_amd import workload as wl
 from test_gpu_parity import (DEV, SliceOracle, check_attn, check_coeffs, check_masks, check_reconstruct,
                              make_cache, run_stream)
@@ -14,7 +15,6 @@ pytestmark = pytest.mark.gpu
 
 @pytest.mark.parametrize("prefill", ["fft", "dense"])
 def test_cfg3_batch8_mixed_masks(prefill):
-    from paper_2507_20030_amd import binding as B
     cfg = wl.CONFIGS["cfg3"]
     bins = wl.layer_bins(cfg)
     assert any(b[-1] >= cfg.n_bins for b in bins) and any(b[-1] == cfg.n_bins - 1 for b in bins)

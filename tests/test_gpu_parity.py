@@ -481,35 +481,89 @@ def test_two_runs_are_bitwise_identical(prefill):
     assert all(torch.equal(a, b) for a, b in zip(outs[0], outs[1]))
 
 
-def test_shortcut_variant_through_prescaled_tokens():
-    # Sec. 4.1's (N-1)/N -> 1 shortcut needs no kernel of its own: in the stored (un-normalised) frame it
-    # is the exact update of a token scaled by M / (T + 1), and its state is T / M times what
-    # iwdft_export_coeffs returns.  Checked against the oracle's closed form of the shortcut; the distance
-    # to the exact rule (the drift the shortcut causes) is printed.
-    from oracle import iwdft_oracle as orc
-    cfg = small_cfg(L=256, n_bins=40, group=2, dtype="f32", steps=64, n_layers=1, batch=1)
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("L,S,R,group,steps", [(256, 0, 0, 2, 64), (1024, 3, 5, 4, 9), (96, 0, 2, 1, 200)])
+def test_shortcut_flag_matches_the_oracle_recursion(dtype, L, S, R, group, steps):
+    """IWDFT_FLAG_SHORTCUT: Sec. 4.1's update with (N-1)/N taken as 1, inside the library (the token's scale
+    M / (T+1) is applied by the append kernel, the gain T/M by every reader).  Exported coefficients against the
+    oracle's shortcut recursion and its closed form, attention and reconstruction against the oracle run on that
+    state; both the two calls and iwdft_append_attn (which must fall back to them)."""
+    cfg = small_cfg(L=L, n_bins=min(40, L // 2), group=group, dtype=dtype, steps=steps, n_layers=2, batch=1, n_sink=S,
+                    n_recent=R)
     bins = random_bins(cfg, 71)
+    K, V = wl.prefill_tensors(cfg, DEV)
+    cache = B.Cache(cfg.n_layers, cfg.batch, cfg.n_kv_heads, cfg.n_q_heads, cfg.head_dim, cfg.torch_dtype, cfg.L,
+                    bins, None, B.IWDFT_FLAG_SHORTCUT, DEV, n_sink=S, n_recent=R, write_every=8)
+    cache.prefill(K, V)
+    key = (1, 0, 1)
+    l = key[0]
+    k0, v0 = f64(K[key]), f64(V[key])
+    SK, SV, T = orc.prefill(k0[S:S + L], bins[l]), orc.prefill(v0[S:S + L], bins[l]), L
+    sink = (k0[:S], v0[:S])
+    rk, rv = [r for r in k0[S + L:]], [r for r in v0[S + L:]]
+    absorbed = [k0[S:S + L]]
+    worst = 0.0
+    G = cfg.group
+    for i in range(cfg.steps):
+        tk, tv, q = wl.decode_step(cfg, i, DEV)
+        if i % 3 == 2:
+            out = cache.step(tk, tv, q)
+        else:
+            cache.append(tk, tv)
+            out = cache.attend(q)
+        rk.append(f64(tk[key]))
+        rv.append(f64(tv[key]))
+        xk, xv = rk.pop(0), rv.pop(0)
+        SK, SV = orc.append_shortcut(SK, xk, T, bins[l], L), orc.append_shortcut(SV, xv, T, bins[l], L)
+        absorbed.append(xk[None, :])
+        T += 1
+        ref = orc.windowed_attention(f64(q[l, 0, G:2 * G]), sink[0], sink[1], SK, SV, T, L, bins[l],
+                                     np.stack(rk) if rk else np.zeros((0, 128)), np.stack(rv) if rv else np.zeros((0, 128)))
+        worst = max(worst, rel_l2(f64(out[l, 0, G:2 * G]), ref))
+    assert worst < TOL_ATTN[cfg.torch_dtype], f"shortcut attention rel-L2 {worst:.3e}"
+    assert cache.T == T
+    gk, gv = cache.export_coeffs(l)
+    e_rec = max(rel_l2(c128(gk[0, 1]), SK), rel_l2(c128(gv[0, 1]), SV))
+    e_closed = rel_l2(c128(gk[0, 1]), orc.closed_form_shortcut(np.vstack(absorbed), L, bins[l]))
+    assert e_rec < TOL_COEF and e_closed < TOL_COEF, f"shortcut coefficients {e_rec:.2e} / {e_closed:.2e}"
+    Kt, Vt = cache.reconstruct(l, 0, L)
+    e_k = rel_l2(f64(Kt[0, 1]), orc.reconstruct(SK, T, L, bins[l]))
+    e_v = rel_l2(f64(Vt[0, 1]), orc.reconstruct(SV, T, L, bins[l]))
+    assert max(e_k, e_v) < TOL_REC[cfg.torch_dtype]
+    drift = rel_l2(SK, orc.closed_form(np.vstack(absorbed), L, bins[l]))
+    print(f"\n[shortcut {dtype} M={L}] coefficients {e_rec:.2e} attention {worst:.2e} reconstruction {max(e_k, e_v):.2e}; "
+          f"drift of the shortcut from the exact rule after {steps} appends: {drift:.2e}", flush=True)
+    cache.close()
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("L,n_bins,steps,grid", [(256, 100, 7, (3, 4, 60)), (1000, 77, 3, (0, 7, 143)), (4096, 300, 2, (5, 64, 64)),
+                                                 (8192, 600, 9, (8191, 1, 1)), (96, 96, 100, (1, 5, 19))])
+def test_reconstruct_on_a_strided_grid(dtype, L, n_bins, steps, grid):
+    """iwdft_reconstruct_grid against the oracle's strided reconstruction (slots a0 + j * stride)."""
+    cfg = small_cfg(L=L, n_bins=n_bins, group=1, dtype=dtype, steps=steps, n_layers=2, batch=2)
+    bins = random_bins(cfg, 73)
     K, V = wl.prefill_tensors(cfg, DEV)
     cache = make_cache(cfg, bins)
     cache.prefill(K, V)
-    hist = [f64(K[0, 0, h]) for h in range(cfg.n_kv_heads)]
-    for i in range(cfg.steps):
+    slices = [(0, 0, 0), (1, 1, 1)]
+    ora = SliceOracle(cfg, bins, None, K, V, slices)
+    for i in range(steps):
         tk, tv, _ = wl.decode_step(cfg, i, DEV)
-        T = cfg.L + i
-        cache.append(tk * (cfg.L / (T + 1)), tv * (cfg.L / (T + 1)))
-        hist = [np.vstack([x, f64(tk[0, 0, h])[None, :]]) for h, x in enumerate(hist)]
-    T = cfg.L + cfg.steps
-    SK, _ = cache.export_coeffs(0)
-    worst, drift = 0.0, 0.0
-    for h in range(cfg.n_kv_heads):
-        got = c128(SK[0, h]) * (T / cfg.L)
-        ref = orc.closed_form_shortcut(hist[h], cfg.L, bins[0])
-        exact = orc.closed_form(hist[h], cfg.L, bins[0])
-        worst = max(worst, rel_l2(got, ref))
-        drift = max(drift, rel_l2(ref, exact))
-    print(f"\n[shortcut] rel-L2 vs oracle {worst:.2e}; drift of the shortcut from the exact rule after "
-          f"{cfg.steps} appends on M = {cfg.L}: {drift:.2e}", flush=True)
-    assert worst < 1e-4      # the scaled tokens are rounded to fp32 once more: still far inside the bar
+        cache.append(tk, tv)
+        ora.append(tk, tv)
+    a0, stride, n = grid
+    worst = 0.0
+    for (l, b, h) in slices:
+        Kt, Vt = cache.reconstruct(l, a0, n, stride=stride)
+        for which, got in ((0, Kt), (1, Vt)):
+            ref = orc.reconstruct_grid(ora.S[(l, b, h)][which], ora.T, L, bins[l], a0, stride, n)
+            worst = max(worst, rel_l2(f64(got[b, h]), ref))
+    assert worst < TOL_REC[cfg.torch_dtype], f"grid reconstruction rel-L2 {worst:.3e}"
+    with pytest.raises(B.IwdftError):
+        cache.reconstruct(0, a0, n + 1 + (L - 1 - a0 - (n - 1) * stride) // stride, stride=stride)   # one row past M
+    with pytest.raises(B.IwdftError):
+        B.iwdft_reconstruct_grid(cache.ctx, 0, 0, 0, 1, None, None)
     cache.close()
 
 
