@@ -62,8 +62,8 @@ enum { IWDFT_F32 = 0, IWDFT_BF16 = 1 };
 /* desc.flags */
 enum {
   IWDFT_FLAG_DIRECT_SYNTHESIS = 1u, /* decode attention evaluates the O(M*|B|) sums
-                                       directly instead of through FFTs (always used
-                                       when M is not a power of two)               */
+                                       directly instead of through FFTs (see
+                                       iwdft_attn_kind for what runs otherwise)    */
   IWDFT_FLAG_DENSE_PREFILL = 2u,    /* iwdft_prefill always runs the dense contraction
                                        at the kept bins (matrix cores)             */
   IWDFT_FLAG_FFT_PREFILL = 4u,      /* iwdft_prefill always runs FFTs + pruning; needs
@@ -130,9 +130,11 @@ int iwdft_prefill(iwdft_ctx* ctx, const void* d_K, const void* d_V, void* hip_st
 int iwdft_prefill_kind(const iwdft_ctx* ctx);
 
 /* Which synthesis compressed_decode_attn / iwdft_append_attn run for this context: 1 = scores and softmax
- * weights through in-LDS FFTs (O(M log M) per query head, the HBM-bound path), 0 = the direct O(M |B|) sums
- * (arithmetic-bound; chosen by IWDFT_FLAG_DIRECT_SYNTHESIS or when the FFT path does not apply); -1 if ctx
- * is NULL.  With 0, desc.write_every is taken as 1. */
+ * weights through in-LDS FFTs (M = 2^m >= 256 and at most 4096 kept bins per layer: O(M log M) per query head,
+ * the HBM-bound path); 2 = through chirp-z transforms (any other 32 <= M <= 8192, e.g. M = context - sink - recent:
+ * O(M log M) as well, about 8 times the arithmetic of 1); 0 = the direct O(M |B|) sums (arithmetic-bound; chosen by
+ * IWDFT_FLAG_DIRECT_SYNTHESIS, for M < 32, and for M > 8192 that is not a power of two); -1 if ctx is NULL.
+ * With 0 or 2, desc.write_every is taken as 1. */
 int iwdft_attn_kind(const iwdft_ctx* ctx);
 
 /* Streaming update with one new token per sequence (Eq. infi-dft, Eq. update-iwdft).

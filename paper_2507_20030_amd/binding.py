@@ -225,7 +225,7 @@ def iwdft_prefill_kind(ctx) -> str:
 
 
 def iwdft_attn_kind(ctx) -> str:
-    return {0: "direct", 1: "fft"}[load_library().iwdft_attn_kind(ctx)]
+    return {0: "direct", 1: "fft", 2: "chirp"}[load_library().iwdft_attn_kind(ctx)]
 
 
 def iwdft_phase_timing(ctx, enable: bool) -> None:

@@ -2,6 +2,7 @@
 // All arithmetic lives in the kernels; this file only decides what to launch.
 #include <algorithm>
 #include <cmath>
+#include <complex>
 #include <cstdarg>
 #include <cstdio>
 #include <cstring>
@@ -42,7 +43,10 @@ struct Plan {  // byte offsets inside the two caller buffers, derived from a des
   int64_t coef_total = 0;  // float2 per tensor
   int64_t ws_total = 0;    // float2 per workspace array
   int32_t G = 1, max_nb = 0, max_Bp = 0;
-  bool use_fft = false;          // decode attention through FFTs
+  bool use_fft = false;          // decode attention through power-of-two FFTs
+  bool use_chirp = false;        // ... through chirp-z transforms (any M up to kChirpMaxM when use_fft is false)
+  int chirp_logN = 0;            // length of its circular convolutions
+  size_t off_chirp = 0, off_chirpH = 0;
   bool use_fft_prefill = false;  // prefill through FFTs (else the dense MFMA contraction)
   int write_every = 1;           // fused decode step: coefficients written back every this many tokens
   size_t off_layers = 0, off_bins = 0, off_weights = 0, off_fold = 0, off_FK = 0, off_FV = 0, state_bytes = 0;
@@ -56,6 +60,7 @@ constexpr int kFftPrefillMinBins = 384;  // fewer kept bins per layer: the dense
 constexpr int kMaxExact = 1024;  // most sink + recent tokens (their scores sit in LDS)
 constexpr uint32_t kFftMinM = 256;
 constexpr int64_t kFftMaxQ = 8192;  // longest transform the FFT attention kernel holds in LDS
+constexpr int64_t kChirpMinM = 32, kChirpMaxM = 8192;  // chirp-z attention: 2M - 1 <= 16384 points fit in LDS
 
 int make_plan(const iwdft_desc* d, Plan* pl) {
   if (!d) return fail(IWDFT_ERR_ARG, "desc is NULL");
@@ -140,26 +145,31 @@ int make_plan(const iwdft_desc* d, Plan* pl) {
   } else {
     pl->use_fft_prefill = fft_pf_ok && !(d->flags & IWDFT_FLAG_DENSE_PREFILL) && pl->max_nb >= kFftPrefillMinBins;
   }
+  pl->use_chirp = !pl->use_fft && !(d->flags & IWDFT_FLAG_DIRECT_SYNTHESIS) && d->M >= kChirpMinM && d->M <= kChirpMaxM;
+  if (pl->use_chirp) {
+    pl->chirp_logN = 8;
+    while (((int64_t)1 << pl->chirp_logN) < 2 * d->M - 1) pl->chirp_logN += 2;  // even lengths only
+  }
   pl->fold.assign((size_t)pl->n_bins_total, 0);
-  if (pl->use_fft) {
-    // The FFT attention kernel folds the sparse spectrum (each bin k and its mirror -k) modulo the
-    // transform length Q.  Entries that land on the same slot are added in separate rounds, so the
-    // kernel needs no atomics and sums in a fixed order: round = how many earlier entries of the
-    // layer already use that slot.
-    const int64_t Q = d->M < kFftMaxQ ? d->M : kFftMaxQ;
+  if (pl->use_fft || pl->use_chirp) {
+    // The FFT attention kernels place the sparse spectrum (each bin k and its mirror -k) into an LDS array:
+    // folded modulo the transform length Q (power-of-two kernel) or at k and M - k (chirp-z kernel).  Entries that
+    // land on the same slot are added in separate rounds, so the kernels need no atomics and sum in a fixed order:
+    // round = how many earlier entries of the layer already use that slot.
+    const int64_t Q = pl->use_chirp ? d->M : (d->M < kFftMaxQ ? d->M : kFftMaxQ);
     std::vector<uint16_t> cnt((size_t)Q);
-    for (int l = 0; l < d->n_layers && pl->use_fft; ++l) {
+    for (int l = 0; l < d->n_layers && (pl->use_fft || pl->use_chirp); ++l) {
       std::fill(cnt.begin(), cnt.end(), 0);
       LayerInfo& L = pl->layers[l];
       int rounds = 0;
       for (int i = 0; i < L.nb; ++i) {
         const int64_t k = d->bins[L.bin_off + i];
-        const int64_t r = k & (Q - 1), rm = (Q - r) & (Q - 1);
+        const int64_t r = k % Q, rm = (Q - r) % Q;
         const int fd = cnt[r]++;
         // a bin whose mirror falls on its own slot (k = 0 or Q/2 mod Q) adds both halves in one write:
         // its mirror byte is 0xff, "no round"
         const int fm = r == rm ? 0xff : cnt[rm]++;
-        if (fd > 254 || (r != rm && fm > 254)) { pl->use_fft = false; break; }
+        if (fd > 254 || (r != rm && fm > 254)) { pl->use_fft = pl->use_chirp = false; break; }
         pl->fold[L.bin_off + i] = (uint16_t)(fd | (fm << 8));
         if (fd + 1 > rounds) rounds = fd + 1;
         if (r != rm && fm + 1 > rounds) rounds = fm + 1;
@@ -173,6 +183,8 @@ int make_plan(const iwdft_desc* d, Plan* pl) {
   pl->off_bins = o;    o = align256(o + sizeof(int32_t) * (size_t)pl->n_bins_total);
   pl->off_weights = o; o = align256(o + sizeof(float) * (size_t)pl->n_bins_total);
   pl->off_fold = o;    o = align256(o + sizeof(uint16_t) * (size_t)pl->n_bins_total);
+  pl->off_chirp = o;   o = align256(o + (pl->use_chirp ? sizeof(float2) * (size_t)d->M : 0));
+  pl->off_chirpH = o;  o = align256(o + (pl->use_chirp ? sizeof(float2) * ((size_t)1 << pl->chirp_logN) : 0));
   pl->off_FK = o;      o = align256(o + sizeof(float2) * (size_t)coef);
   pl->off_FV = o;      o = align256(o + sizeof(float2) * (size_t)coef);
   const size_t esz = d->kv_dtype == IWDFT_BF16 ? 2 : 4;
@@ -197,11 +209,51 @@ int make_plan(const iwdft_desc* d, Plan* pl) {
   pl->off_pendV = o; o = align256(o + esz * n_sl * pend_rows * kHeadDim);
   pl->off_ps = o;    o = align256(o + (pl->write_every > 1 ? sizeof(float) * n_sl * (size_t)pl->G * kMaxPend : 0));
   pl->off_direct = o;
-  if (!pl->use_fft)
+  if (!pl->use_fft && !pl->use_chirp)
     o = align256(o + sizeof(float) * (size_t)d->n_layers * (size_t)slices_per_layer *
                          (size_t)pl->G * (size_t)d->M);
   pl->ws_bytes = o;
   return IWDFT_OK;
+}
+
+// Tables of the chirp-z attention kernel, in double precision: c[a] = exp(+j pi a^2 / M) and the length-N
+// transform (sign +) of h[n] = exp(-j pi n^2 / M), |n| < M, wrapped modulo N, divided by N and stored where the
+// kernel's first in-LDS transform leaves entry m: base-4 digit-reversed position.
+void make_chirp_tables(int64_t M, int logN, std::vector<float2>* chirp, std::vector<float2>* H) {
+  const double kPi = 3.14159265358979323846;
+  const int64_t N = (int64_t)1 << logN;
+  chirp->resize((size_t)M);
+  std::vector<std::complex<double>> h((size_t)N, 0.0);
+  for (int64_t n = 0; n < M; ++n) {
+    const double ph = kPi * (double)((n * n) % (2 * M)) / (double)M;  // exact phase reduction
+    (*chirp)[(size_t)n] = make_float2((float)std::cos(ph), (float)std::sin(ph));
+    const std::complex<double> v(std::cos(ph), -std::sin(ph));
+    h[(size_t)n] = v;
+    if (n) h[(size_t)(N - n)] = v;
+  }
+  // iterative radix-2 transform, sign +
+  for (int64_t i = 1, j = 0; i < N; ++i) {
+    int64_t bit = N >> 1;
+    for (; j & bit; bit >>= 1) j ^= bit;
+    j ^= bit;
+    if (i < j) std::swap(h[(size_t)i], h[(size_t)j]);
+  }
+  for (int64_t len = 2; len <= N; len <<= 1) {
+    for (int64_t i = 0; i < N; i += len)
+      for (int64_t j = 0; j < len / 2; ++j) {
+        const double a = 2.0 * kPi * (double)j / (double)len;
+        const std::complex<double> w(std::cos(a), std::sin(a));
+        const std::complex<double> u = h[(size_t)(i + j)], v = h[(size_t)(i + j + len / 2)] * w;
+        h[(size_t)(i + j)] = u + v;
+        h[(size_t)(i + j + len / 2)] = u - v;
+      }
+  }
+  H->resize((size_t)N);
+  for (int64_t m = 0; m < N; ++m) {
+    int64_t p = 0;
+    for (int t = 0; t < logN / 2; ++t) p |= ((m >> (2 * t)) & 3) << (logN - 2 * t - 2);
+    (*H)[(size_t)p] = make_float2((float)(h[(size_t)m].real() / (double)N), (float)(h[(size_t)m].imag() / (double)N));
+  }
 }
 
 }  // namespace
@@ -374,6 +426,13 @@ int iwdft_create(const iwdft_desc* desc, void* d_state, size_t state_bytes, void
     if (e == hipSuccess)
       e = hipMemcpy(c->state + pl.off_fold, pl.fold.data(), sizeof(uint16_t) * pl.fold.size(),
                     hipMemcpyHostToDevice);
+    if (e == hipSuccess && pl.use_chirp) {
+      std::vector<float2> chirp, H;
+      make_chirp_tables(desc->M, pl.chirp_logN, &chirp, &H);
+      e = hipMemcpy(c->state + pl.off_chirp, chirp.data(), sizeof(float2) * chirp.size(), hipMemcpyHostToDevice);
+      if (e == hipSuccess)
+        e = hipMemcpy(c->state + pl.off_chirpH, H.data(), sizeof(float2) * H.size(), hipMemcpyHostToDevice);
+    }
     if (e != hipSuccess) {
       return fail(IWDFT_ERR_HIP, "initialising the state buffer: %s", hipGetErrorString(e));
     }
@@ -397,6 +456,9 @@ int iwdft_create(const iwdft_desc* desc, void* d_state, size_t state_bytes, void
     P.bins = (const int32_t*)(c->state + pl.off_bins);
     P.weights = (const float*)(c->state + pl.off_weights);
     P.fold = (const uint16_t*)(c->state + pl.off_fold);
+    P.chirp = pl.use_chirp ? (const float2*)(c->state + pl.off_chirp) : nullptr;
+    P.chirpH = pl.use_chirp ? (const float2*)(c->state + pl.off_chirpH) : nullptr;
+    P.chirp_logN = pl.chirp_logN;
     P.FK = (float2*)(c->state + pl.off_FK);
     P.FV = (float2*)(c->state + pl.off_FV);
     P.gain = 1.0f;
@@ -459,7 +521,7 @@ int64_t iwdft_num_tokens(const iwdft_ctx* ctx) { return ctx ? ctx->T : -1; }
 
 int iwdft_prefill_kind(const iwdft_ctx* ctx) { return ctx ? (ctx->plan.use_fft_prefill ? 1 : 0) : -1; }
 
-int iwdft_attn_kind(const iwdft_ctx* ctx) { return ctx ? (ctx->plan.use_fft ? 1 : 0) : -1; }
+int iwdft_attn_kind(const iwdft_ctx* ctx) { return ctx ? (ctx->plan.use_fft ? 1 : (ctx->plan.use_chirp ? 2 : 0)) : -1; }
 
 int iwdft_set_num_tokens(iwdft_ctx* ctx, int64_t T) {
   if (!ctx) return fail(IWDFT_ERR_ARG, "ctx is NULL");
@@ -581,7 +643,7 @@ int compressed_decode_attn_static(iwdft_ctx* ctx, const void* d_q, void* d_out, 
   const size_t n_heads = (size_t)ctx->P.n_slices * (size_t)pl.G;
   const size_t rows = align256(sizeof(float2) * (size_t)pl.ws_total);
   const size_t pe_bytes = align256(sizeof(float) * n_heads * (size_t)(ctx->P.S + ctx->P.R));
-  const size_t direct_bytes = pl.use_fft ? 0 : align256(sizeof(float) * n_heads * (size_t)ctx->desc.M);
+  const size_t direct_bytes = (pl.use_fft || pl.use_chirp) ? 0 : align256(sizeof(float) * n_heads * (size_t)ctx->desc.M);
   const size_t need = 2 * rows + pe_bytes + direct_bytes;
   if (need > kStaticScratchBytes)
     return fail(IWDFT_ERR_SIZE, "compressed_decode_attn_static needs %zu bytes of scratch, the library holds %zu", need,

@@ -786,6 +786,156 @@ __global__ __launch_bounds__(kFftThreads, (MULTI && NBT > 4) ? 2 : 4) void attn_
   }
 }
 
+// ------------------------------------------------------------------------------------ B (chirp)
+// The same two length-M transforms for ANY M up to 8192 (e.g. M = context - sink - recent, Sec. 4.2.1, which is a
+// power of two only by arrangement), through the chirp-z identity  k a = (k^2 + a^2 - (a - k)^2) / 2:
+//   sum_k Z[k] e^{+j 2 pi k a / M} = c[a] * sum_k (Z[k] c[k]) h[a - k],   c[n] = e^{+j pi n^2 / M},  h = conj c,
+// a linear convolution with the chirp h, run as a circular one of length N = 2^LOGN >= 2M - 1 in LDS: transform,
+// multiply by the transform of h (host-made table, already divided by N, stored in the digit-reversed order the
+// first transform leaves), transform back.  The forward transform of the softmax weights is the conjugate chain.
+// Four N-point transforms per pair of query heads instead of two M-point ones: O(M log M) as well, ~8x the work of
+// the power-of-two kernel, against O(M |B|) of the direct sums.  One workgroup per (slice, head pair); LOGN even.
+// No pending tokens (the deferred write-back needs the power-of-two kernel).
+template <int LOGN>
+__global__ __launch_bounds__(kFftThreads, 2) void attn_chirp_kernel(Params P, const float2* __restrict__ qc,
+                                                                   float2* __restrict__ Pn, float* __restrict__ pe,
+                                                                   float scale, int pairs) {
+  static_assert((LOGN & 1) == 0, "even transform lengths only: no radix-2 stage between the passes");
+  extern __shared__ float2 smem[];
+  __shared__ float2 scratch[2 * (kFftThreads / 64)];
+  const int tid = threadIdx.x;
+  constexpr int N = 1 << LOGN;
+  float2* buf = smem;
+  float2* tab = smem + N + (N >> 5);
+  const int pair = blockIdx.x % pairs;
+  const int slice = blockIdx.x / pairs;
+  const int spl = P.batch * P.n_kv;
+  const int layer = slice / spl;
+  const int s = slice - layer * spl;
+  const LayerInfo L = P.layers[layer];
+  const int g0 = pair * 2;
+  const bool has1 = (g0 + 1) < P.G;
+  const uint32_t M = P.M;
+  const float2* q0 = qc + L.ws_off + ((int64_t)s * P.G + g0) * L.Bp;
+  const float2* q1 = has1 ? q0 + L.Bp : q0;
+  const int32_t* bins = P.bins + L.bin_off;
+  const float* wts = P.weights + L.bin_off;
+  const uint16_t* fold = P.fold + L.bin_off;
+  const float2* __restrict__ chirp = P.chirp;    // c[a], a < M
+  const float2* __restrict__ Hd = P.chirpH;      // transform of h / N, digit-reversed positions
+  const float gain = 0.5f * 1.44269504088896341f * scale * P.gain / (float)M;  // log2 units; 0.5: bin + mirror
+
+  for (int m = tid; m <= (N >> 3); m += kFftThreads) tab[m] = cis((uint32_t)m, (uint32_t)N);
+  for (int e = tid; e < N + (N >> 5); e += kFftThreads) buf[e] = make_float2(0.f, 0.f);
+
+  // Exact tokens open the softmax (raw scores q . k_e from kernel A), as in the power-of-two kernel.
+  float2 mx = make_float2(-INFINITY, -INFINITY), Z = make_float2(0.f, 0.f);
+  const int E = P.S + P.R;
+  float* pe0 = pe + ((int64_t)s_global_head(slice, P.G, g0)) * E;
+  float* pe1 = pe0 + E;
+  const float escale = 1.44269504088896341f * scale;
+  if (E > 0) {
+    float2 lm = make_float2(-INFINITY, -INFINITY);
+    for (int e = tid; e < E; e += kFftThreads) {
+      lm.x = fmaxf(lm.x, pe0[e] * escale);
+      if (has1) lm.y = fmaxf(lm.y, pe1[e] * escale);
+    }
+    mx = block_max2(lm, scratch, tid);
+    float2 ls = make_float2(0.f, 0.f);
+    for (int e = tid; e < E; e += kFftThreads) {
+      ls.x += __builtin_amdgcn_exp2f(pe0[e] * escale - mx.x);
+      if (has1) ls.y += __builtin_amdgcn_exp2f(pe1[e] * escale - mx.y);
+    }
+    Z = block_sum2(ls, scratch, tid);
+  }
+  __syncthreads();
+
+  // Hermitian spectrum of both heads (head g0 real, head g0 + 1 imaginary in time), times the chirp.  A slot can
+  // receive the direct term of bin k and the mirror term of bin M - k: successive rounds (host-made schedule).
+  for (int round = 0; round < L.fold_rounds; ++round) {
+    for (int i = tid; i < L.nb; i += kFftThreads) {
+      const uint32_t k = (uint32_t)bins[i], fr = fold[i];
+      const float w = wts[i] * gain;
+      const float2 y0 = q0[i], y1 = q1[i];
+      const float2 z0 = make_float2(y0.x * w, y0.y * w);
+      const float2 z1 = has1 ? make_float2(y1.x * w, y1.y * w) : make_float2(0.f, 0.f);
+      const uint32_t r = k, rm = k ? M - k : 0u;
+      if ((fr & 0xffu) == (uint32_t)round) {  //      z0  + j z1
+        float2 v = make_float2(z0.x - z1.y, z0.y + z1.x);
+        if (r == rm) v = make_float2(2.f * z0.x, 2.f * z1.x);  // ... plus the mirror term, same slot
+        v = cmul(v, chirp[r]);
+        if (round) v = cadd(v, buf[pad(r)]);
+        buf[pad(r)] = v;
+      }
+      if ((fr >> 8) == (uint32_t)round) {     // conj z0  + j conj z1
+        float2 v = cmul(make_float2(z0.x + z1.y, z1.x - z0.y), chirp[rm]);
+        if (round) v = cadd(v, buf[pad(rm)]);
+        buf[pad(rm)] = v;
+      }
+    }
+    __syncthreads();
+  }
+  ifft_dif<LOGN>(buf, tab, tid);
+  for (int p = tid; p < N; p += kFftThreads) buf[pad(p)] = cmul(buf[pad(p)], Hd[p]);
+  __syncthreads();
+  fft_dit<LOGN>(buf, tab, tid);
+
+  // scores of slot a < M: real part head g0, imaginary part head g0 + 1
+  float2 lm = make_float2(-INFINITY, -INFINITY);
+  for (uint32_t a = tid; a < M; a += kFftThreads) {
+    const float2 z = cmul(buf[pad(a)], chirp[a]);
+    buf[pad(a)] = z;
+    lm.x = fmaxf(lm.x, z.x);
+    lm.y = fmaxf(lm.y, z.y);
+  }
+  const float2 bm = block_max2(lm, scratch, tid);
+  const float2 mn = make_float2(fmaxf(mx.x, bm.x), fmaxf(mx.y, bm.y));
+  const float2 f = make_float2(__builtin_amdgcn_exp2f(mx.x - mn.x), __builtin_amdgcn_exp2f(mx.y - mn.y));
+  mx = mn;
+  float2 ls = make_float2(0.f, 0.f);
+  for (uint32_t a = tid; a < (uint32_t)N; a += kFftThreads) {
+    float2 v = make_float2(0.f, 0.f);
+    if (a < M) {
+      const float2 z = buf[pad(a)];
+      const float2 p = make_float2(__builtin_amdgcn_exp2f(z.x - mn.x), has1 ? __builtin_amdgcn_exp2f(z.y - mn.y) : 0.f);
+      ls.x += p.x;
+      ls.y += p.y;
+      v = cmul(p, conjf2(chirp[a]));
+    }
+    buf[pad(a)] = v;
+  }
+  const float2 bs = block_sum2(ls, scratch, tid);  // its barrier also publishes the writes above
+  Z = make_float2(Z.x * f.x + bs.x, Z.y * f.y + bs.y);
+  ifft_dif<LOGN>(buf, tab, tid);
+  for (int p = tid; p < N; p += kFftThreads) buf[pad(p)] = cmul(buf[pad(p)], conjf2(Hd[p]));
+  __syncthreads();
+  fft_dit<LOGN>(buf, tab, tid);
+
+  float2* o0 = Pn + L.ws_off + ((int64_t)s * P.G + g0) * L.Bp;
+  float2* o1 = o0 + L.Bp;
+  const float inv_M = P.gain / (float)M;
+  const float iz0 = inv_M / Z.x, iz1 = has1 ? inv_M / Z.y : 0.f;
+  for (int i = tid; i < L.Bp; i += kFftThreads) {
+    float2 r0 = make_float2(0.f, 0.f), r1 = r0;
+    if (i < L.nb) {
+      const uint32_t k = (uint32_t)bins[i];
+      const uint32_t r = k, rm = k ? M - k : 0u;
+      const float2 w1 = cmul(buf[pad(r)], conjf2(chirp[r])), w2 = cmul(buf[pad(rm)], conjf2(chirp[rm]));
+      const float2 p0 = make_float2(0.5f * (w1.x + w2.x), 0.5f * (w1.y - w2.y));
+      const float2 p1 = make_float2(0.5f * (w1.y + w2.y), 0.5f * (w2.x - w1.x));
+      const float w = wts[i];
+      r0 = make_float2(p0.x * (w * iz0), -p0.y * (w * iz0));
+      r1 = make_float2(p1.x * (w * iz1), -p1.y * (w * iz1));
+    }
+    o0[i] = r0;
+    if (has1) o1[i] = r1;
+  }
+  for (int e = tid; e < E; e += kFftThreads) {  // raw scores -> weights p_e / Z
+    pe0[e] = __builtin_amdgcn_exp2f(pe0[e] * escale - mx.x) / Z.x;
+    if (has1) pe1[e] = __builtin_amdgcn_exp2f(pe1[e] * escale - mx.y) / Z.y;
+  }
+}
+
 // ---------------------------------------------------------------------------------- B (direct)
 constexpr int kDirThreads = 256;
 constexpr int kDirStage = 1024;
@@ -956,6 +1106,25 @@ static hipError_t launch_attn_t(const Params& P, const void* q, void* out, float
     }
 #undef IWDFT_FFT_NBT
 #undef IWDFT_FFT_CASE
+  } else if (P.chirp) {
+    const int pairs = (P.G + 1) / 2;
+    const size_t lds = sizeof(float2) * (size_t)fft_lds_float2(P.chirp_logN);
+    const uint32_t gridB = (uint32_t)((uint64_t)P.n_slices * pairs);
+#define IWDFT_CHIRP_CASE(LN)                                                                             \
+  {                                                                                                      \
+    static LdsLimit lim;                                                                                 \
+    e = lim.ensure((const void*)attn_chirp_kernel<LN>, (int)lds);                                        \
+    if (e != hipSuccess) return e;                                                                       \
+    attn_chirp_kernel<LN><<<dim3(gridB), dim3(kFftThreads), lds, st>>>(P, qc, Pn, pe, scale, pairs);     \
+  }
+    switch (P.chirp_logN) {
+      case 8: IWDFT_CHIRP_CASE(8) break;
+      case 10: IWDFT_CHIRP_CASE(10) break;
+      case 12: IWDFT_CHIRP_CASE(12) break;
+      case 14: IWDFT_CHIRP_CASE(14) break;
+      default: return hipErrorInvalidValue;
+    }
+#undef IWDFT_CHIRP_CASE
   } else {
     attn_direct_kernel<<<dim3((uint32_t)gridBd), dim3(kDirThreads), 0, st>>>(P, qc, Pn, pe, scale, direct_scratch);
   }

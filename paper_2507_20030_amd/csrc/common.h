@@ -43,6 +43,12 @@ struct Params {
   const float* weights;
   const uint16_t* fold;  // per kept bin: low byte = round of its direct slot, high byte = round of its mirror slot
                          // (0xff: the mirror falls on the direct slot and is added in the same write)
+  // Chirp-z attention (any M up to 8192 when the power-of-two transforms do not apply; null otherwise):
+  // chirp[a] = exp(+j pi a^2 / M), a < M; chirpH: 2^chirp_logN entries, the transform of the conjugate chirp
+  // divided by its length, in the digit-reversed order of the in-LDS transform.
+  const float2* chirp;
+  const float2* chirpH;
+  int32_t chirp_logN;
   float2* FK;
   float2* FV;
   // Exact tokens (Sec. 4.2.1): S sink tokens and a ring of R recent tokens per slice, kv_dtype,

@@ -59,6 +59,8 @@ CONFIGS = {
     "cfg5": Config("cfg5", 80, 16, 8, 8, 128, 16384, 1638, 128, "bf16", "mixed", outlier_channels=4),
     # cfg2 with the paper's exact windows (Sec. 5.1: 10 sink tokens, 50 recent tokens)
     "cfg2w": Config("cfg2w", 32, 1, 8, 4, 128, 8192, 2048, 256, "bf16", "low", n_sink=10, n_recent=50),
+    # the same windows cut OUT of an 8192-token context: M = 8192 - 60 = 8132 is not a power of two (25 % of the bins)
+    "cfg2x": Config("cfg2x", 32, 1, 8, 4, 128, 8132, 2033, 256, "bf16", "low", n_sink=10, n_recent=50),
 }
 
 

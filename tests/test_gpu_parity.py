@@ -652,16 +652,55 @@ def test_dc_only_mask_outputs_the_mean_value_row():
     cache.close()
 
 
-@pytest.mark.parametrize("n_bins,kind", [(4096, "fft"), (4100, "direct")])
+@pytest.mark.parametrize("n_bins,kind", [(4096, "fft"), (4100, "chirp")])
 def test_most_bins_the_fft_kernels_take_and_the_fallback_beyond(n_bins, kind):
-    # 4096 kept bins per layer is the limit of the FFT attention and FFT prefill kernels; one more and the
-    # library runs the direct synthesis and the dense prefill (same results, slower)
+    # 4096 kept bins per layer is the limit of the power-of-two FFT attention and FFT prefill kernels; one more and
+    # the library runs the chirp-z attention and the dense prefill (same results, slower)
     cfg = small_cfg(L=8192, n_bins=n_bins, group=2, steps=2, n_layers=1, batch=1, n_kv_heads=2, dtype="bf16")
     bins = [np.sort(np.random.default_rng(3).choice(cfg.L, size=n_bins, replace=False)).astype(np.int32)]
     cache = make_cache(cfg, bins)
     assert B.iwdft_prefill_kind(cache.ctx) == ("fft" if kind == "fft" else "dense")
+    assert B.iwdft_attn_kind(cache.ctx) == kind
     cache.close()
     run_stream(cfg, bins, rec=(5, 40), fused=True, tag=f"maxbins-{n_bins}")
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("L,S,R,group,n_bins", [(33, 0, 0, 1, 9), (100, 2, 3, 2, 100), (129, 0, 0, 3, 40), (1000, 10, 50, 4, 250),
+                                                (2049, 0, 4, 2, 300), (3000, 0, 0, 8, 1500), (8191, 1, 1, 1, 700)])
+def test_any_length_attention_through_chirp_transforms(dtype, L, S, R, group, n_bins):
+    """M that is not a power of two (M = context - sink - recent in general): the attention runs O(M log M)
+    chirp-z transforms, all four convolution lengths; every step against the oracle (two calls and the fused step,
+    which writes back at every step here), and against the direct synthesis of the same library."""
+    cfg = small_cfg(L=L, n_bins=n_bins, group=group, dtype=dtype, steps=4, n_layers=2, batch=1, n_sink=S, n_recent=R)
+    bins = random_bins(cfg, 83)
+    c = make_cache(cfg, bins, write_every=8)
+    assert B.iwdft_attn_kind(c.ctx) == "chirp"
+    c.close()
+    run_stream(cfg, bins, tag=f"chirp-{L}", write_every=8, rec=(0, min(64, L)))
+    run_stream(cfg, bins, tag=f"chirp-{L}-fused", fused=True, write_every=8, rec=(0, min(64, L)))
+    K, V = wl.prefill_tensors(cfg, DEV)
+    a, d = make_cache(cfg, bins), make_cache(cfg, bins, flags=B.IWDFT_FLAG_DIRECT_SYNTHESIS)
+    assert B.iwdft_attn_kind(d.ctx) == "direct"
+    a.prefill(K, V)
+    d.prefill(K, V)
+    _, _, q = wl.decode_step(cfg, 0, DEV)
+    assert rel_l2(f64(a.attend(q)), f64(d.attend(q))) < (2e-5 if dtype == "f32" else 8e-3)
+    a.close()
+    d.close()
+
+
+def test_paper_windows_on_a_context_that_is_a_power_of_two_full_size():
+    """cfg2's shape with the paper's windows cut out of an 8192-token context (Sec. 5.1: 10 sink + 50 recent tokens,
+    M = 8192 - 60 = 8132): the realistic setting, chirp-z attention at full size."""
+    cfg = wl.CONFIGS["cfg2x"]
+    assert cfg.n_prefill == 8192
+    bins = wl.layer_bins(cfg)
+    c = make_cache(cfg, bins)
+    assert B.iwdft_attn_kind(c.ctx) == "chirp" and B.iwdft_prefill_kind(c.ctx) == "dense"
+    c.close()
+    run_stream(cfg, bins, steps=3, tag="cfg2w-8132")
+    run_stream(cfg, bins, steps=3, fused=True, tag="cfg2w-8132-fused")
 
 
 def test_most_exact_tokens():

@@ -56,10 +56,11 @@ def test_static_scratch_matches_workspace_form_twice_second_call_smaller():
 
 def test_static_scratch_direct_synthesis_and_size_limit():
     small = wl.Config("na_dir", 1, 1, 2, 2, 128, 96, 40, 2, "f32", "low", seed=13)   # M not a power of two
-    c = _ready_cache(small)
-    assert B.iwdft_attn_kind(c.ctx) == "direct"
-    _both(c, small, 3)
-    c.close()
+    for flags, kind in ((B.IWDFT_FLAG_DIRECT_SYNTHESIS, "direct"), (0, "chirp")):
+        c = _ready_cache(small, flags)
+        assert B.iwdft_attn_kind(c.ctx) == kind
+        _both(c, small, 3)
+        c.close()
     # a context whose rows exceed the library's scratch is refused with IWDFT_ERR_SIZE before any launch
     huge = wl.Config("na_huge", 8, 8, 8, 8, 128, 8192, 2048, 1, "bf16", "low", seed=14)
     bins = wl.layer_bins(huge)
