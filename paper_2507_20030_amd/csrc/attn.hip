@@ -457,6 +457,23 @@ __global__ __launch_bounds__(kOutThreads) void attn_out_kernel(Params P, const f
     constexpr int rep = 64 / VR;  // lanes holding the same value
     if ((lane % rep) == 0) red[wave][r * VR + lane / rep] = tot;
   }
+  // Exact tokens (weights already divided by the softmax sum): every thread takes a share of the tokens for one
+  // (channel, head) of the block, so that the rows are fetched side by side instead of one after the other.
+  static_assert(V <= kOutThreads && kOutThreads % V == 0, "one or more threads per output value");
+  constexpr int kParts = kOutThreads / V;
+  __shared__ float exs[kOutThreads];
+  const int E = P.S + P.R;
+  if (E > 0) {  // block-uniform
+    const int v = threadIdx.x % V, part = threadIdx.x / V;
+    const int dd = v / GT, g = v % GT;
+    float a = 0.f;
+    if (g0 + g < P.G) {
+      const float* w = pe + ((int64_t)slice * P.G + g0 + g) * E;
+      for (int e = part; e < E; e += kParts)
+        a += w[e] * load_kv<BF16>(exact_row_step<BF16>(P, up, true, slice, e), d0 + dd);
+    }
+    exs[threadIdx.x] = a;
+  }
   __syncthreads();
   for (int v = threadIdx.x; v < V; v += kOutThreads) {
     float tot = 0.f;
@@ -464,10 +481,10 @@ __global__ __launch_bounds__(kOutThreads) void attn_out_kernel(Params P, const f
     for (int w = 0; w < kOutThreads / 64; ++w) tot += red[w][v];
     const int dd = v / GT, g = v % GT;
     if (g0 + g < P.G) {
-      const int E = P.S + P.R;
-      const float* w = pe + ((int64_t)slice * P.G + g0 + g) * E;
-      for (int e = 0; e < E; ++e)  // exact tokens: weights already divided by the softmax sum
-        tot += w[e] * load_kv<BF16>(exact_row_step<BF16>(P, up, true, slice, e), d0 + dd);
+      if (E > 0) {
+#pragma unroll
+        for (int part = 0; part < kParts; ++part) tot += exs[part * V + v];
+      }
       if constexpr (PLAIN) {
         const float* sj = up.ps + ((int64_t)slice * P.G + g0 + g) * kMaxPend;
         for (int j = 0; j < up.np; ++j)  // pending tokens' share of the V coefficients
