@@ -50,6 +50,8 @@ def test_cfg2_full_length_fused_deferred_write_back():
 
 
 def _max_rel_l2(a, b):
+    if a.is_complex():
+        a, b = torch.view_as_real(a), torch.view_as_real(b)
     a, b = a.float(), b.float()
     return float((a - b).norm() / b.norm().clamp_min(1e-30))
 
