@@ -158,7 +158,7 @@ __global__ __launch_bounds__(qc_threads(MODE != kPlain)) void attn_qc_kernel(Par
   constexpr bool UPD = MODE != kPlain;
   constexpr int kQcThreads = qc_threads(UPD), kQcBins = qc_bins(UPD);
   __shared__ float qs[GT][kHeadDim];
-  __shared__ float xs[MODE == kUpdateN ? kMaxPend : 1][kHeadDim];  // pending K rows
+  __shared__ float xs[MODE == kUpdate1 ? 1 : kMaxPend][kHeadDim];    // pending K rows
   __shared__ float dq[MODE == kPlain ? kMaxPend : 1][GT];          // q . k_j of the pending tokens
   uint32_t bid = blockIdx.x;
   const int pass = bid % passes;
@@ -183,14 +183,20 @@ __global__ __launch_bounds__(qc_threads(MODE != kPlain)) void attn_qc_kernel(Par
   }
   if constexpr (MODE == kPlain) {
     if (up.np > 0) {  // block-uniform
+      // the pending rows go through LDS (coalesced loads, one per element), then one (token, head) dot per thread
+      for (int e = threadIdx.x; e < up.np * kHeadDim; e += kQcThreads)
+        xs[e / kHeadDim][e % kHeadDim] = pend_elem<BF16>(P, up, false, slice, e / kHeadDim, e % kHeadDim);
+      __syncthreads();
       for (int idx = threadIdx.x; idx < up.np * GT; idx += kQcThreads) {
         const int j = idx / GT, g = idx % GT;
         float dot = 0.f;
-        for (int c = 0; c < kHeadDim; ++c)
-          dot += qs[g][c] * pend_elem<BF16>(P, up, false, slice, j, c);
+#pragma unroll 8
+        for (int c = 0; c < kHeadDim; ++c) dot += qs[g][c] * xs[j][c];
         dq[j][g] = dot;
       }
-      if (chunk == 0 && pass == 0) pend_keep<BF16>(P, up, false, slice, 0, kHeadDim);
+      if (chunk == 0 && pass == 0 && up.nk && (int)threadIdx.x < kHeadDim)  // keep the newest pending K row
+        store_kv<BF16>(const_cast<void*>(up.xk),
+                       (int64_t)slice * up.stride + (int64_t)(up.np - 1) * kHeadDim + threadIdx.x, xs[up.np - 1][threadIdx.x]);
       __syncthreads();
     }
   }
@@ -463,7 +469,8 @@ __global__ __launch_bounds__(kOutThreads) void attn_out_kernel(Params P, const f
   constexpr int kParts = kOutThreads / V;
   __shared__ float exs[kOutThreads];
   const int E = P.S + P.R;
-  if (E > 0) {  // block-uniform
+  const int np_plain = PLAIN ? up.np : 0;  // pending tokens of the deferred write-back: rows weighted by kernel B's ps
+  if (E + np_plain > 0) {  // block-uniform
     const int v = threadIdx.x % V, part = threadIdx.x / V;
     const int dd = v / GT, g = v % GT;
     float a = 0.f;
@@ -471,6 +478,10 @@ __global__ __launch_bounds__(kOutThreads) void attn_out_kernel(Params P, const f
       const float* w = pe + ((int64_t)slice * P.G + g0 + g) * E;
       for (int e = part; e < E; e += kParts)
         a += w[e] * load_kv<BF16>(exact_row_step<BF16>(P, up, true, slice, e), d0 + dd);
+      if constexpr (PLAIN) {
+        const float* sj = up.ps + ((int64_t)slice * P.G + g0 + g) * kMaxPend;
+        for (int j = part; j < np_plain; j += kParts) a += sj[j] * pend_elem<BF16>(P, up, true, slice, j, d0 + dd);
+      }
     }
     exs[threadIdx.x] = a;
   }
@@ -481,14 +492,9 @@ __global__ __launch_bounds__(kOutThreads) void attn_out_kernel(Params P, const f
     for (int w = 0; w < kOutThreads / 64; ++w) tot += red[w][v];
     const int dd = v / GT, g = v % GT;
     if (g0 + g < P.G) {
-      if (E > 0) {
+      if (E + np_plain > 0) {
 #pragma unroll
         for (int part = 0; part < kParts; ++part) tot += exs[part * V + v];
-      }
-      if constexpr (PLAIN) {
-        const float* sj = up.ps + ((int64_t)slice * P.G + g0 + g) * kMaxPend;
-        for (int j = 0; j < up.np; ++j)  // pending tokens' share of the V coefficients
-          tot += sj[j] * pend_elem<BF16>(P, up, true, slice, j, d0 + dd);
       }
       store_kv<BF16>(out, ((int64_t)slice * P.G + g0 + g) * kHeadDim + d0 + dd, tot);
     }
