@@ -65,7 +65,12 @@ enum {
                                        directly instead of through FFTs (see
                                        iwdft_attn_kind for what runs otherwise)    */
   IWDFT_FLAG_DENSE_PREFILL = 2u,    /* iwdft_prefill always runs the dense contraction
-                                       at the kept bins (matrix cores)             */
+                                       at the kept bins (matrix cores).  Its operands
+                                       are fp16 pairs: inputs must lie within +-65504,
+                                       bf16 inputs below 2^-14 in magnitude lose bits
+                                       (below 2^-24 they count as 0), fp32 inputs keep
+                                       ~21 bits down to 2^-14 and an absolute 2^-25
+                                       below.  The FFT prefill has no such limits.   */
   IWDFT_FLAG_FFT_PREFILL = 4u,      /* iwdft_prefill always runs FFTs + pruning; needs
                                        M = 2^m >= 256 and <= 4096 kept bins per layer,
                                        else IWDFT_ERR_UNSUPPORTED.  With neither flag

@@ -650,6 +650,10 @@ __global__ __launch_bounds__(kFftThreads, (MULTI && NBT > 4) ? 2 : 4) void attn_
     // The entries are formed once and the rounds only place them, except in the 8-bins-per-thread kernel with
     // the 128-register budget, which has no room to keep them and forms them again in every round.
     constexpr bool kKeep = MULTI || NBT <= 4;
+    // The block twiddles e^{j 2 pi k b / M} serve the folding and, conjugated, the pruning below; the kernel with
+    // the 256-register budget keeps them, the others form them twice.
+    constexpr bool kKeepTw = MULTI && NBT > 4;
+    float2 twk[kKeepTw ? NBT : 1];
     float2 z0[kKeep ? NBT : 1], z1[kKeep ? NBT : 1];
     uint32_t fr[NBT];
     for (int round = 0; round < L.fold_rounds; ++round) {
@@ -669,6 +673,7 @@ __global__ __launch_bounds__(kFftThreads, (MULTI && NBT > 4) ? 2 : 4) void attn_
         for (int j = 0; j < NBT; ++j) {
           float2 twj = make_float2(1.f, 0.f);
           if (MULTI) twj = cis_fast((kk[j] * b) & (P.M - 1u), P.M);
+          if constexpr (kKeepTw) twk[j] = twj;
           const float w = ww[j];
           const float2 a0 = cmul(make_float2(y0[j].x * w, y0[j].y * w), twj);
           const float2 a1 = has1 ? cmul(make_float2(y1[j].x * w, y1[j].y * w), twj) : make_float2(0.f, 0.f);
@@ -743,7 +748,7 @@ __global__ __launch_bounds__(kFftThreads, (MULTI && NBT > 4) ? 2 : 4) void attn_
       const float2 p0 = make_float2(0.5f * (w1.x + w2.x), 0.5f * (w1.y - w2.y));
       const float2 p1 = make_float2(0.5f * (w1.y + w2.y), 0.5f * (w2.x - w1.x));
       if (MULTI) {
-        const float2 twc = conjf2(cis_fast((kk[j] * b) & (P.M - 1u), P.M));
+        const float2 twc = conjf2(kKeepTw ? twk[j] : cis_fast((kk[j] * b) & (P.M - 1u), P.M));
         A0[j] = cadd(make_float2(A0[j].x * f.x, A0[j].y * f.x), cmul(twc, p0));
         A1[j] = cadd(make_float2(A1[j].x * f.y, A1[j].y * f.y), cmul(twc, p1));
       } else {

@@ -13,7 +13,8 @@
 //       MFMA it needs exp(-j 2 pi k (n_base + i) / M) = base * t_i, with t_i = exp(-j 2 pi k i/M)
 //       fixed for the whole kernel and base re-derived exactly (integer phase, sincospi) at every
 //       64-token tile and stepped by exp(-j 2 pi k 16/M) in between.
-// Precision.  bf16 inputs are exact in fp16; the basis is split into fp16 hi + lo parts (two MFMAs
+// Precision.  bf16 inputs are exact in fp16 while 2^-14 <= |x| <= 65504 (smaller ones land in fp16 subnormals and
+// lose bits, larger ones overflow -- the documented input range of this path); the basis is split into fp16 hi + lo parts (two MFMAs
 // per product), which keeps ~20 bits of every basis value; fp32 inputs are split the same way
 // (three MFMAs: x_hi*b_hi + x_hi*b_lo + x_lo*b_hi).  Accumulation is fp32.
 #include "common.h"

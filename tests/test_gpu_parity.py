@@ -703,6 +703,26 @@ def test_paper_windows_on_a_context_that_is_a_power_of_two_full_size():
     run_stream(cfg, bins, steps=3, fused=True, tag="cfg2w-8132-fused")
 
 
+@pytest.mark.parametrize("scale", [2.0 ** -6, 2.0 ** 9])
+def test_dense_and_fft_prefill_agree_across_the_dense_path_input_range(scale):
+    # the dense contraction works on fp16 operand pairs (documented range +-65504, full precision above 2^-14):
+    # inside that range a K/V scale of 2^-6 ... 2^9 (values to ~2^-10 and ~2^14 with the 0.1-10 channel scales)
+    # leaves both prefills within the coefficient tolerance of the oracle and of each other
+    cfg = small_cfg(L=2048, n_bins=500, dtype="bf16", n_layers=1, batch=1, n_kv_heads=2)
+    bins = random_bins(cfg, 91)
+    K, V = wl.prefill_tensors(cfg, DEV)
+    K, V = (K.float() * scale).to(K.dtype), (V.float() * scale).to(V.dtype)
+    got = {}
+    for name, flag in (("fft", B.IWDFT_FLAG_FFT_PREFILL), ("dense", B.IWDFT_FLAG_DENSE_PREFILL)):
+        c = make_cache(cfg, bins, flags=flag)
+        c.prefill(K, V)
+        got[name] = c.export_coeffs(0)
+        ref = orc.prefill(f64(K[0, 0, 1]), bins[0])
+        assert rel_l2(c128(got[name][0][0, 1]), ref) < TOL_COEF, name
+        c.close()
+    assert rel_l2(c128(got["dense"][0]), c128(got["fft"][0])) < 2e-5 and rel_l2(c128(got["dense"][1]), c128(got["fft"][1])) < 2e-5
+
+
 def test_most_exact_tokens():
     # S + R = 1024 is the most the library takes
     cfg = small_cfg(L=512, n_bins=60, group=2, steps=3, n_layers=1, batch=1, n_sink=500, n_recent=524, dtype="bf16")
