@@ -49,7 +49,10 @@ __global__ __launch_bounds__(kAppendThreads) void append_kernel(Params P, const 
   const int64_t stride = L.Bp / 2;  // in 16-byte units
   const int64_t xbase = (int64_t)slice * x_slice_stride + d0;
 
-  constexpr int U = 8;
+  // All rows of the block in one pass: every load is issued before the first store (a loop over groups of rows
+  // drains the memory pipeline of the wave between its iterations; measured on 1638 / 2048 / 4096-bin rows:
+  // 16 rows x one pass 72 / 79 / 81 % of the HBM peak, 32 rows in 4 passes of 8: 67 / 75 / 77 %).
+  constexpr int U = DROWS;
 #pragma unroll 1
   for (int dd = 0; dd < DROWS; dd += U) {
     v4f f[U];
@@ -85,7 +88,7 @@ __global__ __launch_bounds__(kHeadDim) void ring_push_kernel(Params P, const voi
 
 hipError_t launch_absorb(const Params& P, const void* xk, const void* xv, int64_t x_stride, uint32_t tsh,
                          hipStream_t st) {
-  constexpr int DROWS = 32;
+  constexpr int DROWS = 16;
   const int chunks = (P.max_nb + kAppendBinsPerBlock - 1) / kAppendBinsPerBlock;
   const uint64_t blocks = (uint64_t)P.n_slices * chunks * (kHeadDim / DROWS) * 2;
   if (blocks > 0x7fffffffull) return hipErrorInvalidConfiguration;
