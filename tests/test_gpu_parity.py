@@ -217,6 +217,24 @@ def test_bin_weights_one_sided():
     cache.close()
 
 
+@pytest.mark.parametrize("L", [100, 75])
+def test_bin_weights_one_sided_any_length(L):
+    # the same one-sided synthesis where M is not a power of two (chirp-z attention, dense prefill, direct
+    # reconstruction); odd M has no Nyquist bin
+    cfg = small_cfg(L=L, n_bins=L // 2 + 1, group=3)
+    bins = [np.arange(L // 2 + 1, dtype=np.int32) for _ in range(cfg.n_layers)]
+    w = [np.where((b == 0) | (2 * b == L), 1.0, 2.0).astype(np.float32) for b in bins]
+    run_stream(cfg, bins, weights=w, steps=3, rec=(0, 32), tag=f"one-sided-{L}")
+    run_stream(cfg, bins, weights=w, steps=3, rec=(0, 32), fused=True, tag=f"one-sided-{L}-fused")
+    K, V = wl.prefill_tensors(cfg, DEV)
+    cache = make_cache(cfg, bins, w)
+    assert B.iwdft_attn_kind(cache.ctx) == "chirp"
+    cache.prefill(K, V)
+    Kt, Vt = cache.reconstruct(1, 0, cfg.L)
+    assert rel_l2(f64(Kt), f64(K[1])) < 1e-5 and rel_l2(f64(Vt), f64(V[1])) < 1e-5
+    cache.close()
+
+
 def test_many_wraps_slot_shift():
     # more appends than M: the shift (T - M) mod M wraps several times
     cfg = small_cfg(L=64, n_bins=20, group=1, steps=150, n_layers=1, batch=1)
