@@ -47,6 +47,8 @@ struct Plan {  // byte offsets inside the two caller buffers, derived from a des
   bool use_chirp = false;        // ... through chirp-z transforms (any M up to kChirpMaxM when use_fft is false)
   int chirp_logN = 0;            // length of its circular convolutions
   size_t off_chirp = 0, off_chirpH = 0;
+  int64_t tw_Q = 0;              // length of the power-of-two in-LDS transforms (0: none), table at off_tw
+  size_t off_tw = 0;
   bool use_fft_prefill = false;  // prefill through FFTs (else the dense MFMA contraction)
   int write_every = 1;           // fused decode step: coefficients written back every this many tokens
   size_t off_layers = 0, off_bins = 0, off_weights = 0, off_fold = 0, off_FK = 0, off_FV = 0, state_bytes = 0;
@@ -185,6 +187,8 @@ int make_plan(const iwdft_desc* d, Plan* pl) {
   pl->off_fold = o;    o = align256(o + sizeof(uint16_t) * (size_t)pl->n_bins_total);
   pl->off_chirp = o;   o = align256(o + (pl->use_chirp ? sizeof(float2) * (size_t)d->M : 0));
   pl->off_chirpH = o;  o = align256(o + (pl->use_chirp ? sizeof(float2) * ((size_t)1 << pl->chirp_logN) : 0));
+  pl->tw_Q = (pow2 && (uint64_t)d->M >= kFftMinM) ? (d->M < kFftMaxQ ? d->M : kFftMaxQ) : 0;
+  pl->off_tw = o;      o = align256(o + (pl->tw_Q ? sizeof(float2) * (size_t)(pl->tw_Q / 8 + 1) : 0));
   pl->off_FK = o;      o = align256(o + sizeof(float2) * (size_t)coef);
   pl->off_FV = o;      o = align256(o + sizeof(float2) * (size_t)coef);
   const size_t esz = d->kv_dtype == IWDFT_BF16 ? 2 : 4;
@@ -433,6 +437,15 @@ int iwdft_create(const iwdft_desc* desc, void* d_state, size_t state_bytes, void
       if (e == hipSuccess)
         e = hipMemcpy(c->state + pl.off_chirpH, H.data(), sizeof(float2) * H.size(), hipMemcpyHostToDevice);
     }
+    if (e == hipSuccess && pl.tw_Q) {
+      const double kTwoPi = 6.28318530717958647692;
+      std::vector<float2> tw((size_t)(pl.tw_Q / 8 + 1));
+      for (size_t m = 0; m < tw.size(); ++m) {
+        const double ph = kTwoPi * (double)m / (double)pl.tw_Q;
+        tw[m] = make_float2((float)std::cos(ph), (float)std::sin(ph));
+      }
+      e = hipMemcpy(c->state + pl.off_tw, tw.data(), sizeof(float2) * tw.size(), hipMemcpyHostToDevice);
+    }
     if (e != hipSuccess) {
       return fail(IWDFT_ERR_HIP, "initialising the state buffer: %s", hipGetErrorString(e));
     }
@@ -459,6 +472,7 @@ int iwdft_create(const iwdft_desc* desc, void* d_state, size_t state_bytes, void
     P.chirp = pl.use_chirp ? (const float2*)(c->state + pl.off_chirp) : nullptr;
     P.chirpH = pl.use_chirp ? (const float2*)(c->state + pl.off_chirpH) : nullptr;
     P.chirp_logN = pl.chirp_logN;
+    P.tw8 = pl.tw_Q ? (const float2*)(c->state + pl.off_tw) : nullptr;
     P.FK = (float2*)(c->state + pl.off_FK);
     P.FV = (float2*)(c->state + pl.off_FV);
     P.gain = 1.0f;

@@ -586,7 +586,7 @@ __global__ __launch_bounds__(kFftThreads, (MULTI && NBT > 4) ? 2 : 4) void attn_
   // 0.5: each bin is split into k and its mirror.
   const float gain = 0.5f * 1.44269504088896341f * scale * P.gain / (float)P.M;
 
-  for (int m = tid; m <= (Q >> 3); m += kFftThreads) tab[m] = cis((uint32_t)m, (uint32_t)Q);
+  for (int m = tid; m <= (Q >> 3); m += kFftThreads) tab[m] = P.tw8[m];  // exp(+j 2 pi m / Q), host-made
 
   float2 A0[NBT], A1[NBT];  // running sums over blocks (MULTI) / the single result
   uint32_t kk[NBT];

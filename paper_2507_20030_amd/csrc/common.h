@@ -49,6 +49,9 @@ struct Params {
   const float2* chirp;
   const float2* chirpH;
   int32_t chirp_logN;
+  // Twiddle octant of the in-LDS power-of-two transforms: tw8[m] = exp(+j 2 pi m / Q), m = 0 .. Q/8, with
+  // Q = min(M, 8192); made on the host in double precision (null unless M = 2^m >= 256).
+  const float2* tw8;
   float2* FK;
   float2* FV;
   // Exact tokens (Sec. 4.2.1): S sink tokens and a ring of R recent tokens per slice, kv_dtype,

@@ -79,7 +79,7 @@ __device__ __forceinline__ int butterfly_of(int t) {
 template <int LOGQ, int LS2, bool INV>
 __device__ __forceinline__ void fft_pass16(float2* buf, const float2* tab, int tid) {
   constexpr int Q = 1 << LOGQ, s2 = 1 << LS2, NB = Q / 16;
-  constexpr int sh1 = LOGQ - LS2 - 4, sh2 = LOGQ - LS2 - 2;
+  constexpr int sh1 = LOGQ - LS2 - 4;
 #pragma unroll
   for (int it = 0; it < (NB + kFftThreads - 1) / kFftThreads; ++it) {
     const int t = it * kFftThreads + tid;

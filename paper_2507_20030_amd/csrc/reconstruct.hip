@@ -127,7 +127,7 @@ __global__ __launch_bounds__(kFftThreads, 4) void reconstruct_fft_kernel(Params 
   const float gain = 0.5f * P.gain / (float)P.M;
   char* orow = out + (int64_t)s * n_slots * kRow + pair * 2 * kElem;
 
-  for (int m = tid; m <= (Q >> 3); m += kFftThreads) tab[m] = cis((uint32_t)m, (uint32_t)Q);
+  for (int m = tid; m <= (Q >> 3); m += kFftThreads) tab[m] = P.tw8[m];  // exp(+j 2 pi m / Q), host-made
 
   for (uint32_t b = 0; b < Pb; ++b) {
     int lt = tid;
