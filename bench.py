@@ -139,6 +139,7 @@ def main():
                "coefficient_GB_per_tensor": sz.coef_bytes / 1e9}
         c1 = new_cache(cfg, bins)
         res["attn_kind"] = B.iwdft_attn_kind(c1.ctx)
+        res["attn_pipelined"] = B.iwdft_attn_pipelined(c1.ctx)   # phases A and B share launches: phase_A_ms = A + B
         pe = mk(2)
         c1.prefill(K, V, stream)
         pe[0].record(stream)
@@ -181,6 +182,28 @@ def main():
                                          "phase_A_frac_hbm_peak": frac(sz.coef_bytes, ph[0]),
                                          "phase_C_frac_hbm_peak": frac(sz.coef_bytes, ph[2]),
                                          "phase_B_fp32_TFLOPps": sz.fft_flop / (ph[1] * 1e-3) / 1e12 if ph[1] > 0 else None}
+        if res["attn_pipelined"]:
+            res["compressed_decode_attn"]["phase_A_frac_hbm_peak"] = None    # phase "A" holds A + B here
+            # the same call with the three kernels one after the other (IWDFT_FLAG_SERIAL_PHASES)
+            free(c1)
+            c1 = new_cache(cfg, bins, flags=B.IWDFT_FLAG_SERIAL_PHASES)
+            c1.prefill(K, V, stream)
+            c1.attend(pool[0][2], out, 0.0, stream)
+            se = mk(2)
+            B.iwdft_phase_timing(c1.ctx, True)
+            se[0].record(stream)
+            for i in range(n):
+                c1.attend(pool[i % len(pool)][2], out, 0.0, stream)
+            se[1].record(stream)
+            torch.cuda.synchronize()
+            ph, calls = B.iwdft_phase_times(c1.ctx)
+            B.iwdft_phase_timing(c1.ctx, False)
+            ph = [m / max(calls, 1) for m in ph]
+            res["compressed_decode_attn_serial_phases"] = {
+                "avg_us": 1e3 * se[0].elapsed_time(se[1]) / n, "frac_hbm_peak": frac(sz.attn_bytes, se[0].elapsed_time(se[1]) / n),
+                "phase_A_ms": ph[0], "phase_B_ms": ph[1], "phase_C_ms": ph[2],
+                "phase_A_frac_hbm_peak": frac(sz.coef_bytes, ph[0]), "phase_C_frac_hbm_peak": frac(sz.coef_bytes, ph[2]),
+                "phase_B_fp32_TFLOPps": sz.fft_flop / (ph[1] * 1e-3) / 1e12 if ph[1] > 0 else None}
         # fused step, coefficients written back at every step
         for i in range(2):
             c1.step(*pool[i % len(pool)], out, 0.0, stream)
@@ -332,6 +355,7 @@ def main():
     ph_ro = [m / max(n_ro, 1) for m in ph_ro]
     pre_kind = B.iwdft_prefill_kind(cache.ctx)
     attn_kind = B.iwdft_attn_kind(cache.ctx)
+    pipelined = B.iwdft_attn_pipelined(cache.ctx)    # read-only steps: kernels A and B share launches (phase 0 = A + B)
     pre_ms = np.array([p[0].elapsed_time(p[1]) for p in pre])
     call_ms = lambda rows, pick, a=0, b=2: np.array([e[a].elapsed_time(e[b]) for row in rows
                                                     for i, e in row.items() if pick(i)] or [float("nan")])
@@ -375,7 +399,9 @@ def main():
             for k_ in ("A_read_only", "B_read_only", "C_read_only"):
                 share[k_] = 0.0
         b_ms = (share["B_read_only"] + share["B_write_back"]) / dsteps
-        share_kernel = {"attn_qc_kernel<plain> (phase A, read-only steps)": share["A_read_only"],
+        name_a = ("attn_ab_kernel (phases A + B pipelined over groups of slices, read-only steps)" if pipelined and J > 1
+                  else "attn_qc_kernel<plain> (phase A, read-only steps)")
+        share_kernel = {name_a: share["A_read_only"],
                         "attn_out_kernel<plain> (phase C, read-only steps)": share["C_read_only"],
                         "attn_fft_kernel (phase B, every step)": share["B_read_only"] + share["B_write_back"],
                         "attn_qc_kernel<update> (phase A, write-back steps)": share["A_write_back"],
@@ -406,12 +432,19 @@ def main():
             rb, rms, tkey = 2 * sz.coef_bytes, ph_wb[0], f"step_qc_{cfg.name}"
         elif "phase C, write-back" in dom:
             rb, rms, tkey = 2 * sz.coef_bytes, ph_wb[2], f"step_out_{cfg.name}"
+        elif dom.startswith("attn_ab_kernel"):
+            rb, rms, tkey = sz.coef_bytes, ph_ro[0], f"attn_ab_{cfg.name}"
         elif "phase A" in dom:
             rb, rms, tkey = sz.coef_bytes, ph_ro[0], f"attn_qc_{cfg.name}"
         else:
             rb, rms, tkey = sz.coef_bytes, ph_ro[2], f"attn_out_{cfg.name}"
         roofline = {"kernel": dom, "bound": "hbm", "achieved": gbps(rb, rms), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                     "frac": frac(rb, rms), "algorithmic_GB": rb / 1e9}
+        if dom.startswith("attn_ab_kernel"):
+            # these launches stream the K coefficients once (the algorithmic bytes) AND run every transform of the step
+            roofline["also_runs_fp32_TFLOPps"] = sz.fft_flop / (rms * 1e-3) / 1e12
+            roofline["note"] = ("one pass over the K coefficients plus all transforms of the step (vector ALU); the "
+                                "three kernels one after the other: see per_config ... compressed_decode_attn_serial_phases")
     roofline["traffic"] = traffic_all.get(tkey)     # GB per launch from rocprofv3 counters, null if not profiled
     if roofline["traffic"] is None:
         roofline["traffic_note"] = f"no counter run recorded for {tkey}"
@@ -448,6 +481,7 @@ def main():
             "step_definition": step_def,
             "prefill_kind": pre_kind,
             "attn_kind": attn_kind,
+            "attn_pipelined": pipelined,
         },
         "job": {"prefill_ms": pre_avg},
         "roofline": roofline,

@@ -76,13 +76,20 @@ enum {
                                        else IWDFT_ERR_UNSUPPORTED.  With neither flag
                                        the library picks: FFT when it applies and some
                                        layer keeps >= 384 bins                     */
-  IWDFT_FLAG_SHORTCUT = 8u          /* the variant of the update that Sec. 4.1 mentions for long
+  IWDFT_FLAG_SHORTCUT = 8u,         /* the variant of the update that Sec. 4.1 mentions for long
                                        contexts, the factor (N-1)/N of Eq. infi-dft taken as 1:
                                        S_{T+1}[k] = W_k ( S_T[k] + x_T / (T+1) ).  Tokens no longer
                                        weigh the same (prefill tokens keep 1/M, token n enters with
                                        1/(n+1)); reconstruction and attention read the state as they
                                        read S_T otherwise (gain T/M).  iwdft_append_attn then runs
                                        its two calls in sequence and write_every is taken as 1.    */
+  IWDFT_FLAG_SERIAL_PHASES = 16u    /* decode attention (Sec. 4.2.2 "Calculating Attention") always runs
+                                       its three kernels one after the other.  Without the flag, long
+                                       contexts with many slices (M >= 16384, >= 2048 pairs of query
+                                       heads in all, more than 1024 kept bins in some layer, 4 or 8 query
+                                       heads per pass) walk the slices in groups and put the transforms
+                                       of one group into the same launches as the K-coefficient stream of
+                                       the next.  Same arithmetic, same results bit for bit.          */
 };
 
 typedef struct {
@@ -141,6 +148,13 @@ int iwdft_prefill_kind(const iwdft_ctx* ctx);
  * IWDFT_FLAG_DIRECT_SYNTHESIS, for M < 32, and for M > 8192 that is not a power of two); -1 if ctx is NULL.
  * With 0 or 2, desc.write_every is taken as 1. */
 int iwdft_attn_kind(const iwdft_ctx* ctx);
+
+/* Whether decode attention on this context (Sec. 4.2.2 "Calculating Attention") walks the slices in groups, with
+ * the transforms of one group in the same launches as the K-coefficient stream of the next (see
+ * IWDFT_FLAG_SERIAL_PHASES for the conditions): 1 = yes, 0 = the three kernels run one after the other;
+ * -1 if ctx is NULL.  Results are identical either way; with 1 the marks of iwdft_phase_timing cannot separate
+ * the first two kernels (their time is reported as phase 0, phase 1 reads ~0). */
+int iwdft_attn_pipelined(const iwdft_ctx* ctx);
 
 /* Streaming update with one new token per sequence (Eq. infi-dft, Eq. update-iwdft).
  * d_tok_k, d_tok_v: [n_layers][batch][n_kv_heads][head_dim], kv_dtype.  T -> T+1.

@@ -21,12 +21,13 @@ IWDFT_FLAG_DIRECT_SYNTHESIS = 1
 IWDFT_FLAG_DENSE_PREFILL = 2
 IWDFT_FLAG_FFT_PREFILL = 4
 IWDFT_FLAG_SHORTCUT = 8
+IWDFT_FLAG_SERIAL_PHASES = 16
 IWDFT_STATIC_SCRATCH_BYTES = 64 << 20
 
 EXPORTED = [
     "iwdft_query_bytes", "iwdft_create", "iwdft_destroy", "iwdft_prefill", "iwdft_append",
     "iwdft_reconstruct", "iwdft_reconstruct_grid", "compressed_decode_attn", "iwdft_append_attn", "iwdft_export_coeffs", "iwdft_export_bins",
-    "iwdft_num_tokens", "iwdft_set_num_tokens", "iwdft_last_error", "iwdft_phase_timing", "iwdft_phase_times", "iwdft_prefill_kind", "iwdft_attn_kind",
+    "iwdft_num_tokens", "iwdft_set_num_tokens", "iwdft_last_error", "iwdft_phase_timing", "iwdft_phase_times", "iwdft_prefill_kind", "iwdft_attn_kind", "iwdft_attn_pipelined",
     "iwdft_select_bins", "iwdft_ablate_chunk", "iwdft_flush", "compressed_decode_attn_static",
 ]
 
@@ -79,6 +80,7 @@ def load_library() -> ctypes.CDLL:
     lib.iwdft_append_attn.argtypes = [vp, vp, vp, vp, vp, f32, vp]
     lib.iwdft_prefill_kind.argtypes = [vp]
     lib.iwdft_attn_kind.argtypes = [vp]
+    lib.iwdft_attn_pipelined.argtypes = [vp]
     lib.iwdft_flush.argtypes = [vp, vp]
     lib.iwdft_select_bins.argtypes = [ctypes.POINTER(ctypes.c_float), i32, i32, i64, ctypes.c_double,
                                       ctypes.POINTER(ctypes.c_int64), ctypes.POINTER(ctypes.c_int32), i64]
@@ -226,6 +228,10 @@ def iwdft_prefill_kind(ctx) -> str:
 
 def iwdft_attn_kind(ctx) -> str:
     return {0: "direct", 1: "fft", 2: "chirp"}[load_library().iwdft_attn_kind(ctx)]
+
+
+def iwdft_attn_pipelined(ctx) -> bool:
+    return load_library().iwdft_attn_pipelined(ctx) == 1
 
 
 def iwdft_phase_timing(ctx, enable: bool) -> None:

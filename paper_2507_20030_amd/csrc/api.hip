@@ -76,7 +76,7 @@ int make_plan(const iwdft_desc* d, Plan* pl) {
   if (d->write_every > (uint32_t)kMaxPend)
     return fail(IWDFT_ERR_ARG, "write_every = %u exceeds %d", d->write_every, kMaxPend);
   if (d->flags & ~(uint32_t)(IWDFT_FLAG_DIRECT_SYNTHESIS | IWDFT_FLAG_DENSE_PREFILL | IWDFT_FLAG_FFT_PREFILL |
-                             IWDFT_FLAG_SHORTCUT))
+                             IWDFT_FLAG_SHORTCUT | IWDFT_FLAG_SERIAL_PHASES))
     return fail(IWDFT_ERR_ARG, "unknown bits in flags: 0x%x", d->flags);
   if ((d->flags & IWDFT_FLAG_DENSE_PREFILL) && (d->flags & IWDFT_FLAG_FFT_PREFILL))
     return fail(IWDFT_ERR_ARG, "flags ask for both the dense and the FFT prefill");
@@ -477,6 +477,7 @@ int iwdft_create(const iwdft_desc* desc, void* d_state, size_t state_bytes, void
     P.FV = (float2*)(c->state + pl.off_FV);
     P.gain = 1.0f;
     P.x_scale = 1.0f;
+    P.serial_phases = (desc->flags & IWDFT_FLAG_SERIAL_PHASES) ? 1 : 0;
     P.S = desc->n_sink;
     P.R = desc->n_recent;
     P.sinkK = c->state + pl.off_sinkK;
@@ -534,6 +535,8 @@ int iwdft_phase_times(iwdft_ctx* ctx, double* ms, int64_t* n_calls) {
 int64_t iwdft_num_tokens(const iwdft_ctx* ctx) { return ctx ? ctx->T : -1; }
 
 int iwdft_prefill_kind(const iwdft_ctx* ctx) { return ctx ? (ctx->plan.use_fft_prefill ? 1 : 0) : -1; }
+
+int iwdft_attn_pipelined(const iwdft_ctx* ctx) { return ctx ? (attn_pipelines(ctx->P, ctx->plan.use_fft) ? 1 : 0) : -1; }
 
 int iwdft_attn_kind(const iwdft_ctx* ctx) { return ctx ? (ctx->plan.use_fft ? 1 : (ctx->plan.use_chirp ? 2 : 0)) : -1; }
 

@@ -151,16 +151,20 @@ __device__ __forceinline__ v4f lane_twiddles(const Params& P, const LayerInfo& L
 // streaming update, Eq. infi-dft in the fixed frame: F += x e^{+j 2 pi k (T-M)/M}), is written back, and
 // the updated value feeds qc, so that K coefficients are read once per step instead of twice (needs
 // passes == 1).  kPlain with pending tokens: qc[k] += sum_j (q . k_j) e^{j theta_jk} instead.
-template <bool BF16, int GT, int MODE>
-__global__ __launch_bounds__(qc_threads(MODE != kPlain)) void attn_qc_kernel(Params P, const void* __restrict__ q,
-                                                            float2* __restrict__ qc, float* __restrict__ pe,
-                                                            int chunks, int passes, StepUpdate up) {
+// Shared memory of one block, in floats: q rows, pending K rows, the dots q . k_j.
+constexpr int qc_smem_floats(int GT, int MODE) {
+  return GT * kHeadDim + (MODE == kUpdate1 ? 1 : kMaxPend) * kHeadDim + (MODE == kPlain ? kMaxPend : 1) * GT;
+}
+// The work of logical block `bid` (wave-uniform) with THREADS threads; `sm` holds qc_smem_floats floats.
+template <bool BF16, int GT, int MODE, int THREADS>
+__device__ __forceinline__ void qc_body(const Params& P, const void* __restrict__ q, float2* __restrict__ qc,
+                                        float* __restrict__ pe, int chunks, int passes, const StepUpdate& up,
+                                        uint32_t bid, float* sm) {
   constexpr bool UPD = MODE != kPlain;
-  constexpr int kQcThreads = qc_threads(UPD), kQcBins = qc_bins(UPD);
-  __shared__ float qs[GT][kHeadDim];
-  __shared__ float xs[MODE == kUpdate1 ? 1 : kMaxPend][kHeadDim];    // pending K rows
-  __shared__ float dq[MODE == kPlain ? kMaxPend : 1][GT];          // q . k_j of the pending tokens
-  uint32_t bid = blockIdx.x;
+  constexpr int kQcThreads = THREADS, kQcBins = THREADS * 2;
+  float (*qs)[kHeadDim] = (float (*)[kHeadDim])sm;                            // [GT][128]
+  float (*xs)[kHeadDim] = qs + GT;                                             // pending K rows
+  float (*dq)[GT] = (float (*)[GT])(xs + (MODE == kUpdate1 ? 1 : kMaxPend));   // q . k_j of the pending tokens
   const int pass = bid % passes;
   bid /= passes;
   const int chunk = bid % chunks;
@@ -305,6 +309,14 @@ __global__ __launch_bounds__(qc_threads(MODE != kPlain)) void attn_qc_kernel(Par
   for (int g = 0; g < GT; ++g)
     if (g0 + g < P.G)
       *(v4f*)(qc + L.ws_off + ((int64_t)s * P.G + g0 + g) * L.Bp + i0) = acc[g];
+}
+
+template <bool BF16, int GT, int MODE>
+__global__ __launch_bounds__(qc_threads(MODE != kPlain)) void attn_qc_kernel(Params P, const void* __restrict__ q,
+                                                            float2* __restrict__ qc, float* __restrict__ pe,
+                                                            int chunks, int passes, StepUpdate up) {
+  __shared__ float sm[qc_smem_floats(GT, MODE)];
+  qc_body<BF16, GT, MODE, qc_threads(MODE != kPlain)>(P, q, qc, pe, chunks, passes, up, blockIdx.x, sm);
 }
 
 // ------------------------------------------------------------------------------------------ C
@@ -556,20 +568,19 @@ __device__ __forceinline__ int64_t s_global_head(int slice, int G, int g) { retu
 // Register budget: 128 VGPRs (two workgroups per CU) except for the multi-block kernel with 8 bins
 // per thread, whose per-bin inputs and running sums (~80 registers) then spill; that one gets 256
 // VGPRs and one workgroup per CU (measured 1.5x faster than spilling at two per CU).
+// The work of logical block `bid` (wave-uniform); smem: fft_lds_float2(LOGQ) float2.
 template <int LOGQ, int NBT, bool MULTI>
-__global__ __launch_bounds__(kFftThreads, (MULTI && NBT > 4) ? 2 : 4) void attn_fft_kernel(Params P, const float2* __restrict__ qc,
-                                                                 float2* __restrict__ Pn, float* __restrict__ pe,
-                                                                 float scale, int pairs, int np, uint32_t ptsh,
-                                                                 float* __restrict__ ps) {
-  extern __shared__ float2 smem[];
+__device__ __forceinline__ void fft_body(const Params& P, const float2* __restrict__ qc, float2* __restrict__ Pn,
+                                         float* __restrict__ pe, float scale, int pairs, int np, uint32_t ptsh,
+                                         float* __restrict__ ps, uint32_t bid, float2* smem) {
   __shared__ float2 scratch[2 * (kFftThreads / 64)];  // row 0: block_max2, row 1: block_sum2
   __shared__ float pscr[kFftThreads / 64][2 * kMaxPend];
   const int tid = threadIdx.x;
   constexpr int Q = 1 << LOGQ;
   float2* buf = smem;                 // Q samples, padded
   float2* tab = smem + Q + (Q >> 5);  // Q/8 + 1 twiddles
-  const int pair = blockIdx.x % pairs;
-  const int slice = blockIdx.x / pairs;
+  const int pair = bid % pairs;
+  const int slice = bid / pairs;
   const int spl = P.batch * P.n_kv;
   const int layer = slice / spl;
   const int s = slice - layer * spl;
@@ -823,6 +834,40 @@ __global__ __launch_bounds__(kFftThreads, (MULTI && NBT > 4) ? 2 : 4) void attn_
   }
 }
 
+template <int LOGQ, int NBT, bool MULTI>
+__global__ __launch_bounds__(kFftThreads, (MULTI && NBT > 4) ? 2 : 4) void attn_fft_kernel(Params P, const float2* __restrict__ qc,
+                                                                 float2* __restrict__ Pn, float* __restrict__ pe,
+                                                                 float scale, int pairs, int np, uint32_t ptsh,
+                                                                 float* __restrict__ ps) {
+  extern __shared__ float2 smem[];
+  fft_body<LOGQ, NBT, MULTI>(P, qc, Pn, pe, scale, pairs, np, ptsh, ps, blockIdx.x, smem);
+}
+
+// ----------------------------------------------------------------------------------- A + B
+// Kernel-A blocks of one group of slices and kernel-B blocks of ANOTHER group in one launch, dealt to the CUs
+// side by side: B's transforms run on the vector ALU while A's blocks wait on HBM.  Nothing inside a launch
+// depends on anything else inside it -- the host walks the groups as a pipeline, launch i = A(group i) next to
+// B(group i - 1), so B always reads qc rows that an earlier launch on the same stream completed.
+// Hardware block ids go round-robin to the 8 XCDs; the role is a function of the per-XCD sequence number, so
+// every XCD sees the same even mix (nA8 / nB8 = blocks of either role per XCD, rounded up).
+// A runs in its read-only form with 512 threads (1024 bins per block).
+template <bool BF16, int GT, int LOGQ, int NBT, bool MULTI>
+__global__ __launch_bounds__(kFftThreads, (MULTI && NBT > 4) ? 2 : 4) void attn_ab_kernel(
+    Params P, const void* __restrict__ q, float2* __restrict__ qc, float* __restrict__ pe, int chunks, StepUpdate up,
+    float2* __restrict__ Pn, float scale, int pairs, int np, float* __restrict__ ps, uint32_t baseA, uint32_t nA,
+    uint32_t nA8, uint32_t baseB, uint32_t nB, uint32_t nB8) {
+  extern __shared__ float2 smem[];
+  const uint32_t seq = blockIdx.x >> 3, xcd = blockIdx.x & 7u, tot = nA8 + nB8;
+  const uint32_t cb = (uint32_t)(((uint64_t)seq * nB8) / tot), cb1 = (uint32_t)(((uint64_t)(seq + 1) * nB8) / tot);
+  if (cb1 > cb) {
+    const uint32_t id = (uint32_t)__builtin_amdgcn_readfirstlane((int)(cb * 8 + xcd));
+    if (id < nB) fft_body<LOGQ, NBT, MULTI>(P, qc, Pn, pe, scale, pairs, np, up.tsh, ps, baseB + id, smem);
+  } else {
+    const uint32_t id = (uint32_t)__builtin_amdgcn_readfirstlane((int)((seq - cb) * 8 + xcd));
+    if (id < nA) qc_body<BF16, GT, kPlain, kFftThreads>(P, q, qc, pe, chunks, 1, up, baseA + id, (float*)smem);
+  }
+}
+
 // ------------------------------------------------------------------------------------ B (chirp)
 // The same two length-M transforms for ANY M up to 8192 (e.g. M = context - sink - recent, Sec. 4.2.1, which is a
 // power of two only by arrangement), through the chirp-z identity  k a = (k^2 + a^2 - (a - k)^2) / 2:
@@ -1064,6 +1109,14 @@ __global__ __launch_bounds__(kDirThreads) void attn_direct_kernel(Params P, cons
 }
 
 // --------------------------------------------------------------------------------------- host
+constexpr uint32_t kAbMinB = 1024, kAbMaxGroups = 8;  // fewest B blocks per group of slices, most groups
+static int heads_per_pass(int G);
+bool attn_pipelines(const Params& P, bool use_fft) {
+  const int GT = heads_per_pass(P.G);
+  const int per_thread = (P.max_Bp + kFftThreads - 1) / kFftThreads;
+  return use_fft && P.G <= GT && (GT == 4 || GT == 8) && P.M >= 16384u && per_thread > 2 &&
+         (uint64_t)P.n_slices * ((P.G + 1) / 2) >= 2 * kAbMinB && !P.serial_phases;
+}
 static int heads_per_pass(int G) { return G <= 2 ? G : (G <= 4 ? 4 : 8); }  // 1, 2, 4 or 8; heads beyond G are masked
 
 // up / mode: the fused decode step's pending tokens and what kernels A and C do with them (see StepUpdate).
@@ -1103,13 +1156,61 @@ static hipError_t launch_attn_t(const Params& P, const void* q, void* out, float
   hipError_t e = hipSuccess;
 #define IWDFT_MARK(I)                                            \
   if (marks && (e = hipEventRecord(marks->ev[I], st)) != hipSuccess) return e;
+  // Long contexts with many slices: A and B run as a pipeline over groups of slices, each launch holding the
+  // A blocks of one group next to the B blocks of the group before (attn_ab_kernel).  Worth it when B is a
+  // large share of the step and a group still fills the chip: M >= 16384 and at least kAbMinB B blocks per group;
+  // measured (A + B, all slices, ms): 2048 slices x 4096 bins, M = 32768: 2.36 -> 1.9; 10240 x 1638, M = 16384:
+  // 6.3 -> 5.5; no gain at M = 8192 (B is 30 us) or with 512 B blocks in all (M = 131072, 256 slices).
+  const int pairsB = (P.G + 1) / 2;
+  const int per_thread_ab = (P.max_Bp + kFftThreads - 1) / kFftThreads;
+  const uint64_t nB_all = (uint64_t)P.n_slices * pairsB;
+  const bool pipeline_ab = mode == kPlain && attn_pipelines(P, use_fft);
+  if (pipeline_ab) {
+    IWDFT_MARK(0)
+    const size_t lds = sizeof(float2) * (size_t)fft_lds_float2(kFftMaxLogQ);
+    const int chunksA = (P.max_Bp + 2 * kFftThreads - 1) / (2 * kFftThreads);
+    uint32_t groups = (uint32_t)(nB_all / kAbMinB);
+    if (groups > kAbMaxGroups) groups = kAbMaxGroups;
+    const uint32_t spg = ((uint32_t)P.n_slices + groups - 1) / groups;  // slices per group
+    for (uint32_t i = 0; i <= groups; ++i) {
+      // A: group i, B: group i - 1
+      const uint32_t a0 = i * spg, a1 = i < groups ? (a0 + spg < (uint32_t)P.n_slices ? a0 + spg : (uint32_t)P.n_slices) : a0;
+      const uint32_t b0 = i ? (i - 1) * spg : 0, b1 = i ? (b0 + spg < (uint32_t)P.n_slices ? b0 + spg : (uint32_t)P.n_slices) : 0;
+      const uint32_t sa = a1 > a0 ? a1 - a0 : 0, sb = b1 > b0 ? b1 - b0 : 0;
+      const uint32_t nA = sa * chunksA, nB = sb * pairsB;
+      if (nA + nB == 0) continue;
+      const uint32_t nA8 = (nA + 7) / 8, nB8 = (nB + 7) / 8;
+      const uint32_t grid = (nA8 + nB8) * 8;
+#define IWDFT_AB_CASE(GTV, NBT, MULTI)                                                                          \
+  {                                                                                                             \
+    static LdsLimit lim;                                                                                        \
+    e = lim.ensure((const void*)attn_ab_kernel<BF16, GTV, kFftMaxLogQ, NBT, MULTI>, (int)lds);                  \
+    if (e != hipSuccess) return e;                                                                              \
+    attn_ab_kernel<BF16, GTV, kFftMaxLogQ, NBT, MULTI><<<dim3(grid), dim3(kFftThreads), lds, st>>>(             \
+        P, q, qc, pe, chunksA, u, Pn, scale, pairsB, np_plain, u.ps, a0 * chunksA, nA, nA8, b0 * pairsB, nB,    \
+        nB8);                                                                                                   \
+  }
+      if (GT == 4) {
+        if (per_thread_ab <= 4) IWDFT_AB_CASE(4, 4, true) else IWDFT_AB_CASE(4, 8, true)
+      } else {
+        if (per_thread_ab <= 4) IWDFT_AB_CASE(8, 4, true) else IWDFT_AB_CASE(8, 8, true)
+      }
+#undef IWDFT_AB_CASE
+      e = hipGetLastError();
+      if (e != hipSuccess) return e;
+    }
+    IWDFT_MARK(1)  // the marks cannot separate A from B here: phase A = the pipeline, phase B = nothing
+    IWDFT_MARK(2)
+  } else {
   IWDFT_MARK(0)
   IWDFT_GT_SWITCH(attn_qc_kernel, gridA, kQcThreads, P, q, qc, pe, chunks, passes, u)
   e = hipGetLastError();
   if (e != hipSuccess) return e;
   IWDFT_MARK(1)
+  }
 
-  if (use_fft) {
+  if (pipeline_ab) {
+  } else if (use_fft) {
     int logM = 0;
     while ((1u << logM) < P.M) ++logM;
     const int logQ = logM < kFftMaxLogQ ? logM : kFftMaxLogQ;
@@ -1167,7 +1268,7 @@ static hipError_t launch_attn_t(const Params& P, const void* q, void* out, float
   }
   e = hipGetLastError();
   if (e != hipSuccess) return e;
-  IWDFT_MARK(2)
+  if (!pipeline_ab) { IWDFT_MARK(2) }
 
   const int per_xcd = (int)((gridC + 7) / 8);
   if (mode == kPlain && u.np > 0) {  // deferred write-back: no append follows that could reuse cached V state

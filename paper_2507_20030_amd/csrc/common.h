@@ -60,6 +60,7 @@ struct Params {
   // absorbed token enters scaled by x_scale = M / (T + 1), and everything that reads the coefficients as the
   // paper's S_T (reconstruction, scores, outputs) applies the extra gain = T / M.
   float gain, x_scale;
+  int32_t serial_phases;  // IWDFT_FLAG_SERIAL_PHASES: never pipeline kernels A and B over groups of slices
   int32_t S, R;
   void* sinkK;
   void* sinkV;
@@ -179,6 +180,8 @@ hipError_t launch_attn(const Params& P, const void* q, void* out, float scale, f
 // ps: [slice][query head][kMaxPend] floats.  step_can_fuse: all query heads fit one pass.
 constexpr int kMaxPend = 16;
 bool heads_fit_one_pass(int G);
+// Whether decode attention on this context walks the slices in groups (kernels A and B pipelined, see attn_ab_kernel).
+bool attn_pipelines(const Params& P, bool use_fft);
 bool step_can_fuse(const Params& P);
 hipError_t launch_step(const Params& P, const void* tok_k, const void* tok_v, const void* q, void* out,
                        float scale, float2* qc, float2* Pn, float* pe, void* pend_k, void* pend_v, float* ps,

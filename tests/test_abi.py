@@ -83,6 +83,7 @@ def test_null_pointers_and_null_ctx():
     assert lib.iwdft_set_num_tokens(None, 5) == B.IWDFT_ERR_ARG
     assert lib.iwdft_prefill_kind(None) == -1
     assert lib.iwdft_attn_kind(None) == -1
+    assert lib.iwdft_attn_pipelined(None) == -1
     assert lib.iwdft_flush(None, None) == B.IWDFT_ERR_ARG
     assert lib.iwdft_phase_timing(None, 1) == B.IWDFT_ERR_ARG
     ms, n = (ctypes.c_double * 3)(), ctypes.c_int64()

@@ -170,3 +170,45 @@ def test_cfg4_long_context_drift(fused):
     stats["rec"] = check_reconstruct(cfg, cache, ora, cfg.L - 64, 64, f"{tag} end")
     print(f"\n[{tag}] " + " ".join(f"{k}={v:.2e}" for k, v in stats.items()), flush=True)
     cache.close()
+
+
+@pytest.mark.parametrize("group,n_bins,n_slices,dtype,windows", [
+    (4, 1100, 1024, "bf16", False),   # 4 heads per pass, 3-4 kept bins per thread
+    (4, 2100, 1024, "bf16", True),    # 4 heads per pass, 5-8 kept bins per thread (256-register transform), windows
+    (8, 1100, 512, "bf16", False),    # 8 heads per pass, 3-4 bins per thread
+    (8, 2100, 512, "f32", False),     # 8 heads per pass, 5-8 bins per thread, fp32 tokens
+])
+def test_pipelined_and_serial_phases_agree_bit_for_bit(group, n_bins, n_slices, dtype, windows):
+    """Long contexts with many slices run kernels A and B as a pipeline over groups of slices (the transforms of one
+    group share launches with the K stream of the next); IWDFT_FLAG_SERIAL_PHASES runs the three kernels one after
+    the other.  Same arithmetic per block, so decode attention, fused read-only steps with pending tokens, the
+    write-back step and the final state must agree bit for bit.  One shape per kernel instantiation; the oracle
+    parity of the pipelined path is covered by the full-size cfg3 / cfg5 tests above."""
+    cfg = wl.Config("pipe", n_slices // 64, 8, 8, group, 128, 16384, n_bins, 20, dtype, "mixed", seed=11,
+                    n_sink=4 if windows else 0, n_recent=12 if windows else 0)
+    bins = wl.layer_bins(cfg)
+    K, V = wl.prefill_tensors(cfg, DEV)
+    steps = [wl.decode_step(cfg, i, DEV) for i in range(18)]
+
+    def run(flags):
+        c = make_cache(cfg, bins, flags=flags | B.IWDFT_FLAG_FFT_PREFILL, write_every=16)
+        c.prefill(K, V)
+        outs = []
+        for i, (tk, tv, q) in enumerate(steps):
+            if i < 2:                       # the two-call form
+                c.append(tk, tv)
+                outs.append(c.attend(q).clone())
+            else:                           # fused steps: 15 read-only ones with 1..15 pending tokens, one write-back
+                outs.append(c.step(tk, tv, q).clone())
+        c.flush()
+        torch.cuda.synchronize()
+        return c, outs
+
+    a, outs_a = run(0)
+    b, outs_b = run(B.IWDFT_FLAG_SERIAL_PHASES)
+    for i, (x, y) in enumerate(zip(outs_a, outs_b)):
+        assert torch.isfinite(x.float()).all(), f"step {i}: non-finite output"
+        assert torch.equal(x, y), f"step {i}: pipelined and serial outputs differ (max {float((x.float() - y.float()).abs().max()):.3e})"
+    assert torch.equal(a.state, b.state), "final state differs"
+    a.close()
+    b.close()
