@@ -172,19 +172,21 @@ def test_cfg4_long_context_drift(fused):
     cache.close()
 
 
-@pytest.mark.parametrize("group,n_bins,n_slices,dtype,windows", [
-    (4, 1100, 1024, "bf16", False),   # 4 heads per pass, 3-4 kept bins per thread
-    (4, 2100, 1024, "bf16", True),    # 4 heads per pass, 5-8 kept bins per thread (256-register transform), windows
-    (8, 1100, 512, "bf16", False),    # 8 heads per pass, 3-4 bins per thread
-    (8, 2100, 512, "f32", False),     # 8 heads per pass, 5-8 bins per thread, fp32 tokens
+@pytest.mark.parametrize("group,n_bins,shape,dtype,windows", [
+    (4, 1100, (16, 8, 8), "bf16", False),   # 4 heads per pass, 3-4 kept bins per thread
+    (4, 2100, (16, 8, 8), "bf16", True),    # 4 heads per pass, 5-8 kept bins per thread (256-register transform), windows
+    (8, 1100, (8, 8, 8), "bf16", False),    # 8 heads per pass, 3-4 bins per thread
+    (8, 2100, (8, 8, 8), "f32", False),     # 8 heads per pass, 5-8 bins per thread, fp32 tokens
+    (3, 1100, (5, 2, 103), "bf16", False),  # 1030 slices, 3 query heads: block counts per group that are not multiples
+                                            # of 8 (tails of the per-XCD role sequence), a last head pair with one head
 ])
-def test_pipelined_and_serial_phases_agree_bit_for_bit(group, n_bins, n_slices, dtype, windows):
+def test_pipelined_and_serial_phases_agree_bit_for_bit(group, n_bins, shape, dtype, windows):
     """Long contexts with many slices run kernels A and B as a pipeline over groups of slices (the transforms of one
     group share launches with the K stream of the next); IWDFT_FLAG_SERIAL_PHASES runs the three kernels one after
     the other.  Same arithmetic per block, so decode attention, fused read-only steps with pending tokens, the
     write-back step and the final state must agree bit for bit.  One shape per kernel instantiation; the oracle
     parity of the pipelined path is covered by the full-size cfg3 / cfg5 tests above."""
-    cfg = wl.Config("pipe", n_slices // 64, 8, 8, group, 128, 16384, n_bins, 20, dtype, "mixed", seed=11,
+    cfg = wl.Config("pipe", shape[0], shape[1], shape[2], group, 128, 16384, n_bins, 20, dtype, "mixed", seed=11,
                     n_sink=4 if windows else 0, n_recent=12 if windows else 0)
     bins = wl.layer_bins(cfg)
     K, V = wl.prefill_tensors(cfg, DEV)
@@ -206,6 +208,7 @@ def test_pipelined_and_serial_phases_agree_bit_for_bit(group, n_bins, n_slices, 
 
     a, outs_a = run(0)
     b, outs_b = run(B.IWDFT_FLAG_SERIAL_PHASES)
+    assert B.iwdft_attn_pipelined(a.ctx) and not B.iwdft_attn_pipelined(b.ctx)
     for i, (x, y) in enumerate(zip(outs_a, outs_b)):
         assert torch.isfinite(x.float()).all(), f"step {i}: non-finite output"
         assert torch.equal(x, y), f"step {i}: pipelined and serial outputs differ (max {float((x.float() - y.float()).abs().max()):.3e})"
