@@ -600,13 +600,20 @@ __device__ __forceinline__ void fft_body(const Params& P, const float2* __restri
   for (int m = tid; m <= (Q >> 3); m += kFftThreads) tab[m] = P.tw8[m];  // exp(+j 2 pi m / Q), host-made
 
   float2 A0[NBT], A1[NBT];  // running sums over blocks (MULTI) / the single result
-  uint32_t kk[NBT];
+  // The 128-register multi-block kernel fetches its bin indices again at every use (L1 / L2 hits) instead of
+  // keeping them: fewer spilled registers (12 -> 7).
+  constexpr bool kReloadK = MULTI && NBT <= 4;
+  uint32_t kkr[kReloadK ? 1 : NBT];
 #pragma unroll
   for (int j = 0; j < NBT; ++j) {
     A0[j] = A1[j] = make_float2(0.f, 0.f);
     const int i = j * kFftThreads + tid;
-    kk[j] = (uint32_t)bins[i < L.nb ? i : L.nb - 1];
+    if constexpr (!kReloadK) kkr[j] = (uint32_t)bins[i < L.nb ? i : L.nb - 1];
   }
+  auto KK = [&](int j) -> uint32_t {
+    if constexpr (kReloadK) { const int i = j * kFftThreads + tid; return (uint32_t)bins[i < L.nb ? i : L.nb - 1]; }
+    else return kkr[j];
+  };
   float2 mx = make_float2(-INFINITY, -INFINITY), Z = make_float2(0.f, 0.f);
 
   // Exact tokens open the online softmax: their raw scores q . k_e come from kernel A.
@@ -645,7 +652,7 @@ __device__ __forceinline__ void fft_body(const Params& P, const float2* __restri
     // Folded entry of bin j of this thread: (z0, z1) for the two heads, from inputs loaded as a group (all
     // loads are issued before the first use: one latency, not one per bin).
     auto place = [&](int j, uint32_t frj, float2 z0, float2 z1, int round) {
-      const int r = kk[j] & (Q - 1), rm = (Q - r) & (Q - 1);
+      const int r = KK(j) & (Q - 1), rm = (Q - r) & (Q - 1);
       if ((frj & 0xffu) == (uint32_t)round) {  //      z0  + j z1
         float2 v = make_float2(z0.x - z1.y, z0.y + z1.x);
         if (r == rm) v = make_float2(2.f * z0.x, 2.f * z1.x);  // ... plus the mirror term, same slot
@@ -683,7 +690,7 @@ __device__ __forceinline__ void fft_body(const Params& P, const float2* __restri
 #pragma unroll
         for (int j = 0; j < NBT; ++j) {
           float2 twj = make_float2(1.f, 0.f);
-          if (MULTI) twj = cis_fast((kk[j] * b) & (P.M - 1u), P.M);
+          if (MULTI) twj = cis_fast((KK(j) * b) & (P.M - 1u), P.M);
           if constexpr (kKeepTw) twk[j] = twj;
           const float w = ww[j];
           const float2 a0 = cmul(make_float2(y0[j].x * w, y0[j].y * w), twj);
@@ -754,12 +761,12 @@ __device__ __forceinline__ void fft_body(const Params& P, const float2* __restri
     fft_dit<LOGQ>(buf, tab, lt);
 #pragma unroll
     for (int j = 0; j < NBT; ++j) {
-      const int r = kk[j] & (Q - 1), rm = (Q - r) & (Q - 1);
+      const int r = KK(j) & (Q - 1), rm = (Q - r) & (Q - 1);
       const float2 w1 = buf[pad(r)], w2 = buf[pad(rm)];
       const float2 p0 = make_float2(0.5f * (w1.x + w2.x), 0.5f * (w1.y - w2.y));
       const float2 p1 = make_float2(0.5f * (w1.y + w2.y), 0.5f * (w2.x - w1.x));
       if (MULTI) {
-        const float2 twc = conjf2(kKeepTw ? twk[j] : cis_fast((kk[j] * b) & (P.M - 1u), P.M));
+        const float2 twc = conjf2(kKeepTw ? twk[j] : cis_fast((KK(j) * b) & (P.M - 1u), P.M));
         A0[j] = cadd(make_float2(A0[j].x * f.x, A0[j].y * f.x), cmul(twc, p0));
         A1[j] = cadd(make_float2(A1[j].x * f.y, A1[j].y * f.y), cmul(twc, p1));
       } else {
@@ -793,8 +800,8 @@ __device__ __forceinline__ void fft_body(const Params& P, const float2* __restri
           // u_n = Re(t step^n r) for n = 0 .. np - 1 obeys u_{n+1} = 2 cos(phi) u_n - u_{n-1} (phi = the step's angle):
           // one multiply-add per token and head instead of a complex rotation (at most 15 steps: no error growth
           // that matters next to the 1e-6 of the hardware sine)
-          const float2 t = cis_fast((kk[j] * ptsh) & (P.M - 1u), P.M);
-          const float2 step = cis_fast(kk[j], P.M);
+          const float2 t = cis_fast((KK(j) * ptsh) & (P.M - 1u), P.M);
+          const float2 step = cis_fast(KK(j), P.M);
           const float2 t1 = cmul(t, step);
           const float c2 = 2.f * step.x;
           float a0 = t.x * r0.x - t.y * r0.y, a1 = t1.x * r0.x - t1.y * r0.y;  // head g0: u_0, u_1

@@ -157,12 +157,15 @@ __global__ __launch_bounds__(kFftThreads, (MULTI && NBT > 4 && NP > 1) ? 2 : 4) 
       for (int j = 0; j < NBT; ++j) {
         const int i = j * kFftThreads + tid;
         if (i < L.nb) {
-          const int r = kk[j] & (Q - 1), rm = (Q - r) & (Q - 1);
+          // decimated form with several pairs: the bin index is fetched again (an L1 / L2 hit) instead of being kept --
+          // the registers it frees are what the kernel would otherwise spill
+          const uint32_t kj = (MULTI && NP > 1) ? (uint32_t)bins[i] : kk[j];
+          const int r = kj & (Q - 1), rm = (Q - r) & (Q - 1);
           const float2 w1 = buf[pad(r)], w2 = buf[pad(rm)];
           const float2 d0 = make_float2(0.5f * (w1.x + w2.x), 0.5f * (w1.y - w2.y));
           const float2 d1 = make_float2(0.5f * (w1.y + w2.y), 0.5f * (w2.x - w1.x));
           if constexpr (MULTI) {
-            const float2 tw = conjf2(cis_poly2((kk[j] * b) & (P.M - 1u), P.M));  // e^{-j 2 pi k b / M}
+            const float2 tw = conjf2(cis_poly2((kj * b) & (P.M - 1u), P.M));  // e^{-j 2 pi k b / M}
             accp[0][j] = cadd(accp[0][j], cmul(tw, d0));
             accp[1][j] = cadd(accp[1][j], cmul(tw, d1));
           } else {
