@@ -72,8 +72,9 @@ enum {
                                        ~21 bits down to 2^-14 and an absolute 2^-25
                                        below.  The FFT prefill has no such limits.   */
   IWDFT_FLAG_FFT_PREFILL = 4u,      /* iwdft_prefill always runs FFTs + pruning; needs
-                                       M = 2^m >= 256 and <= 4096 kept bins per layer,
-                                       else IWDFT_ERR_UNSUPPORTED.  With neither flag
+                                       M = 2^m >= 256, else IWDFT_ERR_UNSUPPORTED (layers
+                                       with more than 4096 kept bins take a form that
+                                       keeps nothing per bin in registers).  With neither flag
                                        the library picks: FFT when it applies and some
                                        layer keeps >= 384 bins                     */
   IWDFT_FLAG_SHORTCUT = 8u,         /* the variant of the update that Sec. 4.1 mentions for long
@@ -142,11 +143,12 @@ int iwdft_prefill(iwdft_ctx* ctx, const void* d_K, const void* d_V, void* hip_st
 int iwdft_prefill_kind(const iwdft_ctx* ctx);
 
 /* Which synthesis compressed_decode_attn / iwdft_append_attn run for this context: 1 = scores and softmax
- * weights through in-LDS FFTs (M = 2^m >= 256 and at most 4096 kept bins per layer: O(M log M) per query head,
- * the HBM-bound path); 2 = through chirp-z transforms (any other 32 <= M <= 8192, e.g. M = context - sink - recent:
- * O(M log M) as well, about 8 times the arithmetic of 1); 0 = the direct O(M |B|) sums (arithmetic-bound; chosen by
- * IWDFT_FLAG_DIRECT_SYNTHESIS, for M < 32, and for M > 8192 that is not a power of two); -1 if ctx is NULL.
- * With 0 or 2, desc.write_every is taken as 1. */
+ * weights through in-LDS FFTs (M = 2^m >= 256: O(M log M) per query head, the HBM-bound path; layers with more than
+ * 4096 kept bins run a form of it that keeps nothing per bin in registers); 2 = through chirp-z transforms (any
+ * other 32 <= M <= 8192, e.g. M = context - sink - recent: O(M log M) as well, about 8 times the arithmetic of 1);
+ * 0 = the direct O(M |B|) sums (arithmetic-bound; chosen by IWDFT_FLAG_DIRECT_SYNTHESIS, for M < 32, and for M > 8192
+ * that is not a power of two); -1 if ctx is NULL.
+ * With 0 or 2, or when some layer keeps more than 4096 bins, desc.write_every is taken as 1. */
 int iwdft_attn_kind(const iwdft_ctx* ctx);
 
 /* Whether decode attention on this context (Sec. 4.2.2 "Calculating Attention") walks the slices in groups, with

@@ -56,7 +56,8 @@ struct Plan {  // byte offsets inside the two caller buffers, derived from a des
   size_t off_qc = 0, off_Pn = 0, off_pe = 0, off_pendK = 0, off_pendV = 0, off_ps = 0, off_direct = 0, ws_bytes = 0;
 };
 
-// Largest problem the FFT attention kernel keeps in registers / LDS.
+// Most kept bins per layer the FFT kernels keep in registers (prefill, reconstruction, the deferred write-back);
+// decode attention itself takes any number through its bin-strided kernel.
 constexpr int kFftMaxBins = 4096;
 constexpr int kFftPrefillMinBins = 384;  // fewer kept bins per layer: the dense contraction is faster
 constexpr int kMaxExact = 1024;  // most sink + recent tokens (their scores sit in LDS)
@@ -134,15 +135,13 @@ int make_plan(const iwdft_desc* d, Plan* pl) {
   pl->ws_total = ws;
 
   const bool pow2 = (d->M & (d->M - 1)) == 0;
-  pl->use_fft = pow2 && (uint64_t)d->M >= kFftMinM && pl->max_nb <= kFftMaxBins &&
-                !(d->flags & IWDFT_FLAG_DIRECT_SYNTHESIS);
+  pl->use_fft = pow2 && (uint64_t)d->M >= kFftMinM && !(d->flags & IWDFT_FLAG_DIRECT_SYNTHESIS);
   // Prefill: the FFT costs the same whatever the number of kept bins, the dense contraction grows
   // with it; measured break-even on MI355X: about 300 kept bins per layer at M = 8192, 430 at M = 131072.
-  const bool fft_pf_ok = pow2 && (uint64_t)d->M >= kFftMinM && pl->max_nb <= kFftMaxBins;
+  const bool fft_pf_ok = pow2 && (uint64_t)d->M >= kFftMinM;
   if (d->flags & IWDFT_FLAG_FFT_PREFILL) {
     if (!fft_pf_ok)
-      return fail(IWDFT_ERR_UNSUPPORTED, "FFT prefill needs M = 2^m >= %d and at most %d kept bins per layer",
-                  (int)kFftMinM, kFftMaxBins);
+      return fail(IWDFT_ERR_UNSUPPORTED, "FFT prefill needs M = 2^m >= %d", (int)kFftMinM);
     pl->use_fft_prefill = true;
   } else {
     pl->use_fft_prefill = fft_pf_ok && !(d->flags & IWDFT_FLAG_DENSE_PREFILL) && pl->max_nb >= kFftPrefillMinBins;
@@ -205,7 +204,8 @@ int make_plan(const iwdft_desc* d, Plan* pl) {
   pl->off_pe = o; o = align256(o + sizeof(float) * n_sl * (size_t)pl->G * (size_t)(d->n_sink + d->n_recent));
   // Deferred write-back needs the FFT attention kernels (they weigh the pending tokens) and all
   // query heads of a KV head in one pass; otherwise every step writes back.
-  pl->write_every = (d->write_every > 1 && pl->use_fft && heads_fit_one_pass(pl->G) && !(d->flags & IWDFT_FLAG_SHORTCUT))
+  pl->write_every = (d->write_every > 1 && pl->use_fft && pl->max_nb <= kFftMaxBins && heads_fit_one_pass(pl->G) &&
+                     !(d->flags & IWDFT_FLAG_SHORTCUT))
                         ? (int)d->write_every
                         : 1;
   const size_t pend_rows = (d->n_recent || pl->write_every > 1) ? (size_t)pl->write_every : 0;

@@ -558,6 +558,61 @@ __device__ __forceinline__ float2 block_sum2(float2 v, float2* scratch, int tid)
 
 __device__ __forceinline__ int64_t s_global_head(int slice, int G, int g) { return (int64_t)slice * G + g; }
 
+// Softmax over the Q time samples of one block, two heads side by side (real / imaginary part), on sample pairs held in
+// registers; the radix-2 stage that ends the inverse transform and the one that starts the forward transform (odd
+// log2 Q) are applied right here.  Online across blocks: (mx, Z) are the running maximum and sum; returns the factor
+// exp2(old max - new max) by which everything accumulated so far has to be scaled.
+template <int LOGQ>
+__device__ __forceinline__ float2 softmax_block(float2* buf, int tid, bool has1, float2* scratch, float2& mx, float2& Z) {
+  constexpr int Q = 1 << LOGQ;
+  float2 v[kFftEPT];
+  float2 lm = make_float2(-INFINITY, -INFINITY);
+#pragma unroll
+  for (int j = 0; j < kFftEPT / 2; ++j) {
+    const int bf = j * kFftThreads + tid;
+    if (2 * bf < Q) {
+      float2 a = buf[pad(2 * bf)], c = buf[pad(2 * bf + 1)];
+      if (LOGQ & 1) {
+        const float2 t = a;
+        a = cadd(t, c);
+        c = csub(t, c);
+      }
+      v[2 * j] = a;
+      v[2 * j + 1] = c;
+      lm.x = fmaxf(lm.x, fmaxf(a.x, c.x));
+      lm.y = fmaxf(lm.y, fmaxf(a.y, c.y));
+    }
+  }
+  const float2 bm = block_max2(lm, scratch, tid);
+  const float2 mn = make_float2(fmaxf(mx.x, bm.x), fmaxf(mx.y, bm.y));
+  // exp2(-inf) = 0 the first time
+  const float2 f = make_float2(__builtin_amdgcn_exp2f(mx.x - mn.x), __builtin_amdgcn_exp2f(mx.y - mn.y));
+  mx = mn;
+  float2 ls = make_float2(0.f, 0.f);
+#pragma unroll
+  for (int j = 0; j < kFftEPT / 2; ++j) {
+    const int bf = j * kFftThreads + tid;
+    if (2 * bf < Q) {
+      float2 a = make_float2(__builtin_amdgcn_exp2f(v[2 * j].x - mn.x),
+                             has1 ? __builtin_amdgcn_exp2f(v[2 * j].y - mn.y) : 0.f);
+      float2 c = make_float2(__builtin_amdgcn_exp2f(v[2 * j + 1].x - mn.x),
+                             has1 ? __builtin_amdgcn_exp2f(v[2 * j + 1].y - mn.y) : 0.f);
+      ls.x += a.x + c.x;
+      ls.y += a.y + c.y;
+      if (LOGQ & 1) {
+        const float2 t = a;
+        a = cadd(t, c);
+        c = csub(t, c);
+      }
+      buf[pad(2 * bf)] = a;
+      buf[pad(2 * bf + 1)] = c;
+    }
+  }
+  const float2 bs = block_sum2(ls, scratch, tid);  // its barrier also publishes the writes above
+  Z = make_float2(Z.x * f.x + bs.x, Z.y * f.y + bs.y);
+  return f;
+}
+
 // grid: slice * pairs + pair.  Two query heads share one complex transform: head g0 travels in
 // the real part, head g0+1 in the imaginary part (each head's spectrum is made Hermitian first,
 // so its time-domain signal is real).  Time index a = Pb * a' + b: block b of Q = M / Pb samples
@@ -711,53 +766,7 @@ __device__ __forceinline__ void fft_body(const Params& P, const float2* __restri
     }
     ifft_dif<LOGQ>(buf, tab, lt);
 
-    // Softmax on sample pairs held in registers; the radix-2 stage that ends the inverse transform
-    // and the one that starts the forward transform (odd log2 Q) are applied right here.
-    float2 v[kFftEPT];
-    float2 lm = make_float2(-INFINITY, -INFINITY);
-#pragma unroll
-    for (int j = 0; j < kFftEPT / 2; ++j) {
-      const int bf = j * kFftThreads + tid;
-      if (2 * bf < Q) {
-        float2 a = buf[pad(2 * bf)], c = buf[pad(2 * bf + 1)];
-        if (LOGQ & 1) {
-          const float2 t = a;
-          a = cadd(t, c);
-          c = csub(t, c);
-        }
-        v[2 * j] = a;
-        v[2 * j + 1] = c;
-        lm.x = fmaxf(lm.x, fmaxf(a.x, c.x));
-        lm.y = fmaxf(lm.y, fmaxf(a.y, c.y));
-      }
-    }
-    const float2 bm = block_max2(lm, scratch, tid);
-    const float2 mn = make_float2(fmaxf(mx.x, bm.x), fmaxf(mx.y, bm.y));
-    // exp2(-inf) = 0 the first time
-    const float2 f = make_float2(__builtin_amdgcn_exp2f(mx.x - mn.x), __builtin_amdgcn_exp2f(mx.y - mn.y));
-    mx = mn;
-    float2 ls = make_float2(0.f, 0.f);
-#pragma unroll
-    for (int j = 0; j < kFftEPT / 2; ++j) {
-      const int bf = j * kFftThreads + tid;
-      if (2 * bf < Q) {
-        float2 a = make_float2(__builtin_amdgcn_exp2f(v[2 * j].x - mn.x),
-                               has1 ? __builtin_amdgcn_exp2f(v[2 * j].y - mn.y) : 0.f);
-        float2 c = make_float2(__builtin_amdgcn_exp2f(v[2 * j + 1].x - mn.x),
-                               has1 ? __builtin_amdgcn_exp2f(v[2 * j + 1].y - mn.y) : 0.f);
-        ls.x += a.x + c.x;
-        ls.y += a.y + c.y;
-        if (LOGQ & 1) {
-          const float2 t = a;
-          a = cadd(t, c);
-          c = csub(t, c);
-        }
-        buf[pad(2 * bf)] = a;
-        buf[pad(2 * bf + 1)] = c;
-      }
-    }
-    const float2 bs = block_sum2(ls, scratch, tid);  // its barrier also publishes the writes above
-    Z = make_float2(Z.x * f.x + bs.x, Z.y * f.y + bs.y);
+    const float2 f = softmax_block<LOGQ>(buf, tid, has1, scratch, mx, Z);
     fft_dit<LOGQ>(buf, tab, lt);
 #pragma unroll
     for (int j = 0; j < NBT; ++j) {
@@ -848,6 +857,141 @@ __global__ __launch_bounds__(kFftThreads, (MULTI && NBT > 4) ? 2 : 4) void attn_
                                                                  float* __restrict__ ps) {
   extern __shared__ float2 smem[];
   fft_body<LOGQ, NBT, MULTI>(P, qc, Pn, pe, scale, pairs, np, ptsh, ps, blockIdx.x, smem);
+}
+
+// ------------------------------------------------------------------------- B (FFT, > 4096 kept bins)
+// The same computation for layers that keep more bins than the kernel above holds in registers (8 per thread): the
+// threads walk the bin list in strides of the workgroup, nothing per bin stays in registers.  Folding re-reads the
+// inputs in every round and block; the running sums over blocks (MULTI) live in the output rows themselves -- every bin
+// belongs to one thread, which reads back its own earlier store, scales it by the online-softmax factor and adds the
+// block's term -- and a last sweep turns them into the normalised weights.  No pending tokens (write_every is 1).
+template <int LOGQ, bool MULTI>
+__global__ __launch_bounds__(kFftThreads, 4) void attn_fft_big_kernel(Params P, const float2* __restrict__ qc,
+                                                                     float2* __restrict__ Pn, float* __restrict__ pe,
+                                                                     float scale, int pairs) {
+  extern __shared__ float2 smem[];
+  __shared__ float2 scratch[2 * (kFftThreads / 64)];
+  const int tid = threadIdx.x;
+  constexpr int Q = 1 << LOGQ;
+  float2* buf = smem;
+  float2* tab = smem + Q + (Q >> 5);
+  const int pair = blockIdx.x % pairs;
+  const int slice = blockIdx.x / pairs;
+  const int spl = P.batch * P.n_kv;
+  const int layer = slice / spl;
+  const int s = slice - layer * spl;
+  const LayerInfo L = P.layers[layer];
+  const int g0 = pair * 2;
+  const bool has1 = (g0 + 1) < P.G;
+  const uint32_t Pb = MULTI ? (P.M >> LOGQ) : 1u;
+  const float2* q0 = qc + L.ws_off + ((int64_t)s * P.G + g0) * L.Bp;
+  const float2* q1 = has1 ? q0 + L.Bp : q0;
+  float2* o0 = Pn + L.ws_off + ((int64_t)s * P.G + g0) * L.Bp;
+  float2* o1 = o0 + L.Bp;  // written only if has1
+  const int32_t* bins = P.bins + L.bin_off;
+  const float* wts = P.weights + L.bin_off;
+  const uint16_t* fold = P.fold + L.bin_off;
+  const float gain = 0.5f * 1.44269504088896341f * scale * P.gain / (float)P.M;  // log2 units; 0.5: bin + mirror
+
+  for (int m = tid; m <= (Q >> 3); m += kFftThreads) tab[m] = P.tw8[m];
+
+  float2 mx = make_float2(-INFINITY, -INFINITY), Z = make_float2(0.f, 0.f);
+  const int E = P.S + P.R;
+  float* pe0 = pe + ((int64_t)s_global_head(slice, P.G, g0)) * E;
+  float* pe1 = pe0 + E;
+  const float escale = 1.44269504088896341f * scale;
+  if (E > 0) {  // exact tokens open the online softmax (raw scores from kernel A)
+    float2 lm = make_float2(-INFINITY, -INFINITY);
+    for (int e = tid; e < E; e += kFftThreads) {
+      lm.x = fmaxf(lm.x, pe0[e] * escale);
+      if (has1) lm.y = fmaxf(lm.y, pe1[e] * escale);
+    }
+    mx = block_max2(lm, scratch, tid);
+    float2 ls = make_float2(0.f, 0.f);
+    for (int e = tid; e < E; e += kFftThreads) {
+      ls.x += __builtin_amdgcn_exp2f(pe0[e] * escale - mx.x);
+      if (has1) ls.y += __builtin_amdgcn_exp2f(pe1[e] * escale - mx.y);
+    }
+    Z = block_sum2(ls, scratch, tid);
+  }
+
+  for (uint32_t b = 0; b < Pb; ++b) {
+    for (int e = tid; e < Q + (Q >> 5); e += kFftThreads) buf[e] = make_float2(0.f, 0.f);
+    __syncthreads();
+    for (int round = 0; round < L.fold_rounds; ++round) {
+      for (int i = tid; i < L.nb; i += kFftThreads) {
+        const uint32_t fr = fold[i];
+        const bool direct = (fr & 0xffu) == (uint32_t)round, mirror = (fr >> 8) == (uint32_t)round;
+        if (!direct && !mirror) continue;
+        const uint32_t k = (uint32_t)bins[i];
+        const float w = wts[i] * gain;
+        const float2 y0 = q0[i], y1 = q1[i];
+        const float2 tw = MULTI ? cis_fast((k * b) & (P.M - 1u), P.M) : make_float2(1.f, 0.f);
+        const float2 z0 = cmul(make_float2(y0.x * w, y0.y * w), tw);
+        const float2 z1 = has1 ? cmul(make_float2(y1.x * w, y1.y * w), tw) : make_float2(0.f, 0.f);
+        const int r = k & (Q - 1), rm = (Q - r) & (Q - 1);
+        if (direct) {  //      z0  + j z1
+          float2 v = make_float2(z0.x - z1.y, z0.y + z1.x);
+          if (r == rm) v = make_float2(2.f * z0.x, 2.f * z1.x);  // ... plus the mirror term, same slot
+          if (round) v = cadd(v, buf[pad(r)]);
+          buf[pad(r)] = v;
+        }
+        if (mirror) {  // conj z0  + j conj z1
+          float2 v = make_float2(z0.x + z1.y, z1.x - z0.y);
+          if (round) v = cadd(v, buf[pad(rm)]);
+          buf[pad(rm)] = v;
+        }
+      }
+      __syncthreads();
+    }
+    ifft_dif<LOGQ>(buf, tab, tid);
+    const float2 f = softmax_block<LOGQ>(buf, tid, has1, scratch, mx, Z);
+    fft_dit<LOGQ>(buf, tab, tid);
+    for (int i = tid; i < L.nb; i += kFftThreads) {
+      const uint32_t k = (uint32_t)bins[i];
+      const int r = k & (Q - 1), rm = (Q - r) & (Q - 1);
+      const float2 w1 = buf[pad(r)], w2 = buf[pad(rm)];
+      float2 p0 = make_float2(0.5f * (w1.x + w2.x), 0.5f * (w1.y - w2.y));
+      float2 p1 = make_float2(0.5f * (w1.y + w2.y), 0.5f * (w2.x - w1.x));
+      if (MULTI) {
+        const float2 twc = conjf2(cis_fast((k * b) & (P.M - 1u), P.M));
+        p0 = cmul(twc, p0);
+        p1 = cmul(twc, p1);
+        if (b) {  // this thread's own running sums, scaled to the new maximum
+          const float2 a0 = o0[i];
+          p0 = make_float2(a0.x * f.x + p0.x, a0.y * f.x + p0.y);
+          if (has1) {
+            const float2 a1 = o1[i];
+            p1 = make_float2(a1.x * f.y + p1.x, a1.y * f.y + p1.y);
+          }
+        }
+      }
+      o0[i] = p0;
+      if (has1) o1[i] = p1;
+    }
+    __syncthreads();
+  }
+
+  const float inv_M = P.gain / (float)P.M;
+  const float iz0 = inv_M / Z.x, iz1 = has1 ? inv_M / Z.y : 0.f;
+  for (int i = tid; i < L.Bp; i += kFftThreads) {  // padding entries are written as zeros: kernel C reads whole rows
+    float2 r0 = make_float2(0.f, 0.f), r1 = r0;
+    if (i < L.nb) {
+      const float w = wts[i];
+      const float2 a0 = o0[i];
+      r0 = make_float2(a0.x * (w * iz0), -a0.y * (w * iz0));
+      if (has1) {
+        const float2 a1 = o1[i];
+        r1 = make_float2(a1.x * (w * iz1), -a1.y * (w * iz1));
+      }
+    }
+    o0[i] = r0;
+    if (has1) o1[i] = r1;
+  }
+  for (int e = tid; e < E; e += kFftThreads) {  // raw scores -> weights p_e / Z (same thread, same entry)
+    pe0[e] = __builtin_amdgcn_exp2f(pe0[e] * escale - mx.x) / Z.x;
+    if (has1) pe1[e] = __builtin_amdgcn_exp2f(pe1[e] * escale - mx.y) / Z.y;
+  }
 }
 
 // ----------------------------------------------------------------------------------- A + B
@@ -1121,7 +1265,7 @@ static int heads_per_pass(int G);
 bool attn_pipelines(const Params& P, bool use_fft) {
   const int GT = heads_per_pass(P.G);
   const int per_thread = (P.max_Bp + kFftThreads - 1) / kFftThreads;
-  return use_fft && P.G <= GT && (GT == 4 || GT == 8) && P.M >= 16384u && per_thread > 2 &&
+  return use_fft && P.G <= GT && (GT == 4 || GT == 8) && P.M >= 16384u && per_thread > 2 && per_thread <= kFftNBT &&
          (uint64_t)P.n_slices * ((P.G + 1) / 2) >= 2 * kAbMinB && !P.serial_phases;
 }
 static int heads_per_pass(int G) { return G <= 2 ? G : (G <= 4 ? 4 : 8); }  // 1, 2, 4 or 8; heads beyond G are masked
@@ -1240,7 +1384,19 @@ static hipError_t launch_attn_t(const Params& P, const void* q, void* out, float
     else if (per_thread <= 4) IWDFT_FFT_CASE(LQ, 4, MULTI)                                               \
     else IWDFT_FFT_CASE(LQ, 8, MULTI)                                                                    \
   }
-    if (logM > logQ) IWDFT_FFT_NBT(kFftMaxLogQ, true)
+    if (per_thread > kFftNBT) {  // more than 4096 kept bins in some layer (so M > 4096): nothing per bin in registers
+      if (np_plain > 0) return hipErrorInvalidValue;  // no pending tokens on this path (the plan takes write_every as 1)
+#define IWDFT_FFT_BIG(MULTI)                                                                             \
+  {                                                                                                      \
+    static LdsLimit lim;                                                                                 \
+    e = lim.ensure((const void*)attn_fft_big_kernel<kFftMaxLogQ, MULTI>, (int)lds);                      \
+    if (e != hipSuccess) return e;                                                                       \
+    attn_fft_big_kernel<kFftMaxLogQ, MULTI><<<dim3(gridB), dim3(kFftThreads), lds, st>>>(P, qc, Pn, pe,  \
+                                                                                        scale, pairs);  \
+  }
+      if (logM > logQ) IWDFT_FFT_BIG(true) else IWDFT_FFT_BIG(false)
+#undef IWDFT_FFT_BIG
+    } else if (logM > logQ) IWDFT_FFT_NBT(kFftMaxLogQ, true)
     else switch (logQ) {
       case 8: IWDFT_FFT_CASE(8, 8, false) break;
       case 9: IWDFT_FFT_CASE(9, 8, false) break;

@@ -60,7 +60,9 @@ __device__ __forceinline__ void raw_pop(Raw<NW>& r) {
 // NP = channel pairs per workgroup: every thread fetches its samples of NP adjacent pairs with one load
 // (4 NP bytes of a token row for bf16) and the pairs are then transformed one after the other from
 // registers, so that a 128-byte line of a token row is requested by 32 / NP workgroups instead of 32.
-// NBT = kept bins per thread.
+// NBT = kept bins per thread; 0: any number of kept bins -- the threads walk the bin list in strides of the workgroup
+// and, in the decimated form, keep the running sums over the residues in the output rows themselves (every bin
+// belongs to one thread, which reads back its own earlier store).
 template <int LOGQ, bool BF16, bool MULTI, int NBT, int NP>
 __global__ __launch_bounds__(kFftThreads, (MULTI && NBT > 4 && NP > 1) ? 2 : 4) void prefill_fft_kernel(Params P, const void* __restrict__ K,
                                                                     const void* __restrict__ V, int per_xcd,
@@ -93,8 +95,9 @@ __global__ __launch_bounds__(kFftThreads, (MULTI && NBT > 4 && NP > 1) ? 2 : 4) 
   for (int m = tid; m <= (Q >> 3); m += kFftThreads) tab[m] = P.tw8[m];  // exp(+j 2 pi m / Q), host-made
 
   // MULTI: running sums over the residues, per pair, channel and kept bin of this thread
-  float2 acc[MULTI ? NP : 1][2][NBT];
-  uint32_t kk[NBT];
+  constexpr int NBR = NBT ? NBT : 1;  // register-held bins per thread
+  float2 acc[MULTI ? NP : 1][2][NBR];
+  uint32_t kk[NBR];
 #pragma unroll
   for (int j = 0; j < NBT; ++j) {
 #pragma unroll
@@ -153,6 +156,26 @@ __global__ __launch_bounds__(kFftThreads, (MULTI && NBT > 4 && NP > 1) ? 2 : 4) 
       __syncthreads();  // (the first time also publishes tab)
       fft_dit<LOGQ>(buf, tab, lt);
       float2* F0 = F + (int64_t)(2 * p) * L.Bp;
+      if constexpr (NBT == 0) {
+        for (int i = tid; i < L.nb; i += kFftThreads) {
+          const uint32_t kj = (uint32_t)bins[i];
+          const int r = kj & (Q - 1), rm = (Q - r) & (Q - 1);
+          const float2 w1 = buf[pad(r)], w2 = buf[pad(rm)];
+          float2 d0 = make_float2(0.5f * (w1.x + w2.x), 0.5f * (w1.y - w2.y));
+          float2 d1 = make_float2(0.5f * (w1.y + w2.y), 0.5f * (w2.x - w1.x));
+          if constexpr (MULTI) {
+            const float2 tw = conjf2(cis_poly2((kj * b) & (P.M - 1u), P.M));  // e^{-j 2 pi k b / M}
+            d0 = cmul(tw, d0);
+            d1 = cmul(tw, d1);
+            if (b) {
+              d0 = cadd(F0[i], d0);
+              d1 = cadd(F0[L.Bp + i], d1);
+            }
+          }
+          F0[i] = d0;
+          F0[L.Bp + i] = d1;
+        }
+      }
 #pragma unroll
       for (int j = 0; j < NBT; ++j) {
         const int i = j * kFftThreads + tid;
@@ -185,7 +208,7 @@ __global__ __launch_bounds__(kFftThreads, (MULTI && NBT > 4 && NP > 1) ? 2 : 4) 
     }
   }
 
-  if constexpr (MULTI) {
+  if constexpr (MULTI && NBT > 0) {
 #pragma unroll
     for (int p = 0; p < NP; ++p) {
       float2* F0 = F + (int64_t)(2 * p) * L.Bp;
@@ -201,9 +224,7 @@ __global__ __launch_bounds__(kFftThreads, (MULTI && NBT > 4 && NP > 1) ? 2 : 4) 
   }
 }
 
-bool prefill_fft_ok(const Params& P) {
-  return P.Mmask != 0 && P.M >= 256 && P.max_nb <= kFftNBT * kFftThreads;
-}
+bool prefill_fft_ok(const Params& P) { return P.Mmask != 0 && P.M >= 256; }
 
 template <bool BF16>
 static hipError_t launch_prefill_fft_t(const Params& P, const void* K, const void* V, hipStream_t st) {
@@ -213,7 +234,7 @@ static hipError_t launch_prefill_fft_t(const Params& P, const void* K, const voi
   const int n_st = P.n_slices * 2;
   const int per_xcd = (n_st + 7) / 8;
   const size_t lds = sizeof(float2) * (size_t)fft_lds_float2(logQ);
-  const int per_thread = (P.max_nb + kFftThreads - 1) / kFftThreads;  // <= kFftNBT (prefill_fft_ok)
+  const int per_thread = (P.max_nb + kFftThreads - 1) / kFftThreads;
   // 16-byte sample loads need 16-byte aligned tensors (and rows, which are 256 or 512 bytes)
   const bool wide = (((uintptr_t)K | (uintptr_t)V) & 15u) == 0;
   hipError_t e = hipSuccess;
@@ -235,7 +256,16 @@ static hipError_t launch_prefill_fft_t(const Params& P, const void* K, const voi
     if (wide) IWDFT_PF_CASE(LQ, false, 8, kNpSingle)                                                         \
     else IWDFT_PF_CASE(LQ, false, 8, 1)                                                                      \
   }
-  if (logM > logQ) {
+  if (per_thread > kFftNBT) {  // more than 4096 kept bins in some layer (so M >= 8192): the bin-strided form
+    constexpr int kNpBig = BF16 ? 2 : 1;
+    if (logM > logQ) {
+      if (wide) IWDFT_PF_CASE(kFftMaxLogQ, true, 0, kNpBig)
+      else IWDFT_PF_CASE(kFftMaxLogQ, true, 0, 1)
+    } else {
+      if (wide) IWDFT_PF_CASE(kFftMaxLogQ, false, 0, kNpBig)
+      else IWDFT_PF_CASE(kFftMaxLogQ, false, 0, 1)
+    }
+  } else if (logM > logQ) {
     if (per_thread <= 4) {
       constexpr int kNpMulti = BF16 ? 2 : 1;
       if (wide) IWDFT_PF_CASE(kFftMaxLogQ, true, 4, kNpMulti)

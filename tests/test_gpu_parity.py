@@ -670,17 +670,38 @@ def test_dc_only_mask_outputs_the_mean_value_row():
     cache.close()
 
 
-@pytest.mark.parametrize("n_bins,kind", [(4096, "fft"), (4100, "chirp")])
-def test_most_bins_the_fft_kernels_take_and_the_fallback_beyond(n_bins, kind):
-    # 4096 kept bins per layer is the limit of the power-of-two FFT attention and FFT prefill kernels; one more and
-    # the library runs the chirp-z attention and the dense prefill (same results, slower)
-    cfg = small_cfg(L=8192, n_bins=n_bins, group=2, steps=2, n_layers=1, batch=1, n_kv_heads=2, dtype="bf16")
+@pytest.mark.parametrize("L,n_bins,group,dtype,S,R", [
+    (8192, 4096, 2, "bf16", 0, 0),     # the most bins the register-resident kernels take
+    (8192, 4100, 2, "bf16", 0, 0),     # one step beyond: the bin-strided kernels, single transform
+    (8192, 8192, 3, "f32", 2, 6),      # every bin kept; a last head pair with one head; windows
+    (16384, 5000, 4, "bf16", 0, 0),    # two decimated blocks, running sums kept in the output rows
+    (32768, 9000, 2, "f32", 4, 4),     # four blocks, fp32 tokens, windows
+    (32768, 16384, 1, "bf16", 0, 0),   # half of all bins (mirror-closed sets collide in every slot), one query head
+])
+def test_more_than_4096_kept_bins_per_layer(L, n_bins, group, dtype, S, R):
+    """Up to 4096 kept bins per layer the FFT kernels hold per-bin values in registers; beyond that the prefill and the
+    decode attention walk the bin list in strides of the workgroup (and keep running sums in their output rows), still
+    O(M log M).  Every step against the oracle, two calls and fused; the deferred write-back is taken as 1 there."""
+    cfg = small_cfg(L=L, n_bins=n_bins, group=group, steps=3, n_layers=1, batch=1, n_kv_heads=2, dtype=dtype,
+                    n_sink=S, n_recent=R)
     bins = [np.sort(np.random.default_rng(3).choice(cfg.L, size=n_bins, replace=False)).astype(np.int32)]
-    cache = make_cache(cfg, bins)
-    assert B.iwdft_prefill_kind(cache.ctx) == ("fft" if kind == "fft" else "dense")
-    assert B.iwdft_attn_kind(cache.ctx) == kind
+    cache = make_cache(cfg, bins, write_every=8)
+    assert B.iwdft_prefill_kind(cache.ctx) == "fft" and B.iwdft_attn_kind(cache.ctx) == "fft"
     cache.close()
-    run_stream(cfg, bins, rec=(5, 40), fused=True, tag=f"maxbins-{n_bins}")
+    run_stream(cfg, bins, rec=(5, 40), tag=f"bins-{L}-{n_bins}")
+    run_stream(cfg, bins, rec=(5, 40), fused=True, write_every=8, tag=f"bins-{L}-{n_bins}-fused")
+    if n_bins > 4096:   # and against the direct sums of the same library
+        K, V = wl.prefill_tensors(cfg, DEV)
+        a, d = make_cache(cfg, bins), make_cache(cfg, bins, flags=B.IWDFT_FLAG_DIRECT_SYNTHESIS | B.IWDFT_FLAG_DENSE_PREFILL)
+        assert B.iwdft_attn_kind(d.ctx) == "direct" and B.iwdft_prefill_kind(d.ctx) == "dense"
+        a.prefill(K, V)
+        d.prefill(K, V)
+        (ka, va), (kd, vd) = a.export_coeffs(0), d.export_coeffs(0)
+        assert rel_l2(c128(ka), c128(kd)) < 2e-5 and rel_l2(c128(va), c128(vd)) < 2e-5
+        _, _, q = wl.decode_step(cfg, 0, DEV)
+        assert rel_l2(f64(a.attend(q)), f64(d.attend(q))) < (2e-5 if dtype == "f32" else 8e-3)
+        a.close()
+        d.close()
 
 
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
