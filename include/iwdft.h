@@ -145,9 +145,10 @@ int iwdft_prefill_kind(const iwdft_ctx* ctx);
 /* Which synthesis compressed_decode_attn / iwdft_append_attn run for this context: 1 = scores and softmax
  * weights through in-LDS FFTs (M = 2^m >= 256: O(M log M) per query head, the HBM-bound path; layers with more than
  * 4096 kept bins run a form of it that keeps nothing per bin in registers); 2 = through chirp-z transforms (any
- * other 32 <= M <= 8192, e.g. M = context - sink - recent: O(M log M) as well, about 8 times the arithmetic of 1);
- * 0 = the direct O(M |B|) sums (arithmetic-bound; chosen by IWDFT_FLAG_DIRECT_SYNTHESIS, for M < 32, and for M > 8192
- * that is not a power of two); -1 if ctx is NULL.
+ * other M >= 32 that is at most 8192 or has a divisor Pb <= 256 with 32 <= M / Pb <= 8192, e.g. M = context - sink -
+ * recent = 16384 - 60 = 2 * 8162: O(M log M) as well, about 8 times the arithmetic of 1); 0 = the direct O(M |B|)
+ * sums (arithmetic-bound; chosen by IWDFT_FLAG_DIRECT_SYNTHESIS, for M < 32, and for M > 8192 without such a divisor,
+ * e.g. a prime); -1 if ctx is NULL.
  * With 0 or 2, or when some layer keeps more than 4096 bins, desc.write_every is taken as 1. */
 int iwdft_attn_kind(const iwdft_ctx* ctx);
 

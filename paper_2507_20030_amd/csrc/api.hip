@@ -46,6 +46,7 @@ struct Plan {  // byte offsets inside the two caller buffers, derived from a des
   bool use_fft = false;          // decode attention through power-of-two FFTs
   bool use_chirp = false;        // ... through chirp-z transforms (any M up to kChirpMaxM when use_fft is false)
   int chirp_logN = 0;            // length of its circular convolutions
+  int64_t chirp_Q = 0;           // points per chirp-z transform: M / Pb (M itself up to 8192)
   size_t off_chirp = 0, off_chirpH = 0;
   int64_t tw_Q = 0;              // length of the power-of-two in-LDS transforms (0: none), table at off_tw
   size_t off_tw = 0;
@@ -63,7 +64,8 @@ constexpr int kFftPrefillMinBins = 384;  // fewer kept bins per layer: the dense
 constexpr int kMaxExact = 1024;  // most sink + recent tokens (their scores sit in LDS)
 constexpr uint32_t kFftMinM = 256;
 constexpr int64_t kFftMaxQ = 8192;  // longest transform the FFT attention kernel holds in LDS
-constexpr int64_t kChirpMinM = 32, kChirpMaxM = 8192;  // chirp-z attention: 2M - 1 <= 16384 points fit in LDS
+constexpr int64_t kChirpMinM = 32, kChirpMaxM = 8192;  // chirp-z transforms: 2 Q - 1 <= 16384 points fit in LDS
+constexpr int64_t kChirpMaxBlocks = 256;  // most decimated blocks M / Q of the chirp-z attention
 
 int make_plan(const iwdft_desc* d, Plan* pl) {
   if (!d) return fail(IWDFT_ERR_ARG, "desc is NULL");
@@ -146,10 +148,21 @@ int make_plan(const iwdft_desc* d, Plan* pl) {
   } else {
     pl->use_fft_prefill = fft_pf_ok && !(d->flags & IWDFT_FLAG_DENSE_PREFILL) && pl->max_nb >= kFftPrefillMinBins;
   }
-  pl->use_chirp = !pl->use_fft && !(d->flags & IWDFT_FLAG_DIRECT_SYNTHESIS) && d->M >= kChirpMinM && d->M <= kChirpMaxM;
+  // Chirp-z attention for M that is not a power of two: M itself up to 8192 points; longer M in Pb decimated blocks
+  // of M / Pb points, Pb the smallest divisor of M that brings the block down to 8192 (none: the direct sums).
+  pl->use_chirp = false;
+  if (!pl->use_fft && !(d->flags & IWDFT_FLAG_DIRECT_SYNTHESIS) && d->M >= kChirpMinM) {
+    for (int64_t pb = (d->M + kChirpMaxM - 1) / kChirpMaxM; pb <= kChirpMaxBlocks && d->M / pb >= kChirpMinM; ++pb) {
+      if (d->M % pb == 0) {
+        pl->use_chirp = true;
+        pl->chirp_Q = d->M / pb;
+        break;
+      }
+    }
+  }
   if (pl->use_chirp) {
     pl->chirp_logN = 8;
-    while (((int64_t)1 << pl->chirp_logN) < 2 * d->M - 1) pl->chirp_logN += 2;  // even lengths only
+    while (((int64_t)1 << pl->chirp_logN) < 2 * pl->chirp_Q - 1) pl->chirp_logN += 2;  // even lengths only
   }
   pl->fold.assign((size_t)pl->n_bins_total, 0);
   if (pl->use_fft || pl->use_chirp) {
@@ -157,7 +170,7 @@ int make_plan(const iwdft_desc* d, Plan* pl) {
     // folded modulo the transform length Q (power-of-two kernel) or at k and M - k (chirp-z kernel).  Entries that
     // land on the same slot are added in separate rounds, so the kernels need no atomics and sum in a fixed order:
     // round = how many earlier entries of the layer already use that slot.
-    const int64_t Q = pl->use_chirp ? d->M : (d->M < kFftMaxQ ? d->M : kFftMaxQ);
+    const int64_t Q = pl->use_chirp ? pl->chirp_Q : (d->M < kFftMaxQ ? d->M : kFftMaxQ);
     std::vector<uint16_t> cnt((size_t)Q);
     for (int l = 0; l < d->n_layers && (pl->use_fft || pl->use_chirp); ++l) {
       std::fill(cnt.begin(), cnt.end(), 0);
@@ -184,7 +197,7 @@ int make_plan(const iwdft_desc* d, Plan* pl) {
   pl->off_bins = o;    o = align256(o + sizeof(int32_t) * (size_t)pl->n_bins_total);
   pl->off_weights = o; o = align256(o + sizeof(float) * (size_t)pl->n_bins_total);
   pl->off_fold = o;    o = align256(o + sizeof(uint16_t) * (size_t)pl->n_bins_total);
-  pl->off_chirp = o;   o = align256(o + (pl->use_chirp ? sizeof(float2) * (size_t)d->M : 0));
+  pl->off_chirp = o;   o = align256(o + (pl->use_chirp ? sizeof(float2) * (size_t)pl->chirp_Q : 0));
   pl->off_chirpH = o;  o = align256(o + (pl->use_chirp ? sizeof(float2) * ((size_t)1 << pl->chirp_logN) : 0));
   pl->tw_Q = (pow2 && (uint64_t)d->M >= kFftMinM) ? (d->M < kFftMaxQ ? d->M : kFftMaxQ) : 0;
   pl->off_tw = o;      o = align256(o + (pl->tw_Q ? sizeof(float2) * (size_t)(pl->tw_Q / 8 + 1) : 0));
@@ -432,7 +445,7 @@ int iwdft_create(const iwdft_desc* desc, void* d_state, size_t state_bytes, void
                     hipMemcpyHostToDevice);
     if (e == hipSuccess && pl.use_chirp) {
       std::vector<float2> chirp, H;
-      make_chirp_tables(desc->M, pl.chirp_logN, &chirp, &H);
+      make_chirp_tables(pl.chirp_Q, pl.chirp_logN, &chirp, &H);
       e = hipMemcpy(c->state + pl.off_chirp, chirp.data(), sizeof(float2) * chirp.size(), hipMemcpyHostToDevice);
       if (e == hipSuccess)
         e = hipMemcpy(c->state + pl.off_chirpH, H.data(), sizeof(float2) * H.size(), hipMemcpyHostToDevice);
@@ -472,6 +485,7 @@ int iwdft_create(const iwdft_desc* desc, void* d_state, size_t state_bytes, void
     P.chirp = pl.use_chirp ? (const float2*)(c->state + pl.off_chirp) : nullptr;
     P.chirpH = pl.use_chirp ? (const float2*)(c->state + pl.off_chirpH) : nullptr;
     P.chirp_logN = pl.chirp_logN;
+    P.chirp_Q = (uint32_t)pl.chirp_Q;
     P.tw8 = pl.tw_Q ? (const float2*)(c->state + pl.off_tw) : nullptr;
     P.FK = (float2*)(c->state + pl.off_FK);
     P.FV = (float2*)(c->state + pl.off_FV);

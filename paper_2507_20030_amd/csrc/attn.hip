@@ -1020,15 +1020,19 @@ __global__ __launch_bounds__(kFftThreads, (MULTI && NBT > 4) ? 2 : 4) void attn_
 }
 
 // ------------------------------------------------------------------------------------ B (chirp)
-// The same two length-M transforms for ANY M up to 8192 (e.g. M = context - sink - recent, Sec. 4.2.1, which is a
+// The same two transforms for M that is not a power of two (e.g. M = context - sink - recent, Sec. 4.2.1, which is a
 // power of two only by arrangement), through the chirp-z identity  k a = (k^2 + a^2 - (a - k)^2) / 2:
-//   sum_k Z[k] e^{+j 2 pi k a / M} = c[a] * sum_k (Z[k] c[k]) h[a - k],   c[n] = e^{+j pi n^2 / M},  h = conj c,
-// a linear convolution with the chirp h, run as a circular one of length N = 2^LOGN >= 2M - 1 in LDS: transform,
+//   sum_k Z[k] e^{+j 2 pi k a / Qc} = c[a] * sum_k (Z[k] c[k]) h[a - k],   c[n] = e^{+j pi n^2 / Qc},  h = conj c,
+// a linear convolution with the chirp h, run as a circular one of length N = 2^LOGN >= 2 Qc - 1 in LDS: transform,
 // multiply by the transform of h (host-made table, already divided by N, stored in the digit-reversed order the
 // first transform leaves), transform back.  The forward transform of the softmax weights is the conjugate chain.
-// Four N-point transforms per pair of query heads instead of two M-point ones: O(M log M) as well, ~8x the work of
-// the power-of-two kernel, against O(M |B|) of the direct sums.  One workgroup per (slice, head pair); LOGN even.
-// No pending tokens (the deferred write-back needs the power-of-two kernel).
+// Qc = M up to 8192.  Longer M run Pb = M / Qc blocks (Pb the smallest divisor of M that brings Qc down to 8192):
+// time index a = Pb a' + b, block b comes from the spectrum folded modulo Qc with twiddle e^{j 2 pi k b / M}, softmax
+// runs online across the blocks and the running sums of the weights live in the output rows (every bin belongs to one
+// thread, which reads back its own earlier store).  Four N-point transforms per block and pair of query heads instead
+// of two Qc-point ones: O(M log M) as well, ~8x the work of the power-of-two kernel, against O(M |B|) of the direct
+// sums.  One workgroup per (slice, head pair); LOGN even.  No pending tokens (the deferred write-back needs the
+// power-of-two kernel).
 template <int LOGN>
 __global__ __launch_bounds__(kFftThreads, 2) void attn_chirp_kernel(Params P, const float2* __restrict__ qc,
                                                                    float2* __restrict__ Pn, float* __restrict__ pe,
@@ -1048,18 +1052,20 @@ __global__ __launch_bounds__(kFftThreads, 2) void attn_chirp_kernel(Params P, co
   const LayerInfo L = P.layers[layer];
   const int g0 = pair * 2;
   const bool has1 = (g0 + 1) < P.G;
-  const uint32_t M = P.M;
+  const uint32_t M = P.M, Qc = P.chirp_Q, Pb = M / Qc;
   const float2* q0 = qc + L.ws_off + ((int64_t)s * P.G + g0) * L.Bp;
   const float2* q1 = has1 ? q0 + L.Bp : q0;
+  float2* o0 = Pn + L.ws_off + ((int64_t)s * P.G + g0) * L.Bp;
+  float2* o1 = o0 + L.Bp;  // written only if has1
   const int32_t* bins = P.bins + L.bin_off;
   const float* wts = P.weights + L.bin_off;
   const uint16_t* fold = P.fold + L.bin_off;
-  const float2* __restrict__ chirp = P.chirp;    // c[a], a < M
+  const float2* __restrict__ chirp = P.chirp;    // c[a], a < Qc
   const float2* __restrict__ Hd = P.chirpH;      // transform of h / N, digit-reversed positions
   const float gain = 0.5f * 1.44269504088896341f * scale * P.gain / (float)M;  // log2 units; 0.5: bin + mirror
+  const float inv_Mf = 1.0f / (float)M;
 
   for (int m = tid; m <= (N >> 3); m += kFftThreads) tab[m] = cis((uint32_t)m, (uint32_t)N);
-  for (int e = tid; e < N + (N >> 5); e += kFftThreads) buf[e] = make_float2(0.f, 0.f);
 
   // Exact tokens open the softmax (raw scores q . k_e from kernel A), as in the power-of-two kernel.
   float2 mx = make_float2(-INFINITY, -INFINITY), Z = make_float2(0.f, 0.f);
@@ -1081,84 +1087,119 @@ __global__ __launch_bounds__(kFftThreads, 2) void attn_chirp_kernel(Params P, co
     }
     Z = block_sum2(ls, scratch, tid);
   }
-  __syncthreads();
 
-  // Hermitian spectrum of both heads (head g0 real, head g0 + 1 imaginary in time), times the chirp.  A slot can
-  // receive the direct term of bin k and the mirror term of bin M - k: successive rounds (host-made schedule).
-  for (int round = 0; round < L.fold_rounds; ++round) {
+  for (uint32_t b = 0; b < Pb; ++b) {
+    // block twiddle e^{j 2 pi k b / M} through the hardware sine / cosine (the phase k b mod M is reduced exactly,
+    // its quotient by M is rounded once: ~1e-7 revolutions)
+    auto block_tw = [&](uint32_t k) {
+      if (Pb == 1) return make_float2(1.f, 0.f);
+      const float ph = (float)mulmod(k, b, M, P.Mmask) * inv_Mf;
+      return make_float2(__builtin_amdgcn_cosf(ph), __builtin_amdgcn_sinf(ph));
+    };
+    for (int e = tid; e < N + (N >> 5); e += kFftThreads) buf[e] = make_float2(0.f, 0.f);
+    __syncthreads();
+    // Hermitian spectrum of both heads (head g0 real, head g0 + 1 imaginary in time), folded modulo Qc, times the
+    // chirp.  A slot can receive several terms: successive rounds (host-made schedule).
+    for (int round = 0; round < L.fold_rounds; ++round) {
+      for (int i = tid; i < L.nb; i += kFftThreads) {
+        const uint32_t fr = fold[i];
+        const bool direct = (fr & 0xffu) == (uint32_t)round, mirror = (fr >> 8) == (uint32_t)round;
+        if (!direct && !mirror) continue;
+        const uint32_t k = (uint32_t)bins[i];
+        const float w = wts[i] * gain;
+        const float2 y0 = q0[i], y1 = q1[i];
+        const float2 tw = block_tw(k);
+        const float2 z0 = cmul(make_float2(y0.x * w, y0.y * w), tw);
+        const float2 z1 = has1 ? cmul(make_float2(y1.x * w, y1.y * w), tw) : make_float2(0.f, 0.f);
+        const uint32_t r = k % Qc, rm = r ? Qc - r : 0u;
+        if (direct) {  //      z0  + j z1
+          float2 v = make_float2(z0.x - z1.y, z0.y + z1.x);
+          if (r == rm) v = make_float2(2.f * z0.x, 2.f * z1.x);  // ... plus the mirror term, same slot
+          v = cmul(v, chirp[r]);
+          if (round) v = cadd(v, buf[pad(r)]);
+          buf[pad(r)] = v;
+        }
+        if (mirror) {  // conj z0  + j conj z1
+          float2 v = cmul(make_float2(z0.x + z1.y, z1.x - z0.y), chirp[rm]);
+          if (round) v = cadd(v, buf[pad(rm)]);
+          buf[pad(rm)] = v;
+        }
+      }
+      __syncthreads();
+    }
+    ifft_dif<LOGN>(buf, tab, tid);
+    for (int p = tid; p < N; p += kFftThreads) buf[pad(p)] = cmul(buf[pad(p)], Hd[p]);
+    __syncthreads();
+    fft_dit<LOGN>(buf, tab, tid);
+
+    // scores of slot a < Qc of this block: real part head g0, imaginary part head g0 + 1
+    float2 lm = make_float2(-INFINITY, -INFINITY);
+    for (uint32_t a = tid; a < Qc; a += kFftThreads) {
+      const float2 z = cmul(buf[pad(a)], chirp[a]);
+      buf[pad(a)] = z;
+      lm.x = fmaxf(lm.x, z.x);
+      lm.y = fmaxf(lm.y, z.y);
+    }
+    const float2 bm = block_max2(lm, scratch, tid);
+    const float2 mn = make_float2(fmaxf(mx.x, bm.x), fmaxf(mx.y, bm.y));
+    const float2 f = make_float2(__builtin_amdgcn_exp2f(mx.x - mn.x), __builtin_amdgcn_exp2f(mx.y - mn.y));
+    mx = mn;
+    float2 ls = make_float2(0.f, 0.f);
+    for (uint32_t a = tid; a < (uint32_t)N; a += kFftThreads) {
+      float2 v = make_float2(0.f, 0.f);
+      if (a < Qc) {
+        const float2 z = buf[pad(a)];
+        const float2 p = make_float2(__builtin_amdgcn_exp2f(z.x - mn.x), has1 ? __builtin_amdgcn_exp2f(z.y - mn.y) : 0.f);
+        ls.x += p.x;
+        ls.y += p.y;
+        v = cmul(p, conjf2(chirp[a]));
+      }
+      buf[pad(a)] = v;
+    }
+    const float2 bs = block_sum2(ls, scratch, tid);  // its barrier also publishes the writes above
+    Z = make_float2(Z.x * f.x + bs.x, Z.y * f.y + bs.y);
+    ifft_dif<LOGN>(buf, tab, tid);
+    for (int p = tid; p < N; p += kFftThreads) buf[pad(p)] = cmul(buf[pad(p)], conjf2(Hd[p]));
+    __syncthreads();
+    fft_dit<LOGN>(buf, tab, tid);
+
     for (int i = tid; i < L.nb; i += kFftThreads) {
-      const uint32_t k = (uint32_t)bins[i], fr = fold[i];
-      const float w = wts[i] * gain;
-      const float2 y0 = q0[i], y1 = q1[i];
-      const float2 z0 = make_float2(y0.x * w, y0.y * w);
-      const float2 z1 = has1 ? make_float2(y1.x * w, y1.y * w) : make_float2(0.f, 0.f);
-      const uint32_t r = k, rm = k ? M - k : 0u;
-      if ((fr & 0xffu) == (uint32_t)round) {  //      z0  + j z1
-        float2 v = make_float2(z0.x - z1.y, z0.y + z1.x);
-        if (r == rm) v = make_float2(2.f * z0.x, 2.f * z1.x);  // ... plus the mirror term, same slot
-        v = cmul(v, chirp[r]);
-        if (round) v = cadd(v, buf[pad(r)]);
-        buf[pad(r)] = v;
+      const uint32_t k = (uint32_t)bins[i];
+      const uint32_t r = k % Qc, rm = r ? Qc - r : 0u;
+      const float2 w1 = cmul(buf[pad(r)], conjf2(chirp[r])), w2 = cmul(buf[pad(rm)], conjf2(chirp[rm]));
+      float2 p0 = make_float2(0.5f * (w1.x + w2.x), 0.5f * (w1.y - w2.y));
+      float2 p1 = make_float2(0.5f * (w1.y + w2.y), 0.5f * (w2.x - w1.x));
+      if (Pb > 1) {
+        const float2 twc = conjf2(block_tw(k));
+        p0 = cmul(twc, p0);
+        p1 = cmul(twc, p1);
+        if (b) {  // this thread's own running sums, scaled to the new maximum
+          const float2 a0 = o0[i];
+          p0 = make_float2(a0.x * f.x + p0.x, a0.y * f.x + p0.y);
+          if (has1) {
+            const float2 a1 = o1[i];
+            p1 = make_float2(a1.x * f.y + p1.x, a1.y * f.y + p1.y);
+          }
+        }
       }
-      if ((fr >> 8) == (uint32_t)round) {     // conj z0  + j conj z1
-        float2 v = cmul(make_float2(z0.x + z1.y, z1.x - z0.y), chirp[rm]);
-        if (round) v = cadd(v, buf[pad(rm)]);
-        buf[pad(rm)] = v;
-      }
+      o0[i] = p0;
+      if (has1) o1[i] = p1;
     }
     __syncthreads();
   }
-  ifft_dif<LOGN>(buf, tab, tid);
-  for (int p = tid; p < N; p += kFftThreads) buf[pad(p)] = cmul(buf[pad(p)], Hd[p]);
-  __syncthreads();
-  fft_dit<LOGN>(buf, tab, tid);
 
-  // scores of slot a < M: real part head g0, imaginary part head g0 + 1
-  float2 lm = make_float2(-INFINITY, -INFINITY);
-  for (uint32_t a = tid; a < M; a += kFftThreads) {
-    const float2 z = cmul(buf[pad(a)], chirp[a]);
-    buf[pad(a)] = z;
-    lm.x = fmaxf(lm.x, z.x);
-    lm.y = fmaxf(lm.y, z.y);
-  }
-  const float2 bm = block_max2(lm, scratch, tid);
-  const float2 mn = make_float2(fmaxf(mx.x, bm.x), fmaxf(mx.y, bm.y));
-  const float2 f = make_float2(__builtin_amdgcn_exp2f(mx.x - mn.x), __builtin_amdgcn_exp2f(mx.y - mn.y));
-  mx = mn;
-  float2 ls = make_float2(0.f, 0.f);
-  for (uint32_t a = tid; a < (uint32_t)N; a += kFftThreads) {
-    float2 v = make_float2(0.f, 0.f);
-    if (a < M) {
-      const float2 z = buf[pad(a)];
-      const float2 p = make_float2(__builtin_amdgcn_exp2f(z.x - mn.x), has1 ? __builtin_amdgcn_exp2f(z.y - mn.y) : 0.f);
-      ls.x += p.x;
-      ls.y += p.y;
-      v = cmul(p, conjf2(chirp[a]));
-    }
-    buf[pad(a)] = v;
-  }
-  const float2 bs = block_sum2(ls, scratch, tid);  // its barrier also publishes the writes above
-  Z = make_float2(Z.x * f.x + bs.x, Z.y * f.y + bs.y);
-  ifft_dif<LOGN>(buf, tab, tid);
-  for (int p = tid; p < N; p += kFftThreads) buf[pad(p)] = cmul(buf[pad(p)], conjf2(Hd[p]));
-  __syncthreads();
-  fft_dit<LOGN>(buf, tab, tid);
-
-  float2* o0 = Pn + L.ws_off + ((int64_t)s * P.G + g0) * L.Bp;
-  float2* o1 = o0 + L.Bp;
   const float inv_M = P.gain / (float)M;
   const float iz0 = inv_M / Z.x, iz1 = has1 ? inv_M / Z.y : 0.f;
-  for (int i = tid; i < L.Bp; i += kFftThreads) {
+  for (int i = tid; i < L.Bp; i += kFftThreads) {  // padding entries are written as zeros: kernel C reads whole rows
     float2 r0 = make_float2(0.f, 0.f), r1 = r0;
     if (i < L.nb) {
-      const uint32_t k = (uint32_t)bins[i];
-      const uint32_t r = k, rm = k ? M - k : 0u;
-      const float2 w1 = cmul(buf[pad(r)], conjf2(chirp[r])), w2 = cmul(buf[pad(rm)], conjf2(chirp[rm]));
-      const float2 p0 = make_float2(0.5f * (w1.x + w2.x), 0.5f * (w1.y - w2.y));
-      const float2 p1 = make_float2(0.5f * (w1.y + w2.y), 0.5f * (w2.x - w1.x));
       const float w = wts[i];
-      r0 = make_float2(p0.x * (w * iz0), -p0.y * (w * iz0));
-      r1 = make_float2(p1.x * (w * iz1), -p1.y * (w * iz1));
+      const float2 a0 = o0[i];
+      r0 = make_float2(a0.x * (w * iz0), -a0.y * (w * iz0));
+      if (has1) {
+        const float2 a1 = o1[i];
+        r1 = make_float2(a1.x * (w * iz1), -a1.y * (w * iz1));
+      }
     }
     o0[i] = r0;
     if (has1) o1[i] = r1;

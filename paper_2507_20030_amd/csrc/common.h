@@ -43,12 +43,14 @@ struct Params {
   const float* weights;
   const uint16_t* fold;  // per kept bin: low byte = round of its direct slot, high byte = round of its mirror slot
                          // (0xff: the mirror falls on the direct slot and is added in the same write)
-  // Chirp-z attention (any M up to 8192 when the power-of-two transforms do not apply; null otherwise):
-  // chirp[a] = exp(+j pi a^2 / M), a < M; chirpH: 2^chirp_logN entries, the transform of the conjugate chirp
-  // divided by its length, in the digit-reversed order of the in-LDS transform.
+  // Chirp-z attention (M that is not a power of two; null otherwise): transforms of chirp_Q = M / Pb points, Pb the
+  // smallest divisor of M with M / Pb <= 8192 (1 for M <= 8192).  chirp[a] = exp(+j pi a^2 / chirp_Q), a < chirp_Q;
+  // chirpH: 2^chirp_logN entries, the transform of the conjugate chirp divided by its length, in the digit-reversed
+  // order of the in-LDS transform.
   const float2* chirp;
   const float2* chirpH;
   int32_t chirp_logN;
+  uint32_t chirp_Q;
   // Twiddle octant of the in-LDS power-of-two transforms: tw8[m] = exp(+j 2 pi m / Q), m = 0 .. Q/8, with
   // Q = min(M, 8192); made on the host in double precision (null unless M = 2^m >= 256).
   const float2* tw8;

@@ -729,6 +729,42 @@ def test_any_length_attention_through_chirp_transforms(dtype, L, S, R, group, n_
     d.close()
 
 
+@pytest.mark.parametrize("L,S,R,group,n_bins,dtype", [
+    (16324, 10, 50, 4, 1600, "bf16"),    # 16384 - 60 = 2 * 8162: the paper's windows cut out of a 16K context
+    (32708, 10, 50, 2, 3000, "f32"),     # 32768 - 60 = 4 * 8177
+    (24570, 0, 0, 3, 5000, "bf16"),      # 3 * 8190, more than 4096 bins, a last head pair with one head
+    (8198, 0, 3, 1, 700, "f32"),         # 2 * 4099 (a prime block length), one query head
+])
+def test_long_contexts_that_are_not_a_power_of_two_through_decimated_chirp_transforms(L, S, R, group, n_bins, dtype):
+    """M > 8192 that is not a power of two: Pb = M / Q decimated blocks of Q <= 8192 points, each through the chirp-z
+    transforms, softmax online across the blocks.  Every step against the oracle (two calls and fused), and against the
+    direct sums of the same library."""
+    cfg = small_cfg(L=L, n_bins=n_bins, group=group, dtype=dtype, steps=3, n_layers=1, batch=1, n_sink=S, n_recent=R)
+    bins = random_bins(cfg, 29)
+    c = make_cache(cfg, bins)
+    assert B.iwdft_attn_kind(c.ctx) == "chirp"
+    c.close()
+    run_stream(cfg, bins, tag=f"chirp-{L}", rec=(0, 64))
+    run_stream(cfg, bins, tag=f"chirp-{L}-fused", fused=True, rec=(0, 64))
+    K, V = wl.prefill_tensors(cfg, DEV)
+    a, d = make_cache(cfg, bins), make_cache(cfg, bins, flags=B.IWDFT_FLAG_DIRECT_SYNTHESIS)
+    a.prefill(K, V)
+    d.prefill(K, V)
+    _, _, q = wl.decode_step(cfg, 0, DEV)
+    assert rel_l2(f64(a.attend(q)), f64(d.attend(q))) < (2e-5 if dtype == "f32" else 8e-3)
+    a.close()
+    d.close()
+
+
+def test_long_prime_context_takes_the_direct_sums():
+    cfg = small_cfg(L=10007, n_bins=300, group=2, dtype="f32", steps=2, n_layers=1, batch=1)
+    bins = random_bins(cfg, 5)
+    c = make_cache(cfg, bins)
+    assert B.iwdft_attn_kind(c.ctx) == "direct"
+    c.close()
+    run_stream(cfg, bins, tag="direct-10007", rec=(0, 64))
+
+
 def test_paper_windows_on_a_context_that_is_a_power_of_two_full_size():
     """cfg2's shape with the paper's windows cut out of an 8192-token context (Sec. 5.1: 10 sink + 50 recent tokens,
     M = 8192 - 60 = 8132): the realistic setting, chirp-z attention at full size."""
