@@ -84,7 +84,7 @@ def main():
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on ONE GPU; --gpus N with N > 1 is not supported "
-                 "(every slice is independent; see DESIGN.md for how the path would shard)")
+                 "(every slice is independent, so the path would shard over layers, sequences or KV heads without any exchange)")
 
     import numpy as np
     import torch
