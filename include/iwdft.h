@@ -148,7 +148,8 @@ int iwdft_prefill_kind(const iwdft_ctx* ctx);
  * other M >= 32 that is at most 8192 or has a divisor Pb <= 256 with 32 <= M / Pb <= 8192, e.g. M = context - sink -
  * recent = 16384 - 60 = 2 * 8162: O(M log M) as well, about 8 times the arithmetic of 1); 0 = the direct O(M |B|)
  * sums (arithmetic-bound; chosen by IWDFT_FLAG_DIRECT_SYNTHESIS, for M < 32, and for M > 8192 without such a divisor,
- * e.g. a prime); -1 if ctx is NULL.
+ * e.g. a prime -- there only while M * (most kept bins of a layer) <= 2^30, beyond that iwdft_query_bytes /
+ * iwdft_create return IWDFT_ERR_UNSUPPORTED unless the flag insists); -1 if ctx is NULL.
  * With 0 or 2, or when some layer keeps more than 4096 bins, desc.write_every is taken as 1. */
 int iwdft_attn_kind(const iwdft_ctx* ctx);
 

@@ -66,6 +66,7 @@ constexpr uint32_t kFftMinM = 256;
 constexpr int64_t kFftMaxQ = 8192;  // longest transform the FFT attention kernel holds in LDS
 constexpr int64_t kChirpMinM = 32, kChirpMaxM = 8192;  // chirp-z transforms: 2 Q - 1 <= 16384 points fit in LDS
 constexpr int64_t kChirpMaxBlocks = 256;  // most decimated blocks M / Q of the chirp-z attention
+constexpr uint64_t kDirectMaxTerms = 1ull << 30;  // most M * |B| the direct sums are chosen for without being asked
 
 int make_plan(const iwdft_desc* d, Plan* pl) {
   if (!d) return fail(IWDFT_ERR_ARG, "desc is NULL");
@@ -191,6 +192,16 @@ int make_plan(const iwdft_desc* d, Plan* pl) {
       L.fold_rounds = rounds;
     }
   }
+
+  // What is left takes the direct O(M |B|) sums: fine for short or sparse states, useless beyond -- refuse instead of
+  // running for minutes per step (a prime M of 2^20 with 4096 kept bins is 2^32 sine / cosine pairs per query head).
+  if (!pl->use_fft && !pl->use_chirp && !(d->flags & IWDFT_FLAG_DIRECT_SYNTHESIS) &&
+      (uint64_t)d->M * (uint64_t)pl->max_nb > kDirectMaxTerms)
+    return fail(IWDFT_ERR_UNSUPPORTED,
+                "M = %lld with %d kept bins in a layer has no O(M log M) decode attention (M is neither a power of two nor "
+                "has a divisor Pb <= %d with 32 <= M / Pb <= %d) and is too large for the direct sums; pick M with such a "
+                "divisor (e.g. move tokens to the sink / recent windows) or pass IWDFT_FLAG_DIRECT_SYNTHESIS to insist",
+                (long long)d->M, pl->max_nb, (int)kChirpMaxBlocks, (int)kChirpMaxM);
 
   size_t o = 0;
   pl->off_layers = o;  o = align256(o + sizeof(LayerInfo) * (size_t)d->n_layers);

@@ -58,6 +58,8 @@ def test_query_bytes_accounts_for_padded_rows():
     (dict(n_sink=-1), B.IWDFT_ERR_ARG),
     (dict(n_recent=-3), B.IWDFT_ERR_ARG),
     (dict(n_sink=1000, n_recent=25), B.IWDFT_ERR_UNSUPPORTED),
+    # a long prime M: no O(M log M) attention, too many terms for the direct sums chosen unasked
+    (dict(M=1048583, bins=[np.arange(2048), np.arange(8)]), B.IWDFT_ERR_UNSUPPORTED),
     (dict(bins=[np.arange(8), np.array([0, 3, 3, 9])]), B.IWDFT_ERR_BINS),
     (dict(bins=[np.arange(8), np.array([5, 3])]), B.IWDFT_ERR_BINS),
     (dict(bins=[np.arange(8), np.array([0, 64])]), B.IWDFT_ERR_BINS),
@@ -129,3 +131,12 @@ def test_static_scratch_symbol_is_visible_to_the_hip_runtime(tmp_path):
     rows = [ln.split() for ln in syms.splitlines() if ln.strip().endswith("scratch")]
     assert rows, "no scratch symbol in the device code object"
     assert all(r[4] == "GLOBAL" and int(r[2]) == B.IWDFT_STATIC_SCRATCH_BYTES for r in rows), rows
+
+
+def test_plan_accepts_long_contexts_with_a_small_divisor_and_the_direct_sums_on_request():
+    # 2^20 - 64 = 129 * 8128: 129 decimated blocks of 8128 points (chirp-z); a long prime is accepted when the caller
+    # insists on the direct sums
+    big = [np.arange(2048), np.arange(8)]
+    assert B.iwdft_query_bytes(desc(M=(1 << 20) - 64 * 1, bins=big))[0] > 0
+    assert B.iwdft_query_bytes(desc(M=1048583, bins=big, flags=B.IWDFT_FLAG_DIRECT_SYNTHESIS))[0] > 0
+    assert B.iwdft_query_bytes(desc(M=10007, bins=big))[0] > 0      # 10007 * 2048 terms: the direct sums are fine
