@@ -837,3 +837,27 @@ def test_fft_and_dense_prefill_give_the_same_state():
         assert rel_l2(c128(ka), c128(kb)) < 1e-5 and rel_l2(c128(va), c128(vb)) < 1e-5
     a.close()
     b.close()
+
+
+@pytest.mark.parametrize("L,n_bins", [(1024, 400), (16384, 1100), (32768, 2100), (8192, 5000)])
+def test_fft_prefill_of_tensors_that_are_not_16_byte_aligned(L, n_bins):
+    """The FFT prefill fetches several channel pairs with one 8- or 16-byte load when K and V allow it; tensors that
+    start 8 bytes off take one pair per workgroup instead.  Every pair's transform is the same arithmetic either way:
+    the two states agree bit for bit."""
+    cfg = small_cfg(L=L, n_bins=n_bins, n_layers=1, batch=1, n_kv_heads=2, dtype="bf16", mask="low")
+    bins = wl.layer_bins(cfg)
+    K, V = wl.prefill_tensors(cfg, DEV)
+    pad = 4                                                    # bf16 elements = 8 bytes
+    Ku = torch.empty(K.numel() + pad, dtype=K.dtype, device=DEV)[pad:].view_as(K)
+    Vu = torch.empty(V.numel() + pad, dtype=V.dtype, device=DEV)[pad:].view_as(V)
+    Ku.copy_(K)
+    Vu.copy_(V)
+    assert K.data_ptr() % 16 == 0 and Ku.data_ptr() % 16 == 8 and Vu.data_ptr() % 16 == 8
+    a = make_cache(cfg, bins, flags=B.IWDFT_FLAG_FFT_PREFILL)
+    b = make_cache(cfg, bins, flags=B.IWDFT_FLAG_FFT_PREFILL)
+    a.prefill(K, V)
+    b.prefill(Ku, Vu)
+    (ka, va), (kb, vb) = a.export_coeffs(0), b.export_coeffs(0)
+    assert torch.equal(ka, kb) and torch.equal(va, vb)
+    a.close()
+    b.close()
