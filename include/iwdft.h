@@ -26,6 +26,9 @@
  * (a hipStream_t passed as void*, NULL = default stream) and never synchronise;
  * T advances when the call is enqueued.  Calls on one context from several host
  * threads, or on different streams without caller-side ordering, race.
+ * Alignment: token, query, attention-output and prefill tensors must be 16-byte
+ * aligned (IWDFT_ERR_ARG otherwise); the FFT prefill of a context without sink /
+ * recent windows also takes K, V aligned to one channel pair (4 bytes bf16, 8 fp32).
  *
  * Errors: every call returns IWDFT_OK or a negative code, validates all
  * arguments before launching anything, and never throws or aborts.

@@ -35,6 +35,9 @@ int fail(int code, const char* fmt, ...) {
 }
 
 size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
+// Token, query and output tensors are read and written with 16-byte accesses.
+bool misaligned16(const void* p) { return ((uintptr_t)p & 15u) != 0; }
+const char kAlignMsg[] = "a device tensor is not 16-byte aligned";
 
 struct Plan {  // byte offsets inside the two caller buffers, derived from a descriptor
   std::vector<LayerInfo> layers;
@@ -577,6 +580,13 @@ int iwdft_prefill(iwdft_ctx* ctx, const void* d_K, const void* d_V, void* hip_st
   int rc = check_ctx(ctx);
   if (rc != IWDFT_OK) return rc;
   if (!d_K || !d_V) return fail(IWDFT_ERR_ARG, "d_K / d_V is NULL");
+  {
+    // the FFT prefill without sink / recent windows falls back to narrower loads; it still needs whole channel pairs
+    const bool narrow_ok = ctx->plan.use_fft_prefill && ctx->desc.n_sink == 0 && ctx->desc.n_recent == 0;
+    const uintptr_t mask = narrow_ok ? (ctx->desc.kv_dtype == IWDFT_BF16 ? 3u : 7u) : 15u;
+    if ((((uintptr_t)d_K | (uintptr_t)d_V) & mask) != 0)
+      return fail(IWDFT_ERR_ARG, "d_K / d_V must be %u-byte aligned for this prefill", (unsigned)mask + 1);
+  }
   ctx->pend = 0;  // the prefill overwrites the whole state
   rc = launched(ctx->plan.use_fft_prefill ? launch_prefill_fft(ctx->P, d_K, d_V, (hipStream_t)hip_stream)
                                           : launch_prefill(ctx->P, d_K, d_V, (hipStream_t)hip_stream),
@@ -590,6 +600,7 @@ int iwdft_append(iwdft_ctx* ctx, const void* d_tok_k, const void* d_tok_v, void*
   int rc = check_ctx(ctx);
   if (rc != IWDFT_OK) return rc;
   if (!d_tok_k || !d_tok_v) return fail(IWDFT_ERR_ARG, "d_tok_k / d_tok_v is NULL");
+  if (misaligned16(d_tok_k) || misaligned16(d_tok_v)) return fail(IWDFT_ERR_ARG, kAlignMsg);
   if (ctx->T < ctx->desc.M) return fail(IWDFT_ERR_STATE, "iwdft_append before iwdft_prefill");
   if ((rc = flush_pending(ctx, (hipStream_t)hip_stream)) != IWDFT_OK) return rc;
   // The recent ring was filled oldest-first at prefill, so after T - M appends the oldest token
@@ -658,6 +669,7 @@ int compressed_decode_attn(iwdft_ctx* ctx, const void* d_q, void* d_out, float s
   int rc = check_ctx(ctx);
   if (rc != IWDFT_OK) return rc;
   if (!d_q || !d_out) return fail(IWDFT_ERR_ARG, "d_q / d_out is NULL");
+  if (misaligned16(d_q) || misaligned16(d_out)) return fail(IWDFT_ERR_ARG, kAlignMsg);
   if (ctx->T < ctx->desc.M) return fail(IWDFT_ERR_STATE, "compressed_decode_attn before iwdft_prefill");
   if (!std::isfinite(scale)) return fail(IWDFT_ERR_ARG, "scale is not finite");
   if (scale <= 0.0f) scale = 1.0f / std::sqrt((float)ctx->desc.head_dim);
@@ -677,6 +689,7 @@ int compressed_decode_attn_static(iwdft_ctx* ctx, const void* d_q, void* d_out, 
   int rc = check_ctx(ctx);
   if (rc != IWDFT_OK) return rc;
   if (!d_q || !d_out) return fail(IWDFT_ERR_ARG, "d_q / d_out is NULL");
+  if (misaligned16(d_q) || misaligned16(d_out)) return fail(IWDFT_ERR_ARG, kAlignMsg);
   if (ctx->T < ctx->desc.M) return fail(IWDFT_ERR_STATE, "compressed_decode_attn_static before iwdft_prefill");
   if (!std::isfinite(scale)) return fail(IWDFT_ERR_ARG, "scale is not finite");
   if (scale <= 0.0f) scale = 1.0f / std::sqrt((float)ctx->desc.head_dim);
@@ -706,6 +719,8 @@ int iwdft_append_attn(iwdft_ctx* ctx, const void* d_tok_k, const void* d_tok_v, 
   int rc = check_ctx(ctx);
   if (rc != IWDFT_OK) return rc;
   if (!d_tok_k || !d_tok_v || !d_q || !d_out) return fail(IWDFT_ERR_ARG, "a token / query / output pointer is NULL");
+  if (misaligned16(d_tok_k) || misaligned16(d_tok_v) || misaligned16(d_q) || misaligned16(d_out))
+    return fail(IWDFT_ERR_ARG, kAlignMsg);
   if (ctx->T < ctx->desc.M) return fail(IWDFT_ERR_STATE, "iwdft_append_attn before iwdft_prefill");
   if (!std::isfinite(scale)) return fail(IWDFT_ERR_ARG, "scale is not finite");
   if (scale <= 0.0f) scale = 1.0f / std::sqrt((float)ctx->desc.head_dim);

@@ -861,3 +861,37 @@ def test_fft_prefill_of_tensors_that_are_not_16_byte_aligned(L, n_bins):
     assert torch.equal(ka, kb) and torch.equal(va, vb)
     a.close()
     b.close()
+
+
+def test_misaligned_tensors_are_refused_before_any_launch():
+    """Token, query, output and prefill tensors are accessed 16 bytes at a time: a tensor that starts elsewhere is an
+    IWDFT_ERR_ARG (only the FFT prefill without windows takes K, V aligned to a channel pair, tested above)."""
+    def off(t, pad=4):
+        u = torch.empty(t.numel() + pad, dtype=t.dtype, device=DEV)[pad:].view_as(t)
+        u.copy_(t)
+        return u
+
+    for S, R, flags in ((0, 0, B.IWDFT_FLAG_DENSE_PREFILL), (2, 3, B.IWDFT_FLAG_FFT_PREFILL)):
+        cfg = small_cfg(L=1024, n_bins=400, n_layers=1, batch=1, n_kv_heads=2, dtype="bf16", n_sink=S, n_recent=R)
+        bins = wl.layer_bins(cfg)
+        K, V = wl.prefill_tensors(cfg, DEV)
+        c = make_cache(cfg, bins, flags=flags)
+        for args in ((off(K), V), (K, off(V))):
+            with pytest.raises(B.IwdftError) as e:
+                c.prefill(*args)
+            assert e.value.code == B.IWDFT_ERR_ARG
+        c.prefill(K, V)
+        tk, tv, q = wl.decode_step(cfg, 0, DEV)
+        out = torch.empty_like(q)
+        for call in (lambda: c.append(off(tk), tv), lambda: c.append(tk, off(tv)), lambda: c.attend(off(q), out),
+                     lambda: c.attend(q, off(out)), lambda: c.step(off(tk), tv, q, out), lambda: c.step(tk, tv, off(q), out),
+                     lambda: c.step(tk, tv, q, off(out))):
+            with pytest.raises(B.IwdftError) as e:
+                call()
+            assert e.value.code == B.IWDFT_ERR_ARG
+        assert c.T == cfg.L                      # nothing was absorbed by the refused calls
+        c.append(tk, tv)
+        c.attend(q, out)
+        torch.cuda.synchronize()
+        assert bool(torch.isfinite(out.float()).all())
+        c.close()
