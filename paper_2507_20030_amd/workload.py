@@ -61,6 +61,11 @@ CONFIGS = {
     "cfg2w": Config("cfg2w", 32, 1, 8, 4, 128, 8192, 2048, 256, "bf16", "low", n_sink=10, n_recent=50),
     # the same windows cut OUT of an 8192-token context: M = 8192 - 60 = 8132 is not a power of two (25 % of the bins)
     "cfg2x": Config("cfg2x", 32, 1, 8, 4, 128, 8132, 2033, 256, "bf16", "low", n_sink=10, n_recent=50),
+    # cfg3's shape keeping 25 % of the bins (the paper's largest ratio, Sec. 5.1): 8192 per layer, beyond the 4096 the
+    # register-resident FFT kernels take
+    "cfg3b": Config("cfg3b", 32, 8, 8, 4, 128, 32768, 8192, 512, "bf16", "mixed"),
+    # cfg3's shape with the paper's windows cut out of a 32768-token context: M = 32708 = 4 x 8177
+    "cfg3x": Config("cfg3x", 32, 8, 8, 4, 128, 32708, 4088, 512, "bf16", "mixed", n_sink=10, n_recent=50),
 }
 
 

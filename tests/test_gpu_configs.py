@@ -215,3 +215,28 @@ def test_pipelined_and_serial_phases_agree_bit_for_bit(group, n_bins, shape, dty
     assert torch.equal(a.state, b.state), "final state differs"
     a.close()
     b.close()
+
+
+def test_cfg3_shape_with_8192_kept_bins_full_size():
+    """A quarter of the bins of a 32768-token context (the paper's largest ratio) at cfg3's full shape: bin-strided FFT
+    prefill and decode attention, two calls and the fused step, on sampled slices against the oracle."""
+    cfg = wl.CONFIGS["cfg3b"]
+    bins = wl.layer_bins(cfg)
+    c = make_cache(cfg, bins)
+    assert B.iwdft_prefill_kind(c.ctx) == "fft" and B.iwdft_attn_kind(c.ctx) == "fft" and not B.iwdft_attn_pipelined(c.ctx)
+    c.close()
+    run_stream(cfg, bins, steps=2, slices=wl.sample_slices(cfg, 6), tag="cfg3b")
+    run_stream(cfg, bins, steps=2, slices=wl.sample_slices(cfg, 4), fused=True, tag="cfg3b-fused")
+
+
+def test_cfg3_shape_with_the_papers_windows_cut_out_of_the_context_full_size():
+    """M = 32768 - 60 = 4 x 8177 at cfg3's full shape: dense prefill, decode attention through four decimated chirp-z
+    blocks per pair of query heads, on sampled slices against the oracle."""
+    cfg = wl.CONFIGS["cfg3x"]
+    assert cfg.n_prefill == 32768
+    bins = wl.layer_bins(cfg)
+    c = make_cache(cfg, bins)
+    assert B.iwdft_prefill_kind(c.ctx) == "dense" and B.iwdft_attn_kind(c.ctx) == "chirp"
+    c.close()
+    run_stream(cfg, bins, steps=2, slices=wl.sample_slices(cfg, 6), tag="cfg3x")
+    run_stream(cfg, bins, steps=2, slices=wl.sample_slices(cfg, 4), fused=True, tag="cfg3x-fused")
